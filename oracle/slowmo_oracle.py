@@ -1,0 +1,163 @@
+"""CPU ORACLE -- test infrastructure, not the product.
+
+Algorithm 1 (Slow Momentum) driven step by step in the paper's order:
+outer iteration t -> buffer policy (line 2) -> tau base-optimizer steps of
+every worker (lines 3-5, directions of Table C.1) -> exact average, slow
+momentum, outer iterate (lines 6-8).  The per-element arithmetic is the plain
+C in slowmo_oracle.c, built in fp64 (the reference) and fp32 (noise floor).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this module.  It shares no code with the HIP path and does not import it.
+
+Readings of the paper where it is silent or inconsistent (also listed in the
+design document): coupled L2 weight decay; Adam's bias-correction exponent
+counts the current update (starts at 1); eps is added after the square root of
+the bias-corrected second moment; the learning rate is a per-call scalar (the
+one given to the outer step is gamma_t of Eq. (2)-(3)); the mean is a
+left-to-right sum over workers 0..m-1 followed by a division by m; "reset"
+zeroes the buffers (and Adam's step counter) at the start of every outer
+iteration, "maintain" leaves them alone.
+
+Parity pins: tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "slowmo_oracle.c")
+_LIBS = {"f64": os.path.join(_HERE, "liboracle_f64.so"),
+         "f32": os.path.join(_HERE, "liboracle_f32.so")}
+_FLAGS = {"f64": ["-DREAL=double"], "f32": ["-DREAL=float", "-DORACLE_F32"]}
+_loaded: dict = {}
+
+
+def build(force: bool = False, src: str = _SRC, out: Optional[dict] = None) -> dict:
+    """Compile the C oracle with gcc (both precisions).  Plain -O2, no
+    fast-math, no FMA contraction, OpenMP over the element index only."""
+    out = out or _LIBS
+    for prec, path in out.items():
+        if not force and os.path.exists(path) and \
+                os.path.getmtime(path) >= os.path.getmtime(src):
+            continue
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+               "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+               *_FLAGS[prec], "-o", path, src, "-lm"]
+        subprocess.run(cmd, check=True)
+    return out
+
+
+def load(prec: str = "f64", path: Optional[str] = None) -> C.CDLL:
+    key = (prec, path)
+    if key in _loaded:
+        return _loaded[key]
+    if path is None:
+        build()
+        path = _LIBS[prec]
+    lib = C.CDLL(path)
+    want = 8 if prec == "f64" else 4
+    lib.oracle_real_bytes.restype = C.c_int
+    assert lib.oracle_real_bytes() == want, "oracle library has the wrong precision"
+    p, i64, dbl = C.c_void_p, C.c_int64, C.c_double
+    lib.oracle_sgd_nesterov_step.argtypes = [p, p, p, i64, dbl, dbl, dbl]
+    lib.oracle_sgd_nesterov_step.restype = None
+    lib.oracle_adam_step.argtypes = [p, p, p, p, i64, dbl, dbl, dbl, dbl, dbl, i64]
+    lib.oracle_adam_step.restype = None
+    lib.oracle_outer_step.argtypes = [p, C.c_int, i64, p, p, dbl, dbl, dbl]
+    lib.oracle_outer_step.restype = None
+    _loaded[key] = lib
+    return lib
+
+
+def _ptr(a: np.ndarray) -> C.c_void_p:
+    assert a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+class SlowMoOracle:
+    """State and control flow of Algorithm 1 for m workers over d elements.
+
+    x[i] is worker i's replica, h[i] (and v[i]) its base-optimizer buffers,
+    x0 the outer iterate x_{t,0}, u the slow momentum buffer (u_0 = 0).
+    All workers start from the same point (Section 2).
+    """
+
+    def __init__(self, x_init, m: int, tau: int, alpha: float, beta: float,
+                 base: str = "sgd_nesterov", policy: Optional[str] = None,
+                 momentum: float = 0.0, weight_decay: float = 0.0,
+                 beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                 prec: str = "f64", lib: Optional[C.CDLL] = None):
+        assert base in ("sgd_nesterov", "adam")
+        if policy is None:      # the paper's defaults (Section 4, Appendix B.4)
+            policy = "reset" if base == "sgd_nesterov" else "maintain"
+        assert policy in ("reset", "maintain")
+        assert m >= 1 and tau >= 1
+        self.lib = lib if lib is not None else load(prec)
+        self.dtype = np.float64 if prec == "f64" else np.float32
+        x_init = np.asarray(x_init)
+        self.d = int(x_init.size)
+        self.m, self.tau = int(m), int(tau)
+        self.alpha, self.beta = float(alpha), float(beta)
+        self.base, self.policy = base, policy
+        self.momentum, self.weight_decay = float(momentum), float(weight_decay)
+        self.beta1, self.beta2, self.eps = float(beta1), float(beta2), float(eps)
+        self.x0 = x_init.astype(self.dtype).reshape(self.d).copy()
+        self.x = np.tile(self.x0, (self.m, 1))
+        self.u = np.zeros(self.d, self.dtype)
+        self.h = np.zeros((self.m, self.d), self.dtype)
+        self.v = np.zeros((self.m, self.d), self.dtype) if base == "adam" else None
+        self.t = 0      # outer iteration
+        self.k = 0      # inner step within the outer iteration
+        self.l = 0      # Adam moment updates applied so far (bias-correction exponent)
+
+    # Algorithm 1 line 2
+    def _apply_buffer_policy(self) -> None:
+        if self.policy == "reset":
+            self.h[...] = 0
+            if self.v is not None:
+                self.v[...] = 0
+            self.l = 0
+        # "maintain": nothing to do
+
+    # Algorithm 1 lines 3-5: one base-optimizer step on every worker
+    def local_step(self, grads, lr: float) -> None:
+        """grads: (m, d) float32 (bf16 inputs already widened)."""
+        assert self.k < self.tau, "tau local steps already taken; outer step is due"
+        g = np.ascontiguousarray(grads, dtype=np.float32).reshape(self.m, self.d)
+        if self.k == 0:
+            self._apply_buffer_policy()
+        if self.base == "adam":
+            self.l += 1
+        for i in range(self.m):
+            if self.base == "sgd_nesterov":
+                self.lib.oracle_sgd_nesterov_step(
+                    _ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,
+                    lr, self.momentum, self.weight_decay)
+            else:
+                self.lib.oracle_adam_step(
+                    _ptr(self.x[i]), _ptr(self.h[i]), _ptr(self.v[i]), _ptr(g[i]),
+                    self.d, lr, self.beta1, self.beta2, self.eps,
+                    self.weight_decay, self.l)
+        self.k += 1
+
+    # Algorithm 1 lines 6-8 (+ copy of x_{t+1,0} into every replica)
+    def outer_step(self, lr: float) -> None:
+        assert self.k == self.tau, "outer step needs exactly tau local steps"
+        self.lib.oracle_outer_step(_ptr(self.x), self.m, self.d, _ptr(self.x0),
+                                   _ptr(self.u), lr, self.alpha, self.beta)
+        self.k = 0
+        self.t += 1
+
+    def run(self, grad_fn, lr, rounds: int) -> None:
+        """grad_fn(t, k) -> (m, d) float32; lr a float or a callable lr(t)."""
+        for _ in range(rounds):
+            t = self.t
+            g_t = lr(t) if callable(lr) else lr
+            for k in range(self.tau):
+                self.local_step(grad_fn(t, k), g_t)
+            self.outer_step(g_t)

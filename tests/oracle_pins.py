@@ -1,0 +1,424 @@
+"""Pins for the CPU oracle: facts fixed by the paper or by mathematics, none of
+which re-types the oracle's own formulas.
+
+Each pin is a function pin_*(make) where make(x_init, **kw) builds an oracle
+instance (fp64).  test_oracle_pins.py runs them on the real oracle;
+test_oracle_mutants.py runs them on deliberately broken copies of the oracle
+and requires every planted mistake to be caught by at least one pin.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+RT = 1e-12   # fp64 identities hold to a few ulp over the short runs used here
+
+
+def _rng(seed=0):
+    return np.random.default_rng(seed)
+
+
+def _close(a, b, rtol=RT, atol=1e-13, what=""):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    err = np.abs(a - b)
+    bound = atol + rtol * np.maximum(np.abs(a), np.abs(b))
+    assert np.all(err <= bound), f"{what}: max err {err.max():.3e} (bound {bound.min():.3e})"
+
+
+def _grads(rng, T, tau, m, d, scale=1.0):
+    return (scale * rng.standard_normal((T, tau, m, d))).astype(np.float32)
+
+
+# ---------------------------------------------------------------- Section 2
+
+def pin_mean_of_updates(make):
+    """Section 2, sentence after Algorithm 1: with plain SGD as base,
+    xbar_{t,tau} = x_{t,0} - (gamma/m) sum_i sum_k g^{(i)}_{t,k}."""
+    rng = _rng(1)
+    T, tau, m, d, lr = 3, 4, 3, 17, 0.05
+    g = _grads(rng, T, tau, m, d)
+    o = make(rng.standard_normal(d), m=m, tau=tau, alpha=0.8, beta=0.5)
+    for t in range(T):
+        x_t0 = o.x0.copy()
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        xbar = o.x.mean(axis=0)
+        _close(xbar, x_t0 - lr / m * g[t].astype(np.float64).sum(axis=(0, 1)),
+               what="mean of updates")
+        o.outer_step(lr)
+
+
+def pin_heavy_ball_form(make):
+    """Appendix D.1 ("Equivalent Updates"): x_{t+1,0} = x_{t,0} - alpha*gamma*
+    sum_k dbar_{t,k} + beta*(x_{t,0} - x_{t-1,0}); with plain SGD dbar is the
+    worker-mean gradient, so the right-hand side needs the inputs only."""
+    rng = _rng(2)
+    T, tau, m, d, lr, alpha, beta = 5, 4, 3, 11, 0.05, 0.75, 0.6
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=alpha, beta=beta)
+    prev, cur = x_init.copy(), x_init.copy()
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        o.outer_step(lr)
+        dsum = g[t].astype(np.float64).mean(axis=1).sum(axis=0)
+        nxt = cur - alpha * lr * dsum + beta * (cur - prev)
+        _close(o.x0, nxt, what=f"heavy-ball form, t={t}")
+        prev, cur = cur, nxt
+
+
+def pin_auxiliary_sequence(make):
+    """Appendix D.1: y_t = x_t + beta/(1-beta)*(x_t - x_{t-1}) obeys
+    y_{t+1} = y_t - alpha*gamma/(1-beta) * sum_k dbar_{t,k}, y_0 = x_0."""
+    rng = _rng(3)
+    T, tau, m, d, lr, alpha, beta = 4, 3, 2, 9, 0.1, 1.0, 0.7
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=alpha, beta=beta)
+    y = x_init.copy()
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        x_t = o.x0.copy()
+        o.outer_step(lr)
+        y = y - alpha * lr / (1 - beta) * g[t].astype(np.float64).mean(axis=1).sum(axis=0)
+        y_oracle = o.x0 + beta / (1 - beta) * (o.x0 - x_t)
+        _close(y_oracle, y, rtol=1e-11, what=f"auxiliary sequence, t={t}")
+
+
+def pin_u_closed_form_and_lr_invariance(make):
+    """Appendix D.3.3 (unrolled momentum): u_T = sum_s beta^{T-1-s} sum_k
+    dbar_{s,k}.  Section 2: dividing by gamma_t makes u independent of the
+    fast learning rate, so the same u results under any schedule gamma_t."""
+    rng = _rng(4)
+    T, tau, m, d, beta = 5, 3, 4, 13, 0.65
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    want = np.zeros(d)
+    for s in range(T):
+        want += beta ** (T - 1 - s) * g[s].astype(np.float64).mean(axis=1).sum(axis=0)
+    for sched in (lambda t: 0.1, lambda t: 0.1 / (1 + t), lambda t: 0.02 * 3 ** t):
+        o = make(x_init, m=m, tau=tau, alpha=0.9, beta=beta)
+        o.run(lambda t, k: g[t, k], sched, T)
+        # (x0 - xbar)/gamma loses digits to cancellation when gamma is small
+        _close(o.u, want, rtol=1e-9, atol=1e-9, what="u closed form")
+
+
+def pin_local_sgd_reduction(make):
+    """Section 2: alpha = 1, beta = 0 gives Local SGD, i.e. the new outer
+    iterate is the plain average of the replicas (here with the Nesterov base
+    of the experiments)."""
+    rng = _rng(5)
+    T, tau, m, d, lr = 3, 4, 5, 10, 0.1
+    g = _grads(rng, T, tau, m, d)
+    o = make(rng.standard_normal(d), m=m, tau=tau, alpha=1.0, beta=0.0,
+             momentum=0.9, weight_decay=1e-4)
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        xbar = o.x.mean(axis=0)
+        o.outer_step(lr)
+        _close(o.x0, xbar, rtol=1e-13, atol=1e-14, what="Local SGD reduction")
+
+
+def pin_lookahead_reduction(make):
+    """Section 2: m = 1, beta = 0 is Lookahead:
+    x_{t+1,0} = x_{t,0} + alpha*(x_{t,tau} - x_{t,0})."""
+    rng = _rng(6)
+    T, tau, d, lr, alpha = 3, 5, 8, 0.05, 0.5
+    g = _grads(rng, T, tau, 1, d)
+    for base in ("sgd_nesterov", "adam"):
+        kw = dict(momentum=0.9) if base == "sgd_nesterov" else dict(beta2=0.98)
+        o = make(rng.standard_normal(d), m=1, tau=tau, alpha=alpha, beta=0.0,
+                 base=base, **kw)
+        for t in range(T):
+            x_t0 = o.x0.copy()
+            for k in range(tau):
+                o.local_step(g[t, k], lr)
+            fast = o.x[0].copy()
+            o.outer_step(lr)
+            _close(o.x0, x_t0 + alpha * (fast - x_t0), rtol=1e-13, atol=1e-14,
+                   what="Lookahead reduction")
+
+
+def pin_replica_consensus(make):
+    """Section 2: after lines 6-8 the iterate is identical on all workers."""
+    rng = _rng(7)
+    T, tau, m, d, lr = 2, 3, 4, 6, 0.1
+    g = _grads(rng, T, tau, m, d)
+    o = make(rng.standard_normal(d), m=m, tau=tau, alpha=0.7, beta=0.4, momentum=0.9)
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        assert not np.array_equal(o.x[0], o.x[1])
+        o.outer_step(lr)
+        for i in range(m):
+            assert np.array_equal(o.x[i], o.x0), "replicas differ after the outer step"
+
+
+def pin_large_minibatch_momentum_sgd(make):
+    """Section 2: base SGD, tau = 1, alpha = 1 is large-minibatch SGD with
+    learning rate gamma and momentum beta -- checked against the library's
+    heavy-ball SGD on the worker-mean gradient."""
+    rng = _rng(8)
+    T, m, d, lr, beta = 12, 4, 10, 0.05, 0.8
+    g = _grads(rng, T, 1, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=1, alpha=1.0, beta=beta)
+    p = torch.tensor(x_init, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=beta, dampening=0.0)
+    for t in range(T):
+        o.local_step(g[t, 0], lr)
+        o.outer_step(lr)
+        p.grad = torch.tensor(g[t, 0].astype(np.float64).mean(axis=0))
+        opt.step()
+        _close(o.x0, p.detach().numpy(), rtol=1e-11, atol=1e-12,
+               what=f"momentum SGD reduction, t={t}")
+
+
+# ------------------------------------------------- Table C.1, SGD (Nesterov)
+
+def _torch_sgd_per_worker(x_init, g, lr, mu, wd, reset_every=None):
+    """Library Nesterov SGD on one worker's gradient sequence g[step, d]."""
+    p = torch.tensor(np.asarray(x_init, dtype=np.float64), requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, nesterov=True, weight_decay=wd)
+    for s in range(g.shape[0]):
+        if reset_every and s % reset_every == 0:
+            opt.state.clear()
+        p.grad = torch.tensor(g[s].astype(np.float64))
+        opt.step()
+    return p.detach().numpy()
+
+
+def pin_nesterov_base_vs_library(make):
+    """Section 2: m = 1, alpha = 1, beta = 0 leaves the bare base optimizer.
+    Table C.1's SGD row is the library's Nesterov SGD (no dampening, coupled
+    weight decay); under "reset" the library's momentum buffer is dropped
+    every tau steps, under "maintain" it is kept."""
+    rng = _rng(9)
+    T, tau, d, lr, mu, wd = 3, 4, 12, 0.1, 0.9, 1e-2
+    g = _grads(rng, T, tau, 1, d)
+    x_init = rng.standard_normal(d)
+    seq = g.reshape(T * tau, d)
+    for policy in ("reset", "maintain"):
+        o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, momentum=mu,
+                 weight_decay=wd, policy=policy)
+        o.run(lambda t, k: g[t, k], lr, T)
+        want = _torch_sgd_per_worker(x_init, seq, lr, mu, wd,
+                                     reset_every=tau if policy == "reset" else None)
+        _close(o.x0, want, rtol=1e-11, atol=1e-12, what=f"Nesterov base ({policy})")
+
+
+def pin_per_worker_replicas_vs_library(make):
+    """Algorithm 1 lines 3-5: within an outer iteration every worker runs the
+    base optimizer on ITS OWN gradients from the common start x_{t,0}."""
+    rng = _rng(10)
+    tau, m, d, lr, mu, wd = 5, 3, 9, 0.1, 0.9, 1e-3
+    g = _grads(rng, 2, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=0.6, beta=0.5, momentum=mu, weight_decay=wd)
+    for t in range(2):
+        start = o.x0.copy()
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+        for i in range(m):
+            want = _torch_sgd_per_worker(start, g[t, :, i, :], lr, mu, wd)
+            _close(o.x[i], want, rtol=1e-11, atol=1e-12, what=f"worker {i} replica")
+        o.outer_step(lr)
+
+
+def pin_nesterov_constant_gradient(make):
+    """Table C.1 SGD row with a constant gradient c and h_0 = 0:
+    h_k = c(1-mu^k)/(1-mu) and sum_{k<tau} d_k =
+    c[tau + mu/(1-mu) * (tau - mu(1-mu^tau)/(1-mu))]."""
+    tau, d, lr, mu = 7, 5, 0.1, 0.9
+    c = np.linspace(-2, 2, d)
+    x_init = np.linspace(1, 3, d)
+    g = np.broadcast_to(c.astype(np.float32), (1, d))
+    cf = g[0].astype(np.float64)
+    o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, momentum=mu, policy="maintain")
+    for k in range(tau):
+        o.local_step(g, lr)
+    sum_d = cf * (tau + mu / (1 - mu) * (tau - mu * (1 - mu ** tau) / (1 - mu)))
+    _close(o.h[0], cf * (1 - mu ** tau) / (1 - mu), what="h closed form")
+    _close(o.x[0], x_init - lr * sum_d, what="sum of Nesterov directions")
+    o.outer_step(lr)
+    for k in range(tau):
+        o.local_step(g, lr)
+    _close(o.h[0], cf * (1 - mu ** (2 * tau)) / (1 - mu), what="maintained h after 2 tau")
+
+
+def pin_reset_restarts_momentum(make):
+    """Appendix B.4 / Table C.1 caption: under "reset" h_{t,0} = 0, so with a
+    constant gradient every outer iteration repeats the same displacement;
+    under "maintain" the second one is larger."""
+    tau, d, lr, mu = 4, 3, 0.1, 0.9
+    g = np.ones((1, d), np.float32)
+    disp = {}
+    for policy in ("reset", "maintain"):
+        o = make(np.zeros(d), m=1, tau=tau, alpha=1.0, beta=0.0, momentum=mu, policy=policy)
+        steps = []
+        for t in range(3):
+            before = o.x0.copy()
+            for k in range(tau):
+                o.local_step(g, lr)
+            o.outer_step(lr)
+            steps.append(o.x0 - before)
+        disp[policy] = steps
+    _close(disp["reset"][1], disp["reset"][0], what="reset repeats")
+    _close(disp["reset"][2], disp["reset"][0], what="reset repeats")
+    _close(disp["maintain"][0], disp["reset"][0], what="first iteration equal")
+    assert np.all(np.abs(disp["maintain"][1]) > 1.5 * np.abs(disp["reset"][1]))
+
+
+def pin_weight_decay_geometric(make):
+    """Coupled L2 decay with zero gradient and no momentum:
+    x_k = (1 - gamma*wd)^k x_0; and wd = 0 leaves x unchanged."""
+    tau, d, lr, wd = 9, 6, 0.1, 0.05
+    x_init = np.linspace(-3, 3, d)
+    g = np.zeros((1, d), np.float32)
+    o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, weight_decay=wd)
+    for k in range(tau):
+        o.local_step(g, lr)
+        _close(o.x[0], (1 - lr * wd) ** (k + 1) * x_init, what="geometric decay")
+    o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, weight_decay=0.0)
+    o.local_step(g, lr)
+    assert np.array_equal(o.x[0], x_init)
+
+
+# ------------------------------------------------------- Table C.1, Adam
+
+def _torch_adam(x_init, g, lr, b1, b2, eps, reset_every=None):
+    p = torch.tensor(np.asarray(x_init, dtype=np.float64), requires_grad=True)
+    mk = lambda: torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps)  # noqa: E731
+    opt = mk()
+    for s in range(g.shape[0]):
+        if reset_every and s % reset_every == 0:
+            opt = mk()
+        p.grad = torch.tensor(g[s].astype(np.float64))
+        opt.step()
+    return p.detach().numpy()
+
+
+def pin_adam_base_vs_library(make):
+    """Table C.1's Adam row (eps added after the root of the bias-corrected
+    second moment) is algebraically the library's Adam; "maintain" keeps
+    moments and step count across outer iterations, "reset" restarts them."""
+    rng = _rng(11)
+    T, tau, d, lr, b1, b2, eps = 3, 4, 10, 1e-2, 0.9, 0.98, 1e-8
+    g = _grads(rng, T, tau, 1, d)
+    x_init = rng.standard_normal(d)
+    for policy in ("maintain", "reset"):
+        o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, base="adam",
+                 beta1=b1, beta2=b2, eps=eps, policy=policy)
+        o.run(lambda t, k: g[t, k], lr, T)
+        want = _torch_adam(x_init, g.reshape(T * tau, d), lr, b1, b2, eps,
+                           reset_every=tau if policy == "reset" else None)
+        _close(o.x0, want, rtol=1e-10, atol=1e-12, what=f"Adam base ({policy})")
+
+
+def pin_adam_per_worker_vs_library(make):
+    rng = _rng(12)
+    tau, m, d, lr, b1, b2, eps = 6, 3, 7, 1e-2, 0.9, 0.98, 1e-8
+    g = _grads(rng, 1, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.5, base="adam",
+             beta1=b1, beta2=b2, eps=eps)
+    for k in range(tau):
+        o.local_step(g[0, k], lr)
+    for i in range(m):
+        _close(o.x[i], _torch_adam(x_init, g[0, :, i, :], lr, b1, b2, eps),
+               rtol=1e-10, atol=1e-12, what=f"Adam worker {i}")
+
+
+def pin_adam_constant_gradient(make):
+    """With a constant gradient c the bias-corrected moments are exactly c and
+    c^2 at every step, so x_k = x_0 - k*gamma*c/(|c| + eps) -- from step 1 on,
+    which only holds if the bias-correction exponent counts the current
+    update.  c = 0 gives a zero direction, not 0/0."""
+    tau, d, lr, eps = 5, 6, 1e-2, 1e-3
+    c = np.array([-2.0, -0.5, 0.0, 0.25, 1.0, 3.0])
+    g = c.astype(np.float32)[None, :]
+    x_init = np.linspace(-1, 1, d)
+    o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, base="adam",
+             beta1=0.9, beta2=0.98, eps=eps, policy="maintain")
+    n = 0
+    for t in range(2):
+        for k in range(tau):
+            o.local_step(g, lr)
+            n += 1
+            _close(o.x[0], x_init - n * lr * c / (np.abs(c) + eps), rtol=1e-11,
+                   what=f"Adam constant gradient, step {n}")
+        o.outer_step(lr)
+    assert np.all(np.isfinite(o.x0))
+
+
+# ------------------------------------------- Algorithm 1, lines 6-8 together
+
+def pin_constant_gradient_slowmo(make):
+    """Eq. (2)-(3) with plain SGD and constant per-worker gradients c_i (mean
+    cbar): u_t = tau*cbar*(1-beta^t)/(1-beta) and
+    x_{T,0} = x_{0,0} - alpha*gamma*tau*cbar*sum_{t=1..T}(1-beta^t)/(1-beta)."""
+    T, tau, m, d, lr, alpha, beta = 6, 3, 4, 5, 0.1, 0.8, 0.6
+    rng = _rng(13)
+    c = rng.standard_normal((m, d)).astype(np.float32)
+    cbar = c.astype(np.float64).mean(axis=0)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=alpha, beta=beta)
+    acc = 0.0
+    for t in range(1, T + 1):
+        for k in range(tau):
+            o.local_step(c, lr)
+        o.outer_step(lr)
+        geo = (1 - beta ** t) / (1 - beta)
+        acc += geo
+        _close(o.u, tau * cbar * geo, rtol=1e-10, atol=1e-12, what=f"u_t closed form t={t}")
+        _close(o.x0, x_init - alpha * lr * tau * cbar * acc, rtol=1e-11, atol=1e-12,
+               what=f"x_T closed form t={t}")
+
+
+def pin_mean_is_symmetric_and_m1_identity(make):
+    """Line 6 is a plain mean: permuting the workers changes nothing beyond
+    rounding; with m = 1 (alpha = 1, beta = 0) the outer step is the identity."""
+    rng = _rng(14)
+    tau, m, d, lr = 3, 5, 8, 0.1
+    g = _grads(rng, 1, tau, m, d)
+    x_init = rng.standard_normal(d)
+    res = []
+    for perm in (np.arange(m), np.array([3, 0, 4, 1, 2])):
+        o = make(x_init, m=m, tau=tau, alpha=0.9, beta=0.3, momentum=0.9)
+        for k in range(tau):
+            o.local_step(g[0, k][perm], lr)
+        o.outer_step(lr)
+        res.append(o.x0.copy())
+    _close(res[0], res[1], rtol=1e-14, atol=1e-15, what="worker permutation")
+    o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, momentum=0.9)
+    for k in range(tau):
+        o.local_step(g[0, k][:1], lr)
+    fast = o.x[0].copy()
+    o.outer_step(lr)
+    _close(o.x0, fast, rtol=1e-14, atol=1e-15, what="m=1 identity")
+
+
+def pin_outer_uses_lr_of_outer_call(make):
+    """Eq. (2)-(3): gamma_t appears as 1/gamma_t in u and as alpha*gamma_t in
+    the iterate; with beta = 0 they cancel, so x_{t+1,0} must not depend on the
+    value handed to the outer step, while u scales with its inverse."""
+    rng = _rng(15)
+    tau, m, d = 3, 2, 6
+    g = _grads(rng, 1, tau, m, d)
+    x_init = rng.standard_normal(d)
+    outs = []
+    for lr_outer in (0.1, 0.4):
+        o = make(x_init, m=m, tau=tau, alpha=0.5, beta=0.0)
+        for k in range(tau):
+            o.local_step(g[0, k], 0.1)
+        o.outer_step(lr_outer)
+        outs.append((o.x0.copy(), o.u.copy()))
+    _close(outs[0][0], outs[1][0], rtol=1e-12, what="x0 independent of outer lr at beta=0")
+    _close(outs[0][1], 4.0 * outs[1][1], rtol=1e-12, what="u scales with 1/gamma")
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

@@ -1,0 +1,112 @@
+"""Every planted mistake in a copy of the oracle must fail at least one pin.
+
+The mistakes are planted on the CPU, in temporary copies of the oracle's C and
+Python sources; the real oracle is untouched."""
+import os
+import types
+
+import pytest
+
+from oracle import slowmo_oracle as O
+
+import oracle_pins as P
+
+C_SRC = open(os.path.join(os.path.dirname(O.__file__), "slowmo_oracle.c")).read()
+PY_SRC = open(O.__file__).read()
+
+# (name, old, new, occurrence)   occurrence: which match of `old` to replace
+C_MUTANTS = [
+    ("sgd_h_sign", "REAL hn = mu * h[j] + grad;", "REAL hn = mu * h[j] - grad;", 0),
+    ("sgd_dir_uses_old_h", "REAL dir = mu * hn + grad;", "REAL dir = mu * h[j] + grad;", 0),
+    ("sgd_dir_drops_grad", "REAL dir = mu * hn + grad;", "REAL dir = mu * hn;", 0),
+    ("sgd_h_drops_mu", "REAL hn = mu * h[j] + grad;", "REAL hn = h[j] + grad;", 0),
+    ("sgd_no_weight_decay", "(REAL)g[j] + wd * x[j]", "(REAL)g[j]", 0),
+    ("sgd_decoupled_decay_sign", "(REAL)g[j] + wd * x[j]", "(REAL)g[j] - wd * x[j]", 0),
+    ("sgd_step_sign", "x[j] = x[j] - lr * dir;", "x[j] = x[j] + lr * dir;", 0),
+    ("sgd_step_drops_lr", "x[j] = x[j] - lr * dir;", "x[j] = x[j] - dir;", 0),
+    ("adam_h_no_one_minus_b1", "(one - b1) * grad", "grad", 0),
+    ("adam_v_not_squared", "(one - b2) * gsq", "(one - b2) * grad", 0),
+    ("adam_v_uses_b1", "b2 * v[j]", "b1 * v[j]", 0),
+    ("adam_exponent_plus_one", "R_POW(b1, (REAL)l)", "R_POW(b1, (REAL)(l + 1))", 0),
+    ("adam_exponent2_plus_one", "R_POW(b2, (REAL)l)", "R_POW(b2, (REAL)(l + 1))", 0),
+    ("adam_eps_inside_root", "(R_SQRT(vhat) + eps)", "R_SQRT(vhat + eps)", 0),
+    ("adam_no_bias_correction_h", "REAL hhat = hn / c1;", "REAL hhat = hn;", 0),
+    ("adam_bias_swapped", "REAL vhat = vn / c2;", "REAL vhat = vn / c1;", 0),
+    ("adam_no_root", "R_SQRT(vhat)", "vhat", 0),
+    ("adam_step_sign", "x[j] = x[j] - lr * dir;", "x[j] = x[j] + lr * dir;", 1),
+    ("adam_v_not_stored", "v[j] = vn;", "v[j] = v[j];", 0),
+    ("outer_no_division_by_m", "REAL xbar = s / (REAL)m;", "REAL xbar = s;", 0),
+    ("outer_drops_last_worker", "for (int i = 1; i < m; ++i)", "for (int i = 1; i < m - 1; ++i)", 0),
+    ("outer_diff_sign", "REAL diff = x0[j] - xbar;", "REAL diff = xbar - x0[j];", 0),
+    ("outer_u_no_inverse_lr", "beta * u[j] + diff / lr", "beta * u[j] + diff", 0),
+    ("outer_u_times_lr", "beta * u[j] + diff / lr", "beta * u[j] + diff * lr", 0),
+    ("outer_u_drops_beta", "beta * u[j] + diff / lr", "u[j] + diff / lr", 0),
+    ("outer_x_drops_alpha", "(alpha * lr) * un", "lr * un", 0),
+    ("outer_x_drops_lr", "(alpha * lr) * un", "alpha * un", 0),
+    ("outer_x_sign", "x0[j] - (alpha * lr) * un", "x0[j] + (alpha * lr) * un", 0),
+    ("outer_u_not_stored", "u[j] = un;", "u[j] = u[j];", 0),
+    ("outer_broadcasts_mean", "xw[(int64_t)i * d + j] = xn;", "xw[(int64_t)i * d + j] = xbar;", 0),
+    ("outer_no_broadcast", "xw[(int64_t)i * d + j] = xn;", ";", 0),
+    ("outer_transposed_replicas", "s = s + xw[(int64_t)i * d + j];", "s = s + xw[(int64_t)j * m + i];", 0),
+]
+
+PY_MUTANTS = [
+    ("policy_never_reset", 'if self.policy == "reset":', "if False:", 0),
+    ("policy_always_reset", 'if self.policy == "reset":', "if True:", 0),
+    ("reset_keeps_v", "                self.v[...] = 0\n", "                pass\n", 0),
+    ("reset_keeps_step_count", "                self.v[...] = 0\n            self.l = 0\n",
+     "                self.v[...] = 0\n", 0),
+    ("policy_only_first_iteration", "if self.k == 0:", "if self.k == 0 and self.t == 0:", 0),
+    ("policy_every_step", "if self.k == 0:", "if True:", 0),
+    ("sgd_all_workers_use_grad0", "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,",
+     "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[0]), self.d,", 0),
+    ("sgd_workers_share_h", "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,",
+     "_ptr(self.x[i]), _ptr(self.h[0]), _ptr(g[i]), self.d,", 0),
+    ("adam_all_workers_use_grad0", "_ptr(self.v[i]), _ptr(g[i]),", "_ptr(self.v[i]), _ptr(g[0]),", 0),
+    ("outer_alpha_beta_swapped", "lr, self.alpha, self.beta)", "lr, self.beta, self.alpha)", 0),
+    ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
+     'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
+]
+
+
+def _replace_nth(src, old, new, n):
+    pos = -1
+    for _ in range(n + 1):
+        pos = src.find(old, pos + 1)
+        assert pos >= 0, f"mutation target not found: {old!r}"
+    return src[:pos] + new + src[pos + len(old):]
+
+
+def _killed(make):
+    """Names of the pins that fail for this (mutated) oracle."""
+    killed = []
+    for pin in P.ALL_PINS:
+        try:
+            pin(make)
+        except AssertionError:
+            killed.append(pin.__name__)
+    return killed
+
+
+@pytest.mark.parametrize("name,old,new,nth", C_MUTANTS, ids=[m[0] for m in C_MUTANTS])
+def test_c_mutant_is_caught(tmp_path, name, old, new, nth):
+    src = tmp_path / "mutant.c"
+    src.write_text(_replace_nth(C_SRC, old, new, nth))
+    lib_path = str(tmp_path / "libmutant_f64.so")
+    O.build(force=True, src=str(src), out={"f64": lib_path})
+    lib = O.load("f64", path=lib_path)
+    killed = _killed(lambda x, **kw: O.SlowMoOracle(x, prec="f64", lib=lib, **kw))
+    assert killed, f"no pin notices the planted mistake '{name}'"
+
+
+@pytest.mark.parametrize("name,old,new,nth", PY_MUTANTS, ids=[m[0] for m in PY_MUTANTS])
+def test_python_mutant_is_caught(name, old, new, nth):
+    mod = types.ModuleType("oracle_mutant")
+    mod.__file__ = O.__file__
+    exec(compile(_replace_nth(PY_SRC, old, new, nth), O.__file__, "exec"), mod.__dict__)
+    killed = _killed(lambda x, **kw: mod.SlowMoOracle(x, prec="f64", **kw))
+    assert killed, f"no pin notices the planted mistake '{name}'"
+
+
+def test_unmutated_oracle_passes_every_pin():
+    assert _killed(lambda x, **kw: O.SlowMoOracle(x, prec="f64", **kw)) == []

@@ -1,0 +1,80 @@
+"""The oracle against what the paper and the mathematics fix (CPU only)."""
+import numpy as np
+import pytest
+
+from oracle import slowmo_oracle as O
+from slowmo_inputs import generator as G
+from slowmo_inputs import workloads as W
+
+import oracle_pins as P
+
+
+def _make(x_init, **kw):
+    return O.SlowMoOracle(x_init, prec="f64", **kw)
+
+
+@pytest.mark.parametrize("pin", P.ALL_PINS, ids=lambda f: f.__name__)
+def test_pin(pin):
+    pin(_make)
+
+
+def _run_tiny(prec, rounds):
+    w = W.tiny()
+    idx = np.arange(w.d, dtype=np.int64)
+    o = O.SlowMoOracle(G.initial_params(w.seed, idx), m=w.m, tau=w.tau,
+                       alpha=w.f32("alpha"), beta=w.f32("beta"), base=w.base,
+                       policy=w.policy, momentum=w.f32("momentum"),
+                       weight_decay=w.f32("weight_decay"), prec=prec)
+
+    def grad(t, k):
+        return np.stack([G.gradient(w.seed, i, t * w.tau + k, idx, w.sigma)
+                         for i in range(w.m)])
+    o.run(grad, w.f32("lr"), rounds)
+    return o
+
+
+def test_fp32_build_is_inside_the_parity_tolerance_of_fp64():
+    """The fp32 build of the same source, on the tiny configuration's full
+    run, stays inside |delta| <= 1e-5 (1 + |x|) for the parameters: the bound
+    the GPU path has to meet leaves room for fp32 rounding (measured: about
+    6e-6).  u carries the parameters' rounding error divided by gamma (Eq. (2)),
+    so its bound is the same one applied to gamma*u, a quantity in x's units."""
+    w = W.tiny()
+    lr = w.f32("lr")
+    o64 = _run_tiny("f64", w.rounds)
+    o32 = _run_tiny("f32", w.rounds)
+    for a, b in ((o64.x0, o32.x0), (o64.x, o32.x)):
+        err = np.abs(a - b.astype(np.float64)) / (1.0 + np.abs(a))
+        assert err.max() <= 1e-5, err.max()
+        assert err.max() > 0.0          # the two builds really differ in precision
+    err_u = lr * np.abs(o64.u - o32.u.astype(np.float64)) / (1.0 + lr * np.abs(o64.u))
+    assert err_u.max() <= 1e-5, err_u.max()
+
+
+def test_f32_and_f64_builds_report_their_precision():
+    assert O.load("f64").oracle_real_bytes() == 8
+    assert O.load("f32").oracle_real_bytes() == 4
+
+
+def _read_golden():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_o64.txt")
+    rows, sums = [], {}
+    for line in open(path):
+        p = line.split()
+        if line.startswith("# sum_"):
+            sums[p[1]] = float.fromhex(p[2])
+        elif not line.startswith("#"):
+            rows.append((int(p[0]), float.fromhex(p[1]), float.fromhex(p[2])))
+    return rows, sums
+
+
+def test_oracle_reproduces_stored_values():
+    """Regression guard: the stored fp64 values of the tiny configuration
+    (written by tests/golden/make_golden.py from the oracle alone)."""
+    o = _run_tiny("f64", W.tiny().rounds)
+    rows, sums = _read_golden()
+    for j, x0, u in rows:
+        assert abs(o.x0[j] - x0) <= 1e-12 * (1 + abs(x0))
+        assert abs(o.u[j] - u) <= 1e-12 * (1 + abs(u))
+    assert abs(o.x0.sum() - sums["sum_x0"]) <= 1e-9 * (1 + abs(sums["sum_x0"]))
