@@ -1,0 +1,188 @@
+/*
+ * slowmo.h -- C ABI of the Slow Momentum optimizer hot path for one AMD
+ * MI355X (gfx950).
+ *
+ * The library runs, for m logical workers whose parameter replicas all live
+ * on one GPU, the per-element work of Algorithm 1 ("Slow Momentum"):
+ * tau base-optimizer steps per worker (directions of Table C.1, Appendix C:
+ * SGD with Nesterov momentum, or Adam), then the outer step (exact average,
+ * slow-momentum update Eq. (2), outer-iterate update Eq. (3)) and the copy of
+ * the new iterate into every replica.
+ *
+ * Conventions
+ *  - All pointers named "device" are HIP device pointers; everything else is
+ *    host memory that may be freed as soon as the call returns.
+ *  - Parameters are fp32.  Gradients are fp32 or bf16 (widened exactly).
+ *    State (x0, u, h, v) is fp32.  All arithmetic is fp32.
+ *  - Tensor lists are worker-major: entry [i * n_tensors + j] belongs to
+ *    worker i, tensor j.  Tensor j has numel[j] contiguous elements on every
+ *    worker.  Pointers need element alignment only (4 bytes fp32, 2 bytes
+ *    bf16); 16-byte alignment selects the vectorized path.
+ *  - Ownership: parameters, gradients and the state workspace belong to the
+ *    caller.  The library keeps the parameter pointers and the workspace for
+ *    the context's lifetime and never frees them; they must not overlap.
+ *  - Streams: work is enqueued on the hipStream_t passed as `stream` (NULL =
+ *    the default stream) and the call returns without synchronizing.  All
+ *    calls on one context must be issued on one stream or be ordered by the
+ *    caller.  A context is not thread-safe.
+ *  - Errors: every entry point returns a slowmo_status; nothing aborts or
+ *    throws.  A call that fails leaves the context's state unchanged.
+ *    slowmo_last_error() gives a message for the most recent failure.
+ */
+#ifndef SLOWMO_H
+#define SLOWMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct slowmo_ctx slowmo_ctx; /* opaque */
+
+typedef enum {
+  SLOWMO_OK = 0,
+  SLOWMO_ERR_ARG = -1,   /* null pointer, size or hyper-parameter out of range, bad enum */
+  SLOWMO_ERR_STATE = -2, /* call out of sequence (see local/outer step) */
+  SLOWMO_ERR_ALIGN = -3, /* pointer not aligned to its element size / workspace not 256-byte aligned */
+  SLOWMO_ERR_HIP = -4,   /* a HIP runtime call failed (no device, launch failure, ...) */
+  SLOWMO_ERR_NOMEM = -5  /* workspace too small, or host allocation failed */
+} slowmo_status;
+
+/* Base optimizer: the rows "SGD" and "Adam" of Table C.1. */
+typedef enum { SLOWMO_SGD_NESTEROV = 0, SLOWMO_ADAM = 1 } slowmo_base;
+
+/* What happens to the base optimizer's buffers at the start of an outer
+ * iteration (Algorithm 1 line 2; Appendix B.4).  RESET: h (and v, and Adam's
+ * step count) restart from zero -- the paper's default for SGD.  MAINTAIN:
+ * they carry over -- the paper's default for Adam. */
+typedef enum { SLOWMO_BUF_RESET = 0, SLOWMO_BUF_MAINTAIN = 1 } slowmo_bufpolicy;
+
+typedef enum { SLOWMO_F32 = 0, SLOWMO_BF16 = 1 } slowmo_dtype; /* gradient element type */
+
+/* Inputs of Algorithm 1 plus the base optimizer's hyper-parameters. */
+typedef struct {
+  int32_t m;           /* number of workers, 1..SLOWMO_MAX_WORKERS */
+  int32_t tau;         /* base-optimizer steps per outer iteration, >= 1 */
+  float alpha;         /* slow learning rate, > 0 */
+  float beta;          /* slow momentum factor, 0 <= beta < 1 */
+  int32_t base;        /* slowmo_base */
+  int32_t policy;      /* slowmo_bufpolicy */
+  int32_t grad_dtype;  /* slowmo_dtype */
+  float momentum;      /* SGD: local Nesterov momentum beta_local, 0 <= . < 1 */
+  float weight_decay;  /* coupled L2 term added to the gradient: g + wd * x, >= 0 */
+  float beta1, beta2;  /* Adam moment factors, 0 <= . < 1 */
+  float eps;           /* Adam epsilon (added after the square root), >= 0 */
+} slowmo_config;
+
+#define SLOWMO_MAX_WORKERS 1024
+
+/* Which internal buffer slowmo_get_buffer() returns. */
+typedef enum { SLOWMO_BUF_X0 = 0, SLOWMO_BUF_U = 1, SLOWMO_BUF_H = 2, SLOWMO_BUF_V = 3 } slowmo_buffer;
+
+/*
+ * Bytes of device workspace a context needs for this configuration and
+ * tensor list: x0 and u (one copy each), h (and v for Adam) per worker, and
+ * the tiling tables.  Returns 0 if the arguments are invalid.  Host-only.
+ */
+size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int64_t *numel);
+
+/*
+ * Algorithm 1, "Input" line.  Creates a context over a fixed tensor list.
+ *   params : host array of m * n_tensors DEVICE pointers (worker-major) to
+ *            the fp32 replicas; kept for the context's lifetime.
+ *   state  : DEVICE workspace, 256-byte aligned, at least
+ *            slowmo_state_bytes() long; owned by the caller.
+ * Effects, enqueued on `stream`: x_{0,0} is taken from worker 0's replica and
+ * copied into x0 and into the replicas of workers 1..m-1 (the paper assumes a
+ * common starting point; this enforces it); u_0 = 0; h = v = 0.
+ * Needs a HIP device.  Errors: ARG, ALIGN, NOMEM, HIP.
+ */
+slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t n_tensors,
+                            const int64_t *numel, float *const *params, void *state,
+                            size_t state_bytes, void *stream);
+
+/*
+ * Algorithm 1 lines 3-5 for one k: one base-optimizer step on all m workers,
+ *   x^{(i)} <- x^{(i)} - lr * d^{(i)},  d per Table C.1 (SGD row: h <- mu h + g~,
+ *   d = mu h + g~;  Adam row: bias-corrected h / (sqrt(v) + eps)),
+ *   g~ = g + weight_decay * x.
+ * Adam's bias-correction exponent is the number of Adam steps taken so far
+ * under the buffer policy, counting this one.
+ *   grads : host array of m * n_tensors DEVICE pointers (worker-major) to the
+ *           gradients of this step, of the configured dtype; may change from
+ *           call to call.  Read only.
+ *   lr    : gamma_t for this step, finite and > 0.
+ * Errors: ARG, ALIGN, HIP; STATE if tau steps were already taken since the
+ * last outer step.
+ */
+slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float lr, void *stream);
+
+/*
+ * Algorithm 1 lines 6-8 in one pass over the elements:
+ *   xbar = (x^{(0)} + x^{(1)} + ... + x^{(m-1)}) / m      (summed in this order)
+ *   u   <- beta * u + (x0 - xbar) / lr                     Eq. (2)
+ *   x0  <- x0 - (alpha * lr) * u                           Eq. (3)
+ *   x^{(i)} <- x0 for every worker i,
+ * and arms the buffer policy for the next outer iteration (line 2).
+ *   lr : gamma_t, finite and > 0 (Eq. (2) divides by it).
+ * Errors: ARG, HIP; STATE unless exactly tau local steps were taken since the
+ * previous outer step (or since creation).
+ */
+slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream);
+
+/* Frees the context's host memory and its small device-side bookkeeping.
+ * Never touches parameters, gradients or the workspace.  NULL is accepted. */
+slowmo_status slowmo_destroy(slowmo_ctx *ctx);
+
+/* Message of the last failed call on ctx; with ctx == NULL, of the last
+ * failed call on this thread that had no context (e.g. a failed create).
+ * Never NULL.  The string stays valid until the next call on that context
+ * (or thread). */
+const char *slowmo_last_error(const slowmo_ctx *ctx);
+
+/*
+ * Inspection (tests, checkpointing): device pointer to the first element of
+ * an internal buffer of `tensor`: x0 / u (worker ignored), h / v of `worker`.
+ * The numel[tensor] elements are contiguous.  Under the RESET policy h and v
+ * are undefined between an outer step and the next local step.  ARG if the
+ * buffer does not exist (v without Adam) or an index is out of range.
+ */
+slowmo_status slowmo_get_buffer(slowmo_ctx *ctx, int32_t which, int32_t worker, int32_t tensor,
+                                float **device_ptr);
+
+/* Counters: t = outer iterations completed, k = local steps taken in the
+ * current outer iteration, l = Adam steps counted by the bias correction.
+ * Any output pointer may be NULL. */
+slowmo_status slowmo_get_counters(const slowmo_ctx *ctx, int64_t *t, int32_t *k, int64_t *l);
+
+/*
+ * Host-only view of the tiling (tests of the host logic; needs no device).
+ * One record per contiguous run of elements a workgroup processes.  The
+ * local-step tiling covers every (worker, tensor, element) exactly once; the
+ * outer-step tiling covers every (tensor, element) exactly once (worker = -1).
+ * Runs continue a tensor only at element offsets that are multiples of 4.
+ * Writes at most `cap` records to `out` (may be NULL with cap 0) and returns
+ * the total number of records, or -1 on invalid arguments.
+ */
+typedef struct {
+  int32_t tile;    /* workgroup-sized unit of work this run belongs to */
+  int32_t worker;  /* -1 for the outer step */
+  int32_t tensor;
+  int32_t n;       /* elements in the run */
+  int64_t offset;  /* first element of the run inside its tensor */
+} slowmo_plan_run;
+
+int64_t slowmo_plan_local(int32_t m, int32_t n_tensors, const int64_t *numel,
+                          slowmo_plan_run *out, int64_t cap);
+int64_t slowmo_plan_outer(int32_t m, int32_t n_tensors, const int64_t *numel,
+                          slowmo_plan_run *out, int64_t cap);
+
+/* Library version, e.g. "0.1.0 gfx950". */
+const char *slowmo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLOWMO_H */

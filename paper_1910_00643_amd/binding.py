@@ -1,0 +1,182 @@
+"""ctypes binding of libslowmo.so: the same entry points as include/slowmo.h,
+argument marshalling only.  No arithmetic on tensor elements happens here.
+
+The library must have been built (python -m paper_1910_00643_amd.build or
+__graft_entry__.build()); loading fails loudly otherwise -- there is no
+fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libslowmo.so")
+
+SLOWMO_OK, SLOWMO_ERR_ARG, SLOWMO_ERR_STATE = 0, -1, -2
+SLOWMO_ERR_ALIGN, SLOWMO_ERR_HIP, SLOWMO_ERR_NOMEM = -3, -4, -5
+SLOWMO_SGD_NESTEROV, SLOWMO_ADAM = 0, 1
+SLOWMO_BUF_RESET, SLOWMO_BUF_MAINTAIN = 0, 1
+SLOWMO_F32, SLOWMO_BF16 = 0, 1
+SLOWMO_BUF_X0, SLOWMO_BUF_U, SLOWMO_BUF_H, SLOWMO_BUF_V = 0, 1, 2, 3
+SLOWMO_MAX_WORKERS = 1024
+
+STATUS_NAMES = {0: "SLOWMO_OK", -1: "SLOWMO_ERR_ARG", -2: "SLOWMO_ERR_STATE",
+                -3: "SLOWMO_ERR_ALIGN", -4: "SLOWMO_ERR_HIP", -5: "SLOWMO_ERR_NOMEM"}
+
+# every symbol include/slowmo.h declares
+EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_outer_step",
+           "slowmo_destroy", "slowmo_last_error", "slowmo_get_buffer", "slowmo_get_counters",
+           "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version"]
+
+
+class slowmo_config(C.Structure):
+    _fields_ = [("m", C.c_int32), ("tau", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
+                ("base", C.c_int32), ("policy", C.c_int32), ("grad_dtype", C.c_int32),
+                ("momentum", C.c_float), ("weight_decay", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+
+
+class slowmo_plan_run(C.Structure):
+    _fields_ = [("tile", C.c_int32), ("worker", C.c_int32), ("tensor", C.c_int32),
+                ("n", C.c_int32), ("offset", C.c_int64)]
+
+
+class SlowMoError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -m paper_1910_00643_amd.build` (needs hipcc); "
+                          "there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    cfgp = C.POINTER(slowmo_config)
+    L.slowmo_state_bytes.argtypes = [cfgp, i32, C.POINTER(i64)]
+    L.slowmo_state_bytes.restype = C.c_size_t
+    L.slowmo_create.argtypes = [C.POINTER(vp), cfgp, i32, C.POINTER(i64), C.POINTER(vp), vp,
+                                C.c_size_t, vp]
+    L.slowmo_create.restype = C.c_int
+    L.slowmo_local_step.argtypes = [vp, C.POINTER(vp), C.c_float, vp]
+    L.slowmo_local_step.restype = C.c_int
+    L.slowmo_outer_step.argtypes = [vp, C.c_float, vp]
+    L.slowmo_outer_step.restype = C.c_int
+    L.slowmo_destroy.argtypes = [vp]
+    L.slowmo_destroy.restype = C.c_int
+    L.slowmo_last_error.argtypes = [vp]
+    L.slowmo_last_error.restype = C.c_char_p
+    L.slowmo_get_buffer.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
+    L.slowmo_get_buffer.restype = C.c_int
+    L.slowmo_get_counters.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
+    L.slowmo_get_counters.restype = C.c_int
+    L.slowmo_plan_local.argtypes = [i32, i32, C.POINTER(i64), C.POINTER(slowmo_plan_run), i64]
+    L.slowmo_plan_local.restype = i64
+    L.slowmo_plan_outer.argtypes = [i32, i32, C.POINTER(i64), C.POINTER(slowmo_plan_run), i64]
+    L.slowmo_plan_outer.restype = i64
+    L.slowmo_version.argtypes = []
+    L.slowmo_version.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _i64_array(values: Sequence[int]):
+    return (C.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(values: Optional[Sequence[int]]):
+    if values is None:
+        return None
+    return (C.c_void_p * len(values))(*[C.c_void_p(int(v)) if v else None for v in values])
+
+
+def _check(status: int, ctx) -> None:
+    if status != SLOWMO_OK:
+        raise SlowMoError(status, slowmo_last_error(ctx))
+
+
+def slowmo_version() -> str:
+    return lib().slowmo_version().decode()
+
+
+def slowmo_last_error(ctx=None) -> str:
+    return lib().slowmo_last_error(ctx).decode()
+
+
+def slowmo_state_bytes(cfg: slowmo_config, numel: Sequence[int]) -> int:
+    """Bytes of device workspace; 0 if the arguments are invalid."""
+    arr = _i64_array(numel) if numel is not None else None
+    return int(lib().slowmo_state_bytes(C.byref(cfg) if cfg is not None else None,
+                                        len(numel) if numel is not None else 0, arr))
+
+
+def slowmo_create(cfg: slowmo_config, numel: Sequence[int], params: Sequence[int],
+                  state: int, state_bytes: int, stream: int = 0) -> C.c_void_p:
+    """params: m * n_tensors device addresses (worker-major); state: device
+    address of the workspace.  Returns the context handle."""
+    ctx = C.c_void_p()
+    st = lib().slowmo_create(C.byref(ctx), C.byref(cfg) if cfg is not None else None,
+                             len(numel) if numel is not None else 0,
+                             _i64_array(numel) if numel is not None else None,
+                             _ptr_array(params), C.c_void_p(state) if state else None,
+                             state_bytes, C.c_void_p(stream) if stream else None)
+    _check(st, None)
+    return ctx
+
+
+def slowmo_local_step(ctx, grads, lr: float, stream: int = 0) -> None:
+    """grads: m * n_tensors device addresses, or a prepared ctypes array."""
+    arr = grads if (grads is None or isinstance(grads, C.Array)) else _ptr_array(grads)
+    _check(lib().slowmo_local_step(ctx, arr, lr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_outer_step(ctx, lr: float, stream: int = 0) -> None:
+    _check(lib().slowmo_outer_step(ctx, lr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_destroy(ctx) -> None:
+    _check(lib().slowmo_destroy(ctx), None)
+
+
+def slowmo_get_buffer(ctx, which: int, worker: int, tensor: int) -> int:
+    """Device address of the first element of an internal buffer of `tensor`."""
+    out = C.c_void_p()
+    _check(lib().slowmo_get_buffer(ctx, which, worker, tensor, C.byref(out)), ctx)
+    return int(out.value or 0)
+
+
+def slowmo_get_counters(ctx):
+    """(t, k, l): outer iterations done, local steps in this one, Adam steps."""
+    t, k, l = C.c_int64(), C.c_int32(), C.c_int64()
+    _check(lib().slowmo_get_counters(ctx, C.byref(t), C.byref(k), C.byref(l)), ctx)
+    return t.value, k.value, l.value
+
+
+def _plan(fn, m: int, numel: Sequence[int]):
+    arr = _i64_array(numel)
+    n = fn(m, len(numel), arr, None, 0)
+    if n < 0:
+        raise SlowMoError(SLOWMO_ERR_ARG, "invalid arguments to the plan query")
+    buf = (slowmo_plan_run * max(n, 1))()
+    fn(m, len(numel), arr, buf, n)
+    return [(r.tile, r.worker, r.tensor, r.n, r.offset) for r in buf[:n]]
+
+
+def slowmo_plan_local(m: int, numel: Sequence[int]):
+    """[(tile, worker, tensor, n, offset)] of the local-step tiling."""
+    return _plan(lib().slowmo_plan_local, m, numel)
+
+
+def slowmo_plan_outer(m: int, numel: Sequence[int]):
+    return _plan(lib().slowmo_plan_outer, m, numel)

@@ -1,0 +1,499 @@
+// C ABI of the Slow Momentum hot path: argument checking, workspace layout,
+// tiling tables, per-call gradient-pointer table, counters.  All arithmetic on
+// tensor elements happens in the kernels (slowmo_kernels.hip).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/slowmo.h"
+#include "slowmo_kernels.h"
+#include "slowmo_plan.h"
+
+using namespace slowmo;
+
+namespace {
+
+constexpr int kSlots = 4;            // ring of gradient-pointer tables
+constexpr size_t kSectionAlign = 256;
+
+thread_local std::string g_err = "";
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Byte offsets of the sections of the caller's workspace.
+struct Sections {
+  size_t x0, u, h, v, xtab, gtab[kSlots], lruns, tile_begin, oruns, total;
+};
+
+Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_lruns,
+                       size_t n_ltiles, size_t n_oruns) {
+  Sections s{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off += round_up(std::max<size_t>(bytes, 1), kSectionAlign);
+    return at;
+  };
+  const size_t arena = static_cast<size_t>(L.d_pad) * sizeof(float);
+  const size_t ptrs = static_cast<size_t>(c.m) * n_tensors * sizeof(void *);
+  s.x0 = take(arena);
+  s.u = take(arena);
+  s.h = take(arena * c.m);
+  s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
+  s.xtab = take(ptrs);
+  for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(ptrs);
+  s.lruns = take(n_lruns * sizeof(LocalRun));
+  s.tile_begin = take((n_ltiles + 1) * sizeof(int32_t));
+  s.oruns = take(n_oruns * sizeof(OuterRun));
+  s.total = off;
+  return s;
+}
+
+bool finite_pos(float v) { return std::isfinite(v) && v > 0.f; }
+bool unit_interval(float v) { return std::isfinite(v) && v >= 0.f && v < 1.f; }
+
+// Returns an empty string if cfg / tensor list are usable.
+std::string check_config(const slowmo_config *c, int32_t n_tensors, const int64_t *numel) {
+  if (!c) return "cfg is NULL";
+  if (!numel) return "numel is NULL";
+  if (n_tensors < 1) return "n_tensors must be >= 1";
+  if (c->m < 1 || c->m > SLOWMO_MAX_WORKERS) return "m must be in 1..SLOWMO_MAX_WORKERS";
+  if (c->tau < 1) return "tau must be >= 1";
+  if (!finite_pos(c->alpha)) return "alpha must be finite and > 0";
+  if (!unit_interval(c->beta)) return "beta must satisfy 0 <= beta < 1";
+  if (c->base != SLOWMO_SGD_NESTEROV && c->base != SLOWMO_ADAM) return "unknown base optimizer";
+  if (c->policy != SLOWMO_BUF_RESET && c->policy != SLOWMO_BUF_MAINTAIN)
+    return "unknown buffer policy";
+  if (c->grad_dtype != SLOWMO_F32 && c->grad_dtype != SLOWMO_BF16) return "unknown gradient dtype";
+  if (!(std::isfinite(c->weight_decay) && c->weight_decay >= 0.f))
+    return "weight_decay must be finite and >= 0";
+  if (c->base == SLOWMO_SGD_NESTEROV) {
+    if (!unit_interval(c->momentum)) return "momentum must satisfy 0 <= momentum < 1";
+  } else {
+    if (!unit_interval(c->beta1) || !unit_interval(c->beta2))
+      return "beta1 and beta2 must satisfy 0 <= . < 1";
+    if (!(std::isfinite(c->eps) && c->eps >= 0.f)) return "eps must be finite and >= 0";
+  }
+  int64_t total = 0;
+  for (int32_t j = 0; j < n_tensors; ++j) {
+    if (numel[j] < 0) return "numel has a negative entry";
+    if (numel[j] > (int64_t(1) << 40)) return "a tensor exceeds 2^40 elements";
+    total += numel[j];
+  }
+  if (total * c->m > (int64_t(1) << 44)) return "m * total elements exceeds 2^44";
+  if (static_cast<int64_t>(c->m) * n_tensors > (int64_t(1) << 24))
+    return "m * n_tensors exceeds 2^24";
+  return "";
+}
+
+int32_t env_flag(const char *name, int32_t dflt) {
+  const char *s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  return static_cast<int32_t>(std::strtol(s, nullptr, 10));
+}
+
+}  // namespace
+
+struct slowmo_ctx {
+  slowmo_config cfg{};
+  int32_t n_tensors = 0;
+  std::vector<int64_t> numel;
+  Layout layout;
+  int device = 0;
+
+  // sections of the caller's workspace (device pointers)
+  float *x0 = nullptr, *u = nullptr, *h = nullptr, *v = nullptr;
+  float **d_xtab = nullptr;
+  const void **d_gtab[kSlots] = {};
+  LocalRun *d_lruns = nullptr;
+  int32_t *d_tile_begin = nullptr;
+  OuterRun *d_oruns = nullptr;
+  int32_t n_ltiles = 0, n_otiles = 0;
+
+  // gradient-pointer table: pinned staging ring, one event per slot recorded
+  // after the slot's upload so that the host copy is not rewritten too early
+  const void **h_gtab[kSlots] = {};
+  hipEvent_t ev[kSlots] = {};
+  bool ev_used[kSlots] = {};
+  int cur_slot = -1;  // slot holding `last_grads`, -1 = none uploaded yet
+  std::vector<const void *> last_grads;
+
+  int64_t t = 0;  // outer iterations done
+  int32_t k = 0;  // local steps in the current outer iteration
+  int64_t l = 0;  // Adam steps counted by the bias correction
+  bool buffers_zero = true;  // h (and v) are to be read as zero by the next local step
+
+  LaunchTuning tune{};
+  std::string err;
+};
+
+namespace {
+
+slowmo_status fail(slowmo_ctx *ctx, slowmo_status st, const std::string &msg) {
+  if (ctx) {
+    ctx->err = msg;
+  } else {
+    g_err = msg;
+  }
+  return st;
+}
+
+slowmo_status fail_hip(slowmo_ctx *ctx, hipError_t e, const char *what) {
+  return fail(ctx, SLOWMO_ERR_HIP,
+              std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) + ")");
+}
+
+void release(slowmo_ctx *ctx) {
+  for (int i = 0; i < kSlots; ++i) {
+    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    if (ctx->h_gtab[i]) (void)hipHostFree(ctx->h_gtab[i]);
+  }
+  delete ctx;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *slowmo_version(void) { return "0.1.0 gfx950"; }
+
+const char *slowmo_last_error(const slowmo_ctx *ctx) {
+  return ctx ? ctx->err.c_str() : g_err.c_str();
+}
+
+size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int64_t *numel) {
+  std::string bad = check_config(cfg, n_tensors, numel);
+  if (!bad.empty()) {
+    g_err = bad;
+    return 0;
+  }
+  Layout L = make_layout(n_tensors, numel);
+  std::vector<PlanRun> lr, orr;
+  std::vector<int32_t> tb;
+  plan_local(cfg->m, n_tensors, numel, local_tile_elems(), lr, tb);
+  plan_outer(n_tensors, numel, outer_tile_elems(cfg->m), orr);
+  return make_sections(*cfg, n_tensors, L, lr.size(), tb.size() - 1, orr.size()).total;
+}
+
+int64_t slowmo_plan_local(int32_t m, int32_t n_tensors, const int64_t *numel, slowmo_plan_run *out,
+                          int64_t cap) {
+  if (m < 1 || n_tensors < 1 || !numel || cap < 0 || (cap > 0 && !out)) return -1;
+  for (int32_t j = 0; j < n_tensors; ++j)
+    if (numel[j] < 0) return -1;
+  std::vector<PlanRun> runs;
+  std::vector<int32_t> tb;
+  plan_local(m, n_tensors, numel, local_tile_elems(), runs, tb);
+  for (int64_t i = 0; i < std::min<int64_t>(cap, runs.size()); ++i) {
+    out[i] = {runs[i].tile, runs[i].worker, runs[i].tensor, runs[i].n, runs[i].offset};
+  }
+  return static_cast<int64_t>(runs.size());
+}
+
+int64_t slowmo_plan_outer(int32_t m, int32_t n_tensors, const int64_t *numel, slowmo_plan_run *out,
+                          int64_t cap) {
+  if (m < 1 || n_tensors < 1 || !numel || cap < 0 || (cap > 0 && !out)) return -1;
+  for (int32_t j = 0; j < n_tensors; ++j)
+    if (numel[j] < 0) return -1;
+  std::vector<PlanRun> runs;
+  plan_outer(n_tensors, numel, outer_tile_elems(m), runs);
+  for (int64_t i = 0; i < std::min<int64_t>(cap, runs.size()); ++i) {
+    out[i] = {runs[i].tile, runs[i].worker, runs[i].tensor, runs[i].n, runs[i].offset};
+  }
+  return static_cast<int64_t>(runs.size());
+}
+
+slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t n_tensors,
+                            const int64_t *numel, float *const *params, void *state,
+                            size_t state_bytes, void *stream_) {
+  if (!out) return fail(nullptr, SLOWMO_ERR_ARG, "out is NULL");
+  *out = nullptr;
+  std::string bad = check_config(cfg, n_tensors, numel);
+  if (!bad.empty()) return fail(nullptr, SLOWMO_ERR_ARG, bad);
+  if (!params) return fail(nullptr, SLOWMO_ERR_ARG, "params is NULL");
+  if (!state) return fail(nullptr, SLOWMO_ERR_ARG, "state is NULL");
+  if (reinterpret_cast<uintptr_t>(state) % kSectionAlign)
+    return fail(nullptr, SLOWMO_ERR_ALIGN, "state workspace must be 256-byte aligned");
+
+  const int32_t m = cfg->m;
+  const size_t n_ptr = static_cast<size_t>(m) * n_tensors;
+  struct Span {
+    uintptr_t lo, hi;
+  };
+  std::vector<Span> spans;
+  for (size_t i = 0; i < n_ptr; ++i) {
+    const int64_t n = numel[i % n_tensors];
+    if (n == 0) continue;
+    if (!params[i]) return fail(nullptr, SLOWMO_ERR_ARG, "a parameter pointer is NULL");
+    uintptr_t p = reinterpret_cast<uintptr_t>(params[i]);
+    if (p % sizeof(float)) return fail(nullptr, SLOWMO_ERR_ALIGN, "a parameter pointer is not 4-byte aligned");
+    spans.push_back({p, p + static_cast<uintptr_t>(n) * sizeof(float)});
+  }
+
+  slowmo_ctx *ctx = new (std::nothrow) slowmo_ctx;
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_NOMEM, "host allocation failed");
+  ctx->cfg = *cfg;
+  ctx->n_tensors = n_tensors;
+  ctx->numel.assign(numel, numel + n_tensors);
+  ctx->layout = make_layout(n_tensors, numel);
+  ctx->tune.local_grid = env_flag("SLOWMO_LOCAL_GRID", 0);
+  ctx->tune.outer_grid = env_flag("SLOWMO_OUTER_GRID", 0);
+  ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
+  ctx->tune.nontemporal = env_flag("SLOWMO_NT", 0) ? 1 : 0;
+
+  std::vector<PlanRun> lruns, oruns;
+  std::vector<int32_t> tile_begin;
+  plan_local(m, n_tensors, numel, local_tile_elems(), lruns, tile_begin);
+  plan_outer(n_tensors, numel, outer_tile_elems(m), oruns);
+  const Sections sec = make_sections(*cfg, n_tensors, ctx->layout, lruns.size(),
+                                     tile_begin.size() - 1, oruns.size());
+  if (state_bytes < sec.total) {
+    delete ctx;
+    return fail(nullptr, SLOWMO_ERR_NOMEM, "state workspace is smaller than slowmo_state_bytes()");
+  }
+  spans.push_back({reinterpret_cast<uintptr_t>(state), reinterpret_cast<uintptr_t>(state) + sec.total});
+  std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+  for (size_t i = 1; i < spans.size(); ++i) {
+    if (spans[i].lo < spans[i - 1].hi) {
+      delete ctx;
+      return fail(nullptr, SLOWMO_ERR_ARG, "parameter tensors overlap each other or the workspace");
+    }
+  }
+
+  // ---- from here on the device is needed -------------------------------------
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail_hip(nullptr, e, "hipGetDevice");
+  }
+  char *base = static_cast<char *>(state);
+  ctx->x0 = reinterpret_cast<float *>(base + sec.x0);
+  ctx->u = reinterpret_cast<float *>(base + sec.u);
+  ctx->h = reinterpret_cast<float *>(base + sec.h);
+  ctx->v = cfg->base == SLOWMO_ADAM ? reinterpret_cast<float *>(base + sec.v) : nullptr;
+  ctx->d_xtab = reinterpret_cast<float **>(base + sec.xtab);
+  for (int i = 0; i < kSlots; ++i) ctx->d_gtab[i] = reinterpret_cast<const void **>(base + sec.gtab[i]);
+  ctx->d_lruns = reinterpret_cast<LocalRun *>(base + sec.lruns);
+  ctx->d_tile_begin = reinterpret_cast<int32_t *>(base + sec.tile_begin);
+  ctx->d_oruns = reinterpret_cast<OuterRun *>(base + sec.oruns);
+  ctx->n_ltiles = static_cast<int32_t>(tile_begin.size()) - 1;
+  ctx->n_otiles = static_cast<int32_t>(oruns.size());
+
+#define CREATE_HIP(call, what)              \
+  do {                                      \
+    hipError_t e_ = (call);                 \
+    if (e_ != hipSuccess) {                 \
+      release(ctx);                         \
+      return fail_hip(nullptr, e_, what);   \
+    }                                       \
+  } while (0)
+
+  for (int i = 0; i < kSlots; ++i) {
+    CREATE_HIP(hipHostMalloc(reinterpret_cast<void **>(&ctx->h_gtab[i]), n_ptr * sizeof(void *),
+                             hipHostMallocDefault),
+               "hipHostMalloc");
+    CREATE_HIP(hipEventCreateWithFlags(&ctx->ev[i], hipEventDisableTiming), "hipEventCreate");
+  }
+
+  // device tables
+  std::vector<LocalRun> dl(lruns.size());
+  const Layout &L = ctx->layout;
+  for (size_t i = 0; i < lruns.size(); ++i) {
+    const PlanRun &r = lruns[i];
+    dl[i].x = params[static_cast<size_t>(r.worker) * n_tensors + r.tensor] + r.offset;
+    dl[i].so = static_cast<int64_t>(r.worker) * L.d_pad + L.arena_off[r.tensor] + r.offset;
+    dl[i].go = r.offset;
+    dl[i].slot = r.worker * n_tensors + r.tensor;
+    dl[i].n = r.n;
+  }
+  std::vector<OuterRun> dout(oruns.size());
+  for (size_t i = 0; i < oruns.size(); ++i) {
+    const PlanRun &r = oruns[i];
+    dout[i].fo = L.arena_off[r.tensor] + r.offset;
+    dout[i].eo = r.offset;
+    dout[i].tensor = r.tensor;
+    dout[i].n = r.n;
+  }
+  if (!dl.empty())
+    CREATE_HIP(hipMemcpyAsync(ctx->d_lruns, dl.data(), dl.size() * sizeof(LocalRun),
+                              hipMemcpyHostToDevice, stream),
+               "upload of the local-step tiling");
+  CREATE_HIP(hipMemcpyAsync(ctx->d_tile_begin, tile_begin.data(),
+                            tile_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream),
+             "upload of the tile index");
+  if (!dout.empty())
+    CREATE_HIP(hipMemcpyAsync(ctx->d_oruns, dout.data(), dout.size() * sizeof(OuterRun),
+                              hipMemcpyHostToDevice, stream),
+               "upload of the outer-step tiling");
+  CREATE_HIP(hipMemcpyAsync(ctx->d_xtab, params, n_ptr * sizeof(float *), hipMemcpyHostToDevice,
+                            stream),
+             "upload of the replica pointers");
+
+  // u_0 = 0, h = v = 0 (Algorithm 1, "Input"; Table C.1 caption)
+  const size_t arena = static_cast<size_t>(L.d_pad) * sizeof(float);
+  CREATE_HIP(hipMemsetAsync(ctx->x0, 0, arena, stream), "clearing x0");
+  CREATE_HIP(hipMemsetAsync(ctx->u, 0, arena, stream), "clearing u");
+  CREATE_HIP(hipMemsetAsync(ctx->h, 0, arena * m, stream), "clearing h");
+  if (ctx->v) CREATE_HIP(hipMemsetAsync(ctx->v, 0, arena * m, stream), "clearing v");
+  // common starting point x_{0,0}: worker 0's replica
+  for (int32_t j = 0; j < n_tensors; ++j) {
+    const size_t bytes = static_cast<size_t>(numel[j]) * sizeof(float);
+    if (!bytes) continue;
+    CREATE_HIP(hipMemcpyAsync(ctx->x0 + L.arena_off[j], params[j], bytes, hipMemcpyDeviceToDevice,
+                              stream),
+               "copy of x_{0,0} into x0");
+    for (int32_t w = 1; w < m; ++w) {
+      CREATE_HIP(hipMemcpyAsync(params[static_cast<size_t>(w) * n_tensors + j], params[j], bytes,
+                                hipMemcpyDeviceToDevice, stream),
+                 "copy of x_{0,0} into a replica");
+    }
+  }
+  // the host-side tables above go out of scope: wait for their uploads
+  CREATE_HIP(hipStreamSynchronize(stream), "hipStreamSynchronize");
+#undef CREATE_HIP
+
+  *out = ctx;
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!grads) return fail(ctx, SLOWMO_ERR_ARG, "grads is NULL");
+  if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
+  if (ctx->k >= ctx->cfg.tau)
+    return fail(ctx, SLOWMO_ERR_STATE, "tau local steps already taken: slowmo_outer_step is due");
+  const slowmo_config &c = ctx->cfg;
+  const size_t n_ptr = static_cast<size_t>(c.m) * ctx->n_tensors;
+  const size_t gsize = c.grad_dtype == SLOWMO_BF16 ? 2 : 4;
+  for (size_t i = 0; i < n_ptr; ++i) {
+    if (ctx->numel[i % ctx->n_tensors] == 0) continue;
+    if (!grads[i]) return fail(ctx, SLOWMO_ERR_ARG, "a gradient pointer is NULL");
+    if (reinterpret_cast<uintptr_t>(grads[i]) % gsize)
+      return fail(ctx, SLOWMO_ERR_ALIGN, "a gradient pointer is not aligned to its element size");
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+  // gradient-pointer table: reuse the uploaded one if the pointers did not change
+  int slot = ctx->cur_slot;
+  const bool same = slot >= 0 && ctx->last_grads.size() == n_ptr &&
+                    std::memcmp(ctx->last_grads.data(), grads, n_ptr * sizeof(void *)) == 0;
+  if (!same) {
+    slot = (ctx->cur_slot + 1) % kSlots;
+    if (ctx->ev_used[slot]) {
+      hipError_t e = hipEventSynchronize(ctx->ev[slot]);
+      if (e != hipSuccess) return fail_hip(ctx, e, "hipEventSynchronize");
+    }
+    std::memcpy(ctx->h_gtab[slot], grads, n_ptr * sizeof(void *));
+    hipError_t e = hipMemcpyAsync(ctx->d_gtab[slot], ctx->h_gtab[slot], n_ptr * sizeof(void *),
+                                  hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "upload of the gradient pointers");
+    e = hipEventRecord(ctx->ev[slot], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_used[slot] = true;
+    ctx->last_grads.assign(grads, grads + n_ptr);
+    ctx->cur_slot = slot;
+  }
+
+  LocalArgs a{};
+  a.runs = ctx->d_lruns;
+  a.tile_begin = ctx->d_tile_begin;
+  a.ntiles = ctx->n_ltiles;
+  a.gtab = ctx->d_gtab[slot];
+  a.h = ctx->h;
+  a.v = ctx->v;
+  a.lr = lr;
+  a.wd = c.weight_decay;
+  a.mu = c.momentum;
+  const int64_t l_next = ctx->l + 1;
+  if (c.base == SLOWMO_ADAM) {
+    a.b1 = c.beta1;
+    a.b2 = c.beta2;
+    a.omb1 = 1.0f - c.beta1;
+    a.omb2 = 1.0f - c.beta2;
+    a.eps = c.eps;
+    // 1 / (1 - beta^l), l counting this step, in fp64, rounded once
+    a.rc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta1), static_cast<double>(l_next))));
+    a.rc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta2), static_cast<double>(l_next))));
+  }
+  hipError_t e = launch_local_step(a, c.base, c.grad_dtype == SLOWMO_BF16, ctx->buffers_zero,
+                                   ctx->tune, stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
+  ctx->k += 1;
+  ctx->l = l_next;
+  ctx->buffers_zero = false;
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
+  if (ctx->k != ctx->cfg.tau)
+    return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
+  const slowmo_config &c = ctx->cfg;
+  OuterArgs a{};
+  a.runs = ctx->d_oruns;
+  a.ntiles = ctx->n_otiles;
+  a.xtab = ctx->d_xtab;
+  a.m = c.m;
+  a.n_tensors = ctx->n_tensors;
+  a.x0 = ctx->x0;
+  a.u = ctx->u;
+  a.lr = lr;
+  a.alpha_lr = c.alpha * lr;  // one fp32 rounding, as (alpha * gamma_t) in Eq. (3)
+  a.beta = c.beta;
+  a.m_f = static_cast<float>(c.m);
+  hipError_t e = launch_outer_step(a, ctx->tune, static_cast<hipStream_t>(stream_));
+  if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
+  ctx->k = 0;
+  ctx->t += 1;
+  if (c.policy == SLOWMO_BUF_RESET) {  // Algorithm 1 line 2 of the next outer iteration
+    ctx->buffers_zero = true;
+    ctx->l = 0;
+  }
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_destroy(slowmo_ctx *ctx) {
+  if (!ctx) return SLOWMO_OK;
+  release(ctx);
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_get_buffer(slowmo_ctx *ctx, int32_t which, int32_t worker, int32_t tensor,
+                                float **device_ptr) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!device_ptr) return fail(ctx, SLOWMO_ERR_ARG, "device_ptr is NULL");
+  if (tensor < 0 || tensor >= ctx->n_tensors) return fail(ctx, SLOWMO_ERR_ARG, "tensor index out of range");
+  const int64_t off = ctx->layout.arena_off[tensor];
+  switch (which) {
+    case SLOWMO_BUF_X0: *device_ptr = ctx->x0 + off; return SLOWMO_OK;
+    case SLOWMO_BUF_U: *device_ptr = ctx->u + off; return SLOWMO_OK;
+    case SLOWMO_BUF_H:
+    case SLOWMO_BUF_V: {
+      if (worker < 0 || worker >= ctx->cfg.m) return fail(ctx, SLOWMO_ERR_ARG, "worker index out of range");
+      float *b = which == SLOWMO_BUF_H ? ctx->h : ctx->v;
+      if (!b) return fail(ctx, SLOWMO_ERR_ARG, "this base optimizer has no v buffer");
+      *device_ptr = b + static_cast<int64_t>(worker) * ctx->layout.d_pad + off;
+      return SLOWMO_OK;
+    }
+    default: return fail(ctx, SLOWMO_ERR_ARG, "unknown buffer id");
+  }
+}
+
+slowmo_status slowmo_get_counters(const slowmo_ctx *ctx, int64_t *t, int32_t *k, int64_t *l) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (t) *t = ctx->t;
+  if (k) *k = ctx->k;
+  if (l) *l = ctx->l;
+  return SLOWMO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Launch interface between the C ABI (host logic) and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "slowmo_plan.h"
+
+namespace slowmo {
+
+struct LocalArgs {
+  const LocalRun *runs;        // device
+  const int32_t *tile_begin;   // device, ntiles + 1 entries
+  int32_t ntiles;
+  const void *const *gtab;     // device: m * n_tensors gradient pointers of this call
+  float *h;                    // device: h arena, m * d_pad
+  float *v;                    // device: v arena (Adam) or nullptr
+  float lr;
+  float wd;
+  // SGD with Nesterov momentum
+  float mu;
+  // Adam: factors and reciprocal bias corrections 1 / (1 - beta^l)
+  float b1, b2, omb1, omb2, rc1, rc2, eps;
+};
+
+struct OuterArgs {
+  const OuterRun *runs;        // device, one per tile
+  int32_t ntiles;
+  float *const *xtab;          // device: m * n_tensors replica pointers (worker-major)
+  int32_t m;
+  int32_t n_tensors;
+  float *x0;                   // device: arena d_pad
+  float *u;                    // device: arena d_pad
+  float lr;                    // gamma_t
+  float alpha_lr;              // alpha * gamma_t, rounded once to fp32
+  float beta;
+  float m_f;                   // (float) m
+};
+
+struct LaunchTuning {
+  int32_t local_grid;   // 0: one workgroup per tile; else a persistent grid of this many
+  int32_t outer_grid;
+  int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
+  int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
+};
+
+// base: 0 SGD-Nesterov, 1 Adam.  bf16: gradient dtype.  first: the stored
+// h (and v) are to be read as zero (first step after a reset / after create).
+hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first,
+                             const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+
+}  // namespace slowmo

@@ -1,0 +1,101 @@
+"""SlowMo: a thin holder around the C ABI for callers that keep their tensors
+in PyTorch.  PyTorch supplies device memory and the stream; every step of the
+method runs in libslowmo.so.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+_BASE = {"sgd_nesterov": B.SLOWMO_SGD_NESTEROV, "adam": B.SLOWMO_ADAM}
+_POLICY = {"reset": B.SLOWMO_BUF_RESET, "maintain": B.SLOWMO_BUF_MAINTAIN}
+_DTYPE = {"f32": B.SLOWMO_F32, "bf16": B.SLOWMO_BF16}
+_TORCH_GRAD = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def make_config(m: int, tau: int, alpha: float, beta: float, base: str = "sgd_nesterov",
+                policy: Optional[str] = None, grad_dtype: str = "f32", momentum: float = 0.0,
+                weight_decay: float = 0.0, beta1: float = 0.9, beta2: float = 0.999,
+                eps: float = 1e-8) -> B.slowmo_config:
+    if policy is None:
+        policy = "reset" if base == "sgd_nesterov" else "maintain"
+    return B.slowmo_config(m=m, tau=tau, alpha=alpha, beta=beta, base=_BASE[base],
+                           policy=_POLICY[policy], grad_dtype=_DTYPE[grad_dtype],
+                           momentum=momentum, weight_decay=weight_decay,
+                           beta1=beta1, beta2=beta2, eps=eps)
+
+
+class SlowMo:
+    """params[i][j]: worker i's replica of tensor j (fp32, contiguous, on one
+    GPU).  Worker 0's values become the common starting point."""
+
+    def __init__(self, params: Sequence[Sequence[torch.Tensor]], cfg: B.slowmo_config):
+        m, n_t = len(params), len(params[0])
+        assert m == cfg.m and all(len(p) == n_t for p in params)
+        dev = params[0][0].device
+        assert dev.type == "cuda", "parameters must live on the GPU"
+        for p in params:
+            for j, t in enumerate(p):
+                assert t.dtype == torch.float32 and t.is_contiguous() and t.device == dev
+                assert t.numel() == params[0][j].numel()
+        self.cfg, self.m, self.n_tensors, self.device = cfg, m, n_t, dev
+        self.params = [list(p) for p in params]          # keeps the memory alive
+        self.numel = [int(t.numel()) for t in params[0]]
+        self.grad_dtype = _TORCH_GRAD["bf16" if cfg.grad_dtype == B.SLOWMO_BF16 else "f32"]
+        nbytes = B.slowmo_state_bytes(cfg, self.numel)
+        if nbytes == 0:
+            raise B.SlowMoError(B.SLOWMO_ERR_ARG, B.slowmo_last_error(None))
+        self.state = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        ptrs = [t.data_ptr() if t.numel() else 0 for p in self.params for t in p]
+        with torch.cuda.device(dev):
+            self.ctx = B.slowmo_create(cfg, self.numel, ptrs, self.state.data_ptr(), nbytes,
+                                       torch.cuda.current_stream(dev).cuda_stream)
+        self._grad_key = None
+        self._grad_arr = None
+
+    def grad_pointer_array(self, grads: Sequence[Sequence[torch.Tensor]]):
+        """ctypes array of the m * n_tensors gradient addresses (reusable)."""
+        flat = []
+        for i, g in enumerate(grads):
+            for j, t in enumerate(g):
+                assert t.dtype == self.grad_dtype and t.is_contiguous() and t.device == self.device
+                assert t.numel() == self.numel[j]
+                flat.append(t.data_ptr() if t.numel() else 0)
+        assert len(flat) == self.m * self.n_tensors
+        return (C.c_void_p * len(flat))(*[C.c_void_p(v) if v else None for v in flat])
+
+    def local_step(self, grads, lr: float) -> None:
+        """grads: m lists of tensors, or an array from grad_pointer_array()."""
+        arr = grads if isinstance(grads, C.Array) else self.grad_pointer_array(grads)
+        B.slowmo_local_step(self.ctx, arr, lr, torch.cuda.current_stream(self.device).cuda_stream)
+
+    def outer_step(self, lr: float) -> None:
+        B.slowmo_outer_step(self.ctx, lr, torch.cuda.current_stream(self.device).cuda_stream)
+
+    def counters(self):
+        return B.slowmo_get_counters(self.ctx)
+
+    def buffer(self, which: str, tensor: int, worker: int = 0) -> torch.Tensor:
+        """A view (no copy) of x0 / u / h / v of one tensor inside the workspace."""
+        code = {"x0": B.SLOWMO_BUF_X0, "u": B.SLOWMO_BUF_U, "h": B.SLOWMO_BUF_H,
+                "v": B.SLOWMO_BUF_V}[which]
+        addr = B.slowmo_get_buffer(self.ctx, code, worker, tensor)
+        off = addr - self.state.data_ptr()
+        n = self.numel[tensor]
+        return self.state[off:off + 4 * n].view(torch.float32)
+
+    def close(self) -> None:
+        if getattr(self, "ctx", None) is not None:
+            torch.cuda.synchronize(self.device)
+            B.slowmo_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,63 @@
+"""Device side of the seeded input generator: fills GPU tensors with the same
+values generator.py computes on the host (bit for bit).  Test and benchmark
+infrastructure; no optimizer arithmetic."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(_HERE, "csrc", "gradgen.hip")
+LIB_PATH = os.path.join(_HERE, "libslowmo_inputs.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB_PATH) and \
+            os.path.getmtime(LIB_PATH) >= os.path.getmtime(SRC):
+        return LIB_PATH
+    hipcc = "/opt/rocm/bin/hipcc" if os.path.exists("/opt/rocm/bin/hipcc") else "hipcc"
+    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+           "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-x", "hip", SRC, "-o", LIB_PATH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    return LIB_PATH
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run slowmo_inputs.device.build()")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.slowmo_inputs_fill.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint64,
+                                            C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                            C.c_float, C.c_int32, C.c_void_p]
+        _lib.slowmo_inputs_fill.restype = C.c_int
+    return _lib
+
+
+def fill(out, first_index: int, seed: int, worker: int, step: int, scale: float,
+         n_workers: int = 1, worker_stride: int = 0) -> None:
+    """Fills a contiguous CUDA tensor (fp32 or bf16) with
+    scale * n(seed, worker, step, first_index + j).  With n_workers > 1, `out`
+    is 2-D [n_workers, n] and row w is filled for worker `worker + w`."""
+    import torch
+    assert out.is_cuda and out.is_contiguous()
+    bf16 = {torch.float32: 0, torch.bfloat16: 1}[out.dtype]
+    if n_workers > 1:
+        assert out.dim() == 2 and out.shape[0] == n_workers
+        n = out.shape[1]
+        worker_stride = worker_stride or out.stride(0)
+    else:
+        n = out.numel()
+    if n == 0:
+        return
+    rc = lib().slowmo_inputs_fill(out.data_ptr(), n, first_index, seed, worker, n_workers,
+                                  worker_stride, step, scale, bf16,
+                                  torch.cuda.current_stream(out.device).cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"slowmo_inputs_fill failed with hipError {rc}")

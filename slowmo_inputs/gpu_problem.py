@@ -1,0 +1,109 @@
+"""GPU-resident synthetic problem for a workload: parameter replicas, gradient
+buffers and index bookkeeping.  Allocation and input generation only -- the
+optimizer itself is not involved (callers hand these tensors to it)."""
+from __future__ import annotations
+
+from typing import List, Sequence
+
+import numpy as np
+
+from . import device as _device
+from . import generator as _gen
+from .workloads import Workload
+
+
+class GpuProblem:
+    """params[i][j]   worker i's replica of tensor j (fp32).  Worker 0 holds
+                      the seeded x_{0,0}; the others are zero until the
+                      optimizer's create call copies worker 0 into them.
+       grads[s][i][j] gradient buffers, `ring` independent sets.
+
+    param_layout / grad_layout:
+      "separate"  every tensor is its own allocation (the allocator aligns it);
+      "flat"      one allocation per worker, tensors back to back without
+                  padding, so tensors after an odd-sized one are not 16-byte
+                  aligned; gradients of one step are then produced by a single
+                  launch over all workers.
+    """
+
+    def __init__(self, w: Workload, device="cuda:0", ring: int = 1,
+                 param_layout: str = "separate", grad_layout: str = "flat"):
+        import torch
+        self.torch = torch
+        self.w = w
+        self.device = torch.device(device)
+        self.numel = w.numel
+        self.starts = w.tensor_starts
+        self.d = w.d
+        self.ring = ring
+        self.grad_layout = grad_layout
+        self.gdtype = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+        dev = self.device
+
+        def views(flat):
+            return [flat[int(s):int(s) + n] for s, n in zip(self.starts, self.numel)]
+
+        if param_layout == "separate":
+            self.params = [[torch.zeros(n, dtype=torch.float32, device=dev) for n in self.numel]
+                           for _ in range(w.m)]
+        else:
+            self._pflat = torch.zeros((w.m, max(self.d, 1)), dtype=torch.float32, device=dev)
+            self.params = [views(self._pflat[i]) for i in range(w.m)]
+        for j, t in enumerate(self.params[0]):          # x_{0,0} on worker 0
+            _device.fill(t, int(self.starts[j]), w.seed ^ _gen.PARAM_SEED_XOR, 0, 0, 0.01)
+
+        if grad_layout == "flat":
+            self._gflat = [torch.zeros((w.m, max(self.d, 1)), dtype=self.gdtype, device=dev)
+                           for _ in range(ring)]
+            self.grads = [[views(g[i]) for i in range(w.m)] for g in self._gflat]
+        else:
+            self.grads = [[[torch.zeros(n, dtype=self.gdtype, device=dev) for n in self.numel]
+                           for _ in range(w.m)] for _ in range(ring)]
+
+    def fill_grads(self, slot: int, step: int) -> None:
+        """Gradients of global step `step` (= t * tau + k) into ring slot `slot`."""
+        w = self.w
+        if self.d == 0:
+            return
+        if self.grad_layout == "flat":
+            g = self._gflat[slot]
+            _device.fill(g if w.m > 1 else g[0], 0, w.seed, 0, step, w.sigma, n_workers=w.m)
+        else:
+            for i in range(w.m):
+                for j, t in enumerate(self.grads[slot][i]):
+                    _device.fill(t, int(self.starts[j]), w.seed, i, step, w.sigma)
+
+    # ---- index bookkeeping ----------------------------------------------------
+    def locate(self, index: np.ndarray):
+        """(tensor, offset) of global element indices."""
+        index = np.asarray(index, dtype=np.int64)
+        ends = self.starts + np.asarray(self.numel, dtype=np.int64)
+        tensor = np.searchsorted(ends, index, side="right")
+        return tensor, index - self.starts[tensor]
+
+    def gather(self, tensors: Sequence, index: np.ndarray) -> np.ndarray:
+        """Values of a per-tensor list (e.g. one worker's replica) at global
+        element indices, as a host float32 array."""
+        torch = self.torch
+        tensor, off = self.locate(index)
+        out = np.empty(index.shape, dtype=np.float32)
+        for j in np.unique(tensor):
+            sel = np.nonzero(tensor == j)[0]
+            idx = torch.from_numpy(off[sel]).to(self.device)
+            out[sel] = tensors[int(j)].reshape(-1)[idx].to(torch.float32).cpu().numpy()
+        return out
+
+    def sample_indices(self, n_random: int, edges: Sequence[int] = (), halo: int = 8,
+                       seed: int = 0) -> np.ndarray:
+        """Sorted unique global indices: a halo around every tensor boundary
+        and around the given extra edges (e.g. tile boundaries), the two ends
+        of the range, and n_random uniformly drawn indices."""
+        pts: List[np.ndarray] = []
+        marks = np.concatenate([self.starts, self.starts + np.asarray(self.numel, np.int64),
+                                np.asarray(list(edges), dtype=np.int64)])
+        for d in range(-halo, halo):
+            pts.append(marks + d)
+        rng = np.random.default_rng(seed)
+        pts.append(rng.integers(0, max(self.d, 1), size=n_random, dtype=np.int64))
+        idx = np.unique(np.concatenate(pts))
+        return idx[(idx >= 0) & (idx < self.d)]

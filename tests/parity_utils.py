@@ -1,0 +1,136 @@
+"""Shared helpers of the GPU parity tests: run a workload through the HIP
+library, run the CPU oracle on the same seeded inputs (all elements, or an
+index subset -- every element evolves independently of the others, so a subset
+is exact), and compare within the stated tolerances."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import slowmo_oracle as O
+from slowmo_inputs import generator as G
+
+
+# ---- tolerances ---------------------------------------------------------------
+# Parameters (replicas, x0): the bound the task states, |d| <= 1e-5 (1 + |x|).
+# u is (x0 - xbar)/gamma accumulated (Eq. (2)): it carries x's rounding error
+# divided by gamma, so the same bound is applied to gamma*u, which has x's units.
+# h, v are compared relatively (they are inputs of the next step, not results).
+def assert_params_close(got, want, what):
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(np.asarray(got, dtype=np.float64) - want) / (1.0 + np.abs(want))
+    assert err.max(initial=0.0) <= 1e-5, f"{what}: max |d|/(1+|x|) = {err.max():.3e}"
+    return float(err.max(initial=0.0))
+
+
+def assert_u_close(got, want, lr, what):
+    want = np.asarray(want, dtype=np.float64)
+    err = lr * np.abs(np.asarray(got, dtype=np.float64) - want) / (1.0 + lr * np.abs(want))
+    assert err.max(initial=0.0) <= 1e-5, f"{what}: max = {err.max():.3e}"
+    return float(err.max(initial=0.0))
+
+
+def assert_buffer_close(got, want, what, rtol=1e-5, atol=1e-7):
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(np.asarray(got, dtype=np.float64) - want)
+    bound = atol + rtol * np.abs(want)
+    assert np.all(err <= bound), f"{what}: max err {err.max():.3e}"
+
+
+# ---- oracle side ----------------------------------------------------------------
+def make_oracle(w, index, prec="f64"):
+    return O.SlowMoOracle(G.initial_params(w.seed, index), m=w.m, tau=w.tau,
+                          alpha=w.f32("alpha"), beta=w.f32("beta"), base=w.base,
+                          policy=w.policy, momentum=w.f32("momentum"),
+                          weight_decay=w.f32("weight_decay"), beta1=w.f32("beta1"),
+                          beta2=w.f32("beta2"), eps=w.f32("eps"), prec=prec)
+
+
+def oracle_grads(w, index, step):
+    return np.stack([G.gradient(w.seed, i, step, index, w.sigma, bf16=(w.grad_dtype == "bf16"))
+                     for i in range(w.m)])
+
+
+def run_oracle(w, index, rounds, prec="f64"):
+    """Returns (oracle after the last outer step, snapshot taken after the
+    local steps of the last round: dict with x, h, v)."""
+    o = make_oracle(w, index, prec)
+    lr = w.f32("lr")
+    snap = None
+    for t in range(rounds):
+        for k in range(w.tau):
+            o.local_step(oracle_grads(w, index, t * w.tau + k), lr)
+        if t == rounds - 1:
+            snap = dict(x=o.x.copy(), h=o.h.copy(), v=None if o.v is None else o.v.copy())
+        o.outer_step(lr)
+    return o, snap
+
+
+# ---- GPU side -------------------------------------------------------------------
+def make_gpu(w, prob):
+    from paper_1910_00643_amd.optimizer import SlowMo, make_config
+    cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
+                      policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
+                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
+    return SlowMo(prob.params, cfg)
+
+
+def run_gpu(w, prob, opt, rounds, index):
+    """Runs `rounds` outer iterations; gradients are regenerated before every
+    local step (ring slots in turn).  Returns the snapshot (x, h, v at the
+    sampled indices) taken after the local steps of the last round."""
+    lr = w.lr
+    arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(prob.ring)]
+    snap = None
+    step = 0
+    for t in range(rounds):
+        for k in range(w.tau):
+            s = step % prob.ring
+            prob.fill_grads(s, step)
+            opt.local_step(arrays[s], lr)
+            step += 1
+        if t == rounds - 1:
+            snap = gpu_state(w, prob, opt, index, with_outer=False)
+        opt.outer_step(lr)
+    return snap
+
+
+def gpu_state(w, prob, opt, index, with_outer=True):
+    nt = len(prob.numel)
+    out = dict(
+        x=np.stack([prob.gather(prob.params[i], index) for i in range(w.m)]),
+        h=np.stack([prob.gather([opt.buffer("h", j, i) for j in range(nt)], index)
+                    for i in range(w.m)]))
+    out["v"] = None
+    if w.base == "adam":
+        out["v"] = np.stack([prob.gather([opt.buffer("v", j, i) for j in range(nt)], index)
+                             for i in range(w.m)])
+    if with_outer:
+        out["x0"] = prob.gather([opt.buffer("x0", j) for j in range(nt)], index)
+        out["u"] = prob.gather([opt.buffer("u", j) for j in range(nt)], index)
+    return out
+
+
+def compare_run(w, prob, opt, index, rounds, bitwise_f32=False):
+    """Full comparison of a finished GPU run against the oracle on `index`."""
+    lr = w.f32("lr")
+    snap = run_gpu(w, prob, opt, rounds, index)
+    final = gpu_state(w, prob, opt, index)
+    o64, s64 = run_oracle(w, index, rounds, "f64")
+    worst = {}
+    worst["x_local"] = assert_params_close(snap["x"], s64["x"], "replicas after the local steps")
+    assert_buffer_close(snap["h"], s64["h"], "h after the local steps")
+    if w.base == "adam":
+        assert_buffer_close(snap["v"], s64["v"], "v after the local steps", atol=1e-9)
+    worst["x0"] = assert_params_close(final["x0"], o64.x0, "x0 after the run")
+    worst["u"] = assert_u_close(final["u"], o64.u, lr, "u after the run")
+    for i in range(w.m):                 # Section 2: identical on all workers
+        assert np.array_equal(final["x"][i], final["x0"]), f"replica {i} differs from x0"
+    if bitwise_f32:
+        # The SGD and outer kernels round every product and sum separately in
+        # the order of the formulas, as the fp32 build of the oracle does.
+        o32, s32 = run_oracle(w, index, rounds, "f32")
+        assert np.array_equal(snap["x"], s32["x"]), "replicas differ from the fp32 oracle"
+        assert np.array_equal(snap["h"], s32["h"])
+        assert np.array_equal(final["x0"], o32.x0), "x0 differs from the fp32 oracle"
+        assert np.array_equal(final["u"], o32.u), "u differs from the fp32 oracle"
+    return worst

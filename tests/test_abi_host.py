@@ -1,0 +1,154 @@
+"""The C ABI without a GPU: the library loads, exports every declared symbol,
+rejects bad arguments before touching the device, and tiles correctly."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1910_00643_amd as P
+from paper_1910_00643_amd import binding as B
+from paper_1910_00643_amd.optimizer import make_config
+from slowmo_inputs import shapes as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "slowmo.h")).read()
+    declared = set(re.findall(r"\b(slowmo_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in P.slowmo_version()
+
+
+def test_config_struct_matches_header_layout():
+    assert C.sizeof(B.slowmo_config) == 48
+    assert C.sizeof(B.slowmo_plan_run) == 24
+
+
+def _cfg(**kw):
+    base = dict(m=4, tau=12, alpha=1.0, beta=0.7, momentum=0.9, weight_decay=1e-4)
+    base.update(kw)
+    return make_config(**base)
+
+
+@pytest.mark.parametrize("kw", [dict(m=0), dict(m=B.SLOWMO_MAX_WORKERS + 1), dict(tau=0),
+                                dict(alpha=0.0), dict(alpha=float("inf")), dict(beta=1.0),
+                                dict(beta=-0.1), dict(momentum=1.0), dict(weight_decay=-1.0),
+                                dict(base="adam", beta1=1.0), dict(base="adam", eps=-1.0),
+                                dict(beta=float("nan"))])
+def test_bad_hyperparameters_are_rejected(kw):
+    cfg = _cfg(**kw)
+    assert P.slowmo_state_bytes(cfg, [16]) == 0
+    with pytest.raises(P.SlowMoError) as e:
+        P.slowmo_create(cfg, [16], [256] * cfg.m, 4096, 1 << 20)
+    assert e.value.status == B.SLOWMO_ERR_ARG and e.value.message
+
+
+def test_bad_enums_and_sizes_are_rejected():
+    cfg = _cfg()
+    for field in ("base", "policy", "grad_dtype"):
+        bad = _cfg()
+        setattr(bad, field, 7)
+        assert P.slowmo_state_bytes(bad, [16]) == 0
+    assert P.slowmo_state_bytes(cfg, [16, -1]) == 0
+    assert P.slowmo_state_bytes(cfg, []) == 0
+    assert P.slowmo_state_bytes(cfg, [16]) > 0
+
+
+def test_create_rejects_bad_pointers_before_using_the_device():
+    cfg = _cfg(m=2)
+    n = P.slowmo_state_bytes(cfg, [64, 8])
+    good = [0x10000, 0x20000, 0x30000, 0x40000]
+    state = 0x100000
+
+    def create(params=good, st=state, nbytes=n):
+        P.slowmo_create(cfg, [64, 8], params, st, nbytes)
+
+    with pytest.raises(P.SlowMoError) as e:
+        create(params=[0x10000, 0, 0x30000, 0x40000])
+    assert e.value.status == B.SLOWMO_ERR_ARG
+    with pytest.raises(P.SlowMoError) as e:
+        create(params=[0x10002, 0x20000, 0x30000, 0x40000])
+    assert e.value.status == B.SLOWMO_ERR_ALIGN
+    with pytest.raises(P.SlowMoError) as e:
+        create(st=state + 16)
+    assert e.value.status == B.SLOWMO_ERR_ALIGN
+    with pytest.raises(P.SlowMoError) as e:
+        create(nbytes=n - 1)
+    assert e.value.status == B.SLOWMO_ERR_NOMEM
+    with pytest.raises(P.SlowMoError) as e:
+        create(params=[0x10000, 0x20000, 0x10080, 0x40000])     # replicas overlap
+    assert e.value.status == B.SLOWMO_ERR_ARG and "overlap" in e.value.message
+    with pytest.raises(P.SlowMoError) as e:
+        create(params=[0x10000, 0x20000, 0x30000, state + 64])  # overlaps the workspace
+    assert e.value.status == B.SLOWMO_ERR_ARG
+    with pytest.raises(P.SlowMoError) as e:
+        create(st=0)
+    assert e.value.status == B.SLOWMO_ERR_ARG
+
+
+def test_null_context_calls_fail_cleanly():
+    lib = B.lib()
+    assert lib.slowmo_local_step(None, None, 0.1, None) == B.SLOWMO_ERR_ARG
+    assert lib.slowmo_outer_step(None, 0.1, None) == B.SLOWMO_ERR_ARG
+    assert lib.slowmo_destroy(None) == B.SLOWMO_OK
+    assert lib.slowmo_get_counters(None, None, None, None) == B.SLOWMO_ERR_ARG
+    assert "NULL" in P.slowmo_last_error(None)
+
+
+def _check_cover(runs, m_eff, numel, local):
+    """Every (worker, tensor, element) appears in exactly one run."""
+    seen = {}
+    for tile, worker, tensor, n, off in runs:
+        assert n > 0 and off >= 0 and off + n <= numel[tensor]
+        key = (worker, tensor)
+        seen.setdefault(key, []).append((off, n))
+    workers = range(m_eff) if local else [-1]
+    for wk in workers:
+        for j, total in enumerate(numel):
+            pieces = sorted(seen.get((wk, j), []))
+            pos = 0
+            for off, n in pieces:
+                assert off == pos, (wk, j, off, pos)
+                pos += n
+            assert pos == total, (wk, j)
+            for off, n in pieces[1:]:
+                assert off % 4 == 0          # a tensor continues 16-byte aligned
+
+
+@pytest.mark.parametrize("shapes,m", [(S.ragged_mini(), 3), (S.resnet50(), 32),
+                                      (S.resnet18(), 8), (S.tiny_flat(), 4)])
+def test_tiling_covers_everything_once(shapes, m):
+    numel = S.numels(shapes)
+    local = P.slowmo_plan_local(m, numel)
+    _check_cover(local, m, numel, local=True)
+    outer = P.slowmo_plan_outer(m, numel)
+    _check_cover(outer, m, numel, local=False)
+    # tiles are numbered consecutively, runs of a tile are adjacent
+    tiles = [r[0] for r in local]
+    assert tiles == sorted(tiles) and tiles[0] == 0 and len(set(tiles)) == tiles[-1] + 1
+    assert [r[0] for r in outer] == list(range(len(outer)))
+    # balance: no tile exceeds the budget; few tiles are much below it
+    per_tile = np.bincount(tiles, weights=[max(r[3], 512) for r in local])
+    budget = per_tile.max()
+    assert budget <= 65536
+    runs_per_tile = np.bincount(tiles)
+    assert runs_per_tile.max() <= budget // 512
+    if sum(numel) * m > 50 * budget:
+        assert np.mean(per_tile >= 0.5 * budget) > 0.9
+
+
+def test_plan_of_transformer_big_and_1e9():
+    numel = S.numels(S.transformer_big())
+    assert len(P.slowmo_plan_local(1, numel)) > 0
+    lib = B.lib()
+    arr = (C.c_int64 * 1)(10 ** 9)
+    n_local = lib.slowmo_plan_local(8, 1, arr, None, 0)
+    n_outer = lib.slowmo_plan_outer(8, 1, arr, None, 0)
+    assert n_local >= 8 * 10 ** 9 // 65536 and n_outer >= 10 ** 9 // (1 << 20)
+    assert lib.slowmo_plan_local(0, 1, arr, None, 0) == -1
