@@ -14,7 +14,8 @@ from slowmo_inputs import generator as G
 # Parameters (replicas, x0): the bound the task states, |d| <= 1e-5 (1 + |x|).
 # u is (x0 - xbar)/gamma accumulated (Eq. (2)): it carries x's rounding error
 # divided by gamma, so the same bound is applied to gamma*u, which has x's units.
-# h, v are compared relatively (they are inputs of the next step, not results).
+# h and v are sums of gradient-sized (sigma) resp. sigma^2-sized terms: the same
+# relative bound with sigma resp. sigma^2 as the unit.
 def assert_params_close(got, want, what):
     want = np.asarray(want, dtype=np.float64)
     err = np.abs(np.asarray(got, dtype=np.float64) - want) / (1.0 + np.abs(want))
@@ -29,11 +30,10 @@ def assert_u_close(got, want, lr, what):
     return float(err.max(initial=0.0))
 
 
-def assert_buffer_close(got, want, what, rtol=1e-5, atol=1e-7):
+def assert_buffer_close(got, want, what, unit):
     want = np.asarray(want, dtype=np.float64)
-    err = np.abs(np.asarray(got, dtype=np.float64) - want)
-    bound = atol + rtol * np.abs(want)
-    assert np.all(err <= bound), f"{what}: max err {err.max():.3e}"
+    err = np.abs(np.asarray(got, dtype=np.float64) - want) / (unit + np.abs(want))
+    assert err.max(initial=0.0) <= 1e-5, f"{what}: max |d|/({unit:g}+|.|) = {err.max():.3e}"
 
 
 # ---- oracle side ----------------------------------------------------------------
@@ -50,19 +50,28 @@ def oracle_grads(w, index, step):
                      for i in range(w.m)])
 
 
-def run_oracle(w, index, rounds, prec="f64"):
-    """Returns (oracle after the last outer step, snapshot taken after the
-    local steps of the last round: dict with x, h, v)."""
-    o = make_oracle(w, index, prec)
+def run_oracles(w, index, rounds, precs=("f64",)):
+    """Runs the oracle builds named in `precs` side by side on the same
+    gradients.  Returns {prec: (oracle after the last outer step, snapshot
+    taken after the local steps of the last round: dict with x, h, v)}."""
+    os_ = {p: make_oracle(w, index, p) for p in precs}
     lr = w.f32("lr")
-    snap = None
+    snaps = {}
     for t in range(rounds):
         for k in range(w.tau):
-            o.local_step(oracle_grads(w, index, t * w.tau + k), lr)
-        if t == rounds - 1:
-            snap = dict(x=o.x.copy(), h=o.h.copy(), v=None if o.v is None else o.v.copy())
-        o.outer_step(lr)
-    return o, snap
+            g = oracle_grads(w, index, t * w.tau + k)
+            for o in os_.values():
+                o.local_step(g, lr)
+        for p, o in os_.items():
+            if t == rounds - 1:
+                snaps[p] = dict(x=o.x.copy(), h=o.h.copy(),
+                                v=None if o.v is None else o.v.copy())
+            o.outer_step(lr)
+    return {p: (os_[p], snaps[p]) for p in precs}
+
+
+def run_oracle(w, index, rounds, prec="f64"):
+    return run_oracles(w, index, rounds, (prec,))[prec]
 
 
 # ---- GPU side -------------------------------------------------------------------
@@ -115,12 +124,13 @@ def compare_run(w, prob, opt, index, rounds, bitwise_f32=False):
     lr = w.f32("lr")
     snap = run_gpu(w, prob, opt, rounds, index)
     final = gpu_state(w, prob, opt, index)
-    o64, s64 = run_oracle(w, index, rounds, "f64")
+    res = run_oracles(w, index, rounds, ("f64", "f32") if bitwise_f32 else ("f64",))
+    o64, s64 = res["f64"]
     worst = {}
     worst["x_local"] = assert_params_close(snap["x"], s64["x"], "replicas after the local steps")
-    assert_buffer_close(snap["h"], s64["h"], "h after the local steps")
+    assert_buffer_close(snap["h"], s64["h"], "h after the local steps", unit=w.sigma)
     if w.base == "adam":
-        assert_buffer_close(snap["v"], s64["v"], "v after the local steps", atol=1e-9)
+        assert_buffer_close(snap["v"], s64["v"], "v after the local steps", unit=w.sigma ** 2)
     worst["x0"] = assert_params_close(final["x0"], o64.x0, "x0 after the run")
     worst["u"] = assert_u_close(final["u"], o64.u, lr, "u after the run")
     for i in range(w.m):                 # Section 2: identical on all workers
@@ -128,7 +138,7 @@ def compare_run(w, prob, opt, index, rounds, bitwise_f32=False):
     if bitwise_f32:
         # The SGD and outer kernels round every product and sum separately in
         # the order of the formulas, as the fp32 build of the oracle does.
-        o32, s32 = run_oracle(w, index, rounds, "f32")
+        o32, s32 = res["f32"]
         assert np.array_equal(snap["x"], s32["x"]), "replicas differ from the fp32 oracle"
         assert np.array_equal(snap["h"], s32["h"])
         assert np.array_equal(final["x0"], o32.x0), "x0 differs from the fp32 oracle"
