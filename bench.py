@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the Slow Momentum hot path on one MI355X.
+
+A "step" is one outer iteration (round) of Algorithm 1 over the whole tensor
+list: tau local steps on all m workers plus the outer step.  All inputs
+(replicas, state, tau pre-generated gradient sets) are resident in HBM before
+the timed region starts; gradients stand in for the backward pass and are not
+regenerated inside it.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
+# profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def local_bytes_per_update(w, first: bool) -> int:
+    """Algorithmic HBM bytes of one base-optimizer update of one (worker,
+    element): x, h (and v) read and written, the gradient read; the first step
+    after a reset does not read the buffers."""
+    g = 2 if w.grad_dtype == "bf16" else 4
+    nbuf = 2 if w.base == "adam" else 1
+    reads = 4 + (0 if first else 4 * nbuf) + g
+    writes = 4 + 4 * nbuf
+    return reads + writes
+
+
+def outer_bytes_per_element(w) -> int:
+    return 8 * w.m + 16         # m replicas + x0 + u read, the same written
+
+
+def round_bytes(w) -> int:
+    reset = w.policy == "reset"
+    per_worker_elem = (local_bytes_per_update(w, reset) +
+                       (w.tau - 1) * local_bytes_per_update(w, False))
+    return w.d * (w.m * per_worker_elem + outer_bytes_per_element(w))
+
+
+def build_problem(w, ring):
+    import torch
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from slowmo_inputs.gpu_problem import GpuProblem
+    from paper_1910_00643_amd.optimizer import SlowMo, make_config
+    prob = GpuProblem(w, "cuda:0", ring=ring)
+    cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
+                      policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
+                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
+    opt = SlowMo(prob.params, cfg)
+    for s in range(ring):
+        prob.fill_grads(s, s)
+    torch.cuda.synchronize()
+    return prob, opt
+
+
+def run_rounds(w, opt, arrays, rounds, events=None):
+    """`rounds` outer iterations.  With `events`, brackets every call with HIP
+    events on the stream the kernels are launched on (torch's current one)."""
+    import torch
+    ring = len(arrays)
+    for _ in range(rounds):
+        for k in range(w.tau):
+            if events is not None:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            opt.local_step(arrays[k % ring], w.lr)
+            if events is not None:
+                b.record()
+                events["local_first" if (k == 0 and w.policy == "reset") else "local"].append((a, b))
+        if events is not None:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+        opt.outer_step(w.lr)
+        if events is not None:
+            b.record()
+            events["outer"].append((a, b))
+
+
+def time_workload(w, steps, warmup, ring=None):
+    import torch
+    ring = ring or w.tau
+    prob, opt = build_problem(w, ring)
+    arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(ring)]
+    run_rounds(w, opt, arrays, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_rounds(w, opt, arrays, steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    # second pass: per-kernel durations from HIP events around every launch
+    events = {"local": [], "local_first": [], "outer": []}
+    run_rounds(w, opt, arrays, steps, events)
+    torch.cuda.synchronize()
+    kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
+               for k, v in events.items()}
+    opt.close()
+    del prob, opt
+    torch.cuda.empty_cache()
+    return wall, kern_ms
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The fp32 build of the CPU oracle, as it stands, timed on this host's
+    cores over one outer iteration of a contiguous slice of the workload."""
+    import numpy as np
+    import torch
+    from oracle import slowmo_oracle as O
+    from slowmo_inputs import device, generator as G
+    lib = O.load("f32")
+    cores = int(lib.oracle_num_threads())
+    bf16 = w.grad_dtype == "bf16"
+
+    def one_round(n):
+        idx = np.arange(n, dtype=np.int64)
+        o = O.SlowMoOracle(G.initial_params(w.seed, idx), m=w.m, tau=w.tau, alpha=w.f32("alpha"),
+                           beta=w.f32("beta"), base=w.base, policy=w.policy,
+                           momentum=w.f32("momentum"), weight_decay=w.f32("weight_decay"),
+                           beta1=w.f32("beta1"), beta2=w.f32("beta2"), eps=w.f32("eps"), prec="f32")
+        g_dev = torch.empty((w.m, n), dtype=torch.bfloat16 if bf16 else torch.float32,
+                            device="cuda:0")
+        spent = 0.0
+        for k in range(w.tau):
+            device.fill(g_dev if w.m > 1 else g_dev[0], 0, w.seed, 0, k, w.sigma, n_workers=w.m)
+            g = g_dev.to(torch.float32).cpu().numpy()      # gradient generation is not timed
+            t0 = time.perf_counter()
+            o.local_step(g, w.f32("lr"))
+            spent += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        o.outer_step(w.f32("lr"))
+        spent += time.perf_counter() - t0
+        return spent
+
+    n = min(w.d, 1 << 16)
+    t = one_round(n)                                        # warm-up and rate estimate
+    rate = w.m * n * w.tau / max(t, 1e-9)
+    n = int(min(w.d, max(n, rate * budget_s / (w.m * w.tau)), (4 << 30) // (16 * w.m)))
+    t = one_round(n)
+    return {"value": w.m * n * w.tau / t, "unit": "updates/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp32 build of the oracle (gcc -O2, OpenMP over elements), one outer "
+                      f"iteration (tau={w.tau} local steps + outer step) of the first {n} "
+                      f"elements of the flat range on all m={w.m} workers, {t:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["tiny", "resnet18", "resnet50", "transformer_big", "stress"])
+    ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (m logical workers share it); "
+                 "--gpus N with N > 1 is not supported and no multi-GPU figure is reported")
+    import torch
+    from slowmo_inputs import workloads as W
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    w = W.BY_NAME[args.workload]()
+    ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
+                            2 if w.name == "stress" else w.tau)
+    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring)
+    ms_per_step = 1e3 * wall / args.steps
+    value = w.updates_per_round * args.steps / wall
+    local_bytes = local_bytes_per_update(w, False) * w.m * w.d
+    achieved = local_bytes / (kern_ms["local"] * 1e-3) / 1e9
+    out = {
+        "metric": "param-element updates/s (m*d*tau per round)",
+        "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}-shaped tensor list ({len(w.numel)} tensors, d={w.d}), "
+                               f"m={w.m}, tau={w.tau}, base={w.base}, grads={w.grad_dtype}, "
+                               f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}",
+                   "step": "one outer iteration: tau local steps on all m workers + outer step",
+                   "gradient_sets_resident": ring},
+        "hbm_gbps_whole_round": round_bytes(w) / wall * args.steps / 1e9,
+        "hbm_frac_whole_round": round_bytes(w) / wall * args.steps / 1e9 / HBM_PEAK_GBPS,
+        "kernel_ms": kern_ms,
+        "roofline": {"bound": "hbm", "kernel": "k_local_step (steady state)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "algorithmic_bytes_per_launch": local_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+    }
+    if kern_ms["outer"]:
+        ob = outer_bytes_per_element(w) * w.d
+        out["outer_kernel"] = {"achieved": ob / (kern_ms["outer"] * 1e-3) / 1e9, "unit": "GB/s",
+                               "frac": ob / (kern_ms["outer"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                               "algorithmic_bytes_per_launch": ob}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

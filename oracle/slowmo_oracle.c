@@ -42,6 +42,14 @@
 /* Size in bytes of REAL, so the caller can check which build it loaded. */
 int oracle_real_bytes(void) { return (int)sizeof(REAL); }
 
+/* Threads the "parallel for" loops below run on (for the timing report). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
+
 /*
  * One base-optimizer step of one worker, SGD with Nesterov momentum
  * (Table C.1, row "SGD"; Algorithm 1 line 4):

@@ -63,6 +63,7 @@ def load(prec: str = "f64", path: Optional[str] = None) -> C.CDLL:
     want = 8 if prec == "f64" else 4
     lib.oracle_real_bytes.restype = C.c_int
     assert lib.oracle_real_bytes() == want, "oracle library has the wrong precision"
+    lib.oracle_num_threads.restype = C.c_int
     p, i64, dbl = C.c_void_p, C.c_int64, C.c_double
     lib.oracle_sgd_nesterov_step.argtypes = [p, p, p, i64, dbl, dbl, dbl]
     lib.oracle_sgd_nesterov_step.restype = None
