@@ -159,15 +159,16 @@ slowmo_status slowmo_get_counters(const slowmo_ctx *ctx, int64_t *t, int32_t *k,
 
 /*
  * Host-only view of the tiling (tests of the host logic; needs no device).
- * One record per contiguous run of elements a workgroup processes.  The
- * local-step tiling covers every (worker, tensor, element) exactly once; the
- * outer-step tiling covers every (tensor, element) exactly once (worker = -1).
- * Runs continue a tensor only at element offsets that are multiples of 4.
+ * One record per tile: the contiguous run of elements of one tensor that one
+ * workgroup processes.  The local-step tiling covers every (worker, tensor,
+ * element) exactly once; the outer-step tiling covers every (tensor, element)
+ * exactly once (worker = -1).  Tiles start at element offsets that are
+ * multiples of 4, so a tile is 16-byte aligned whenever its tensor is.
  * Writes at most `cap` records to `out` (may be NULL with cap 0) and returns
  * the total number of records, or -1 on invalid arguments.
  */
 typedef struct {
-  int32_t tile;    /* workgroup-sized unit of work this run belongs to */
+  int32_t tile;    /* index of the tile in launch order */
   int32_t worker;  /* -1 for the outer step */
   int32_t tensor;
   int32_t n;       /* elements in the run */

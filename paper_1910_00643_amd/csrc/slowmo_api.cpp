@@ -29,11 +29,11 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab, gtab[kSlots], lruns, tile_begin, oruns, total;
+  size_t x0, u, h, v, xtab_t, gtab[kSlots], slots, ltiles, otiles, total;
 };
 
-Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_lruns,
-                       size_t n_ltiles, size_t n_oruns) {
+Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
+                       size_t n_otiles) {
   Sections s{};
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -42,16 +42,16 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
     return at;
   };
   const size_t arena = static_cast<size_t>(L.d_pad) * sizeof(float);
-  const size_t ptrs = static_cast<size_t>(c.m) * n_tensors * sizeof(void *);
+  const size_t n_ptr = static_cast<size_t>(c.m) * n_tensors;
   s.x0 = take(arena);
   s.u = take(arena);
   s.h = take(arena * c.m);
   s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
-  s.xtab = take(ptrs);
-  for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(ptrs);
-  s.lruns = take(n_lruns * sizeof(LocalRun));
-  s.tile_begin = take((n_ltiles + 1) * sizeof(int32_t));
-  s.oruns = take(n_oruns * sizeof(OuterRun));
+  s.xtab_t = take(n_ptr * sizeof(void *));
+  for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
+  s.slots = take(n_ptr * sizeof(SlotInfo));
+  s.ltiles = take(n_ltiles * sizeof(LocalTile));
+  s.otiles = take(n_otiles * sizeof(OuterTile));
   s.total = off;
   return s;
 }
@@ -90,6 +90,8 @@ std::string check_config(const slowmo_config *c, int32_t n_tensors, const int64_
   if (total * c->m > (int64_t(1) << 44)) return "m * total elements exceeds 2^44";
   if (static_cast<int64_t>(c->m) * n_tensors > (int64_t(1) << 24))
     return "m * n_tensors exceeds 2^24";
+  if (count_local_tiles(c->m, n_tensors, numel) > (int64_t(1) << 31) - 16)
+    return "too many tiles for one launch (m * total elements too large)";
   return "";
 }
 
@@ -110,11 +112,11 @@ struct slowmo_ctx {
 
   // sections of the caller's workspace (device pointers)
   float *x0 = nullptr, *u = nullptr, *h = nullptr, *v = nullptr;
-  float **d_xtab = nullptr;
+  float **d_xtab_t = nullptr;  // replica pointers, tensor-major
   const void **d_gtab[kSlots] = {};
-  LocalRun *d_lruns = nullptr;
-  int32_t *d_tile_begin = nullptr;
-  OuterRun *d_oruns = nullptr;
+  SlotInfo *d_slots = nullptr;
+  LocalTile *d_ltiles = nullptr;
+  OuterTile *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
 
   // gradient-pointer table: pinned staging ring, one event per slot recorded
@@ -175,38 +177,41 @@ size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int
     return 0;
   }
   Layout L = make_layout(n_tensors, numel);
-  std::vector<PlanRun> lr, orr;
-  std::vector<int32_t> tb;
-  plan_local(cfg->m, n_tensors, numel, local_tile_elems(), lr, tb);
-  plan_outer(n_tensors, numel, outer_tile_elems(cfg->m), orr);
-  return make_sections(*cfg, n_tensors, L, lr.size(), tb.size() - 1, orr.size()).total;
+  return make_sections(*cfg, n_tensors, L,
+                       static_cast<size_t>(count_local_tiles(cfg->m, n_tensors, numel)),
+                       static_cast<size_t>(count_outer_tiles(n_tensors, numel)))
+      .total;
+}
+
+static int64_t plan_query(bool local, int32_t m, int32_t n_tensors, const int64_t *numel,
+                          slowmo_plan_run *out, int64_t cap) {
+  if (m < 1 || n_tensors < 1 || !numel || cap < 0 || (cap > 0 && !out)) return -1;
+  for (int32_t j = 0; j < n_tensors; ++j)
+    if (numel[j] < 0) return -1;
+  const int64_t total =
+      local ? count_local_tiles(m, n_tensors, numel) : count_outer_tiles(n_tensors, numel);
+  if (cap == 0) return total;
+  if (total > (int64_t(1) << 31) - 16) return -1;
+  std::vector<PlanRun> runs;
+  if (local) {
+    plan_local(m, n_tensors, numel, runs);
+  } else {
+    plan_outer(n_tensors, numel, runs);
+  }
+  for (int64_t i = 0; i < std::min<int64_t>(cap, runs.size()); ++i) {
+    out[i] = {runs[i].tile, runs[i].worker, runs[i].tensor, runs[i].n, runs[i].offset};
+  }
+  return total;
 }
 
 int64_t slowmo_plan_local(int32_t m, int32_t n_tensors, const int64_t *numel, slowmo_plan_run *out,
                           int64_t cap) {
-  if (m < 1 || n_tensors < 1 || !numel || cap < 0 || (cap > 0 && !out)) return -1;
-  for (int32_t j = 0; j < n_tensors; ++j)
-    if (numel[j] < 0) return -1;
-  std::vector<PlanRun> runs;
-  std::vector<int32_t> tb;
-  plan_local(m, n_tensors, numel, local_tile_elems(), runs, tb);
-  for (int64_t i = 0; i < std::min<int64_t>(cap, runs.size()); ++i) {
-    out[i] = {runs[i].tile, runs[i].worker, runs[i].tensor, runs[i].n, runs[i].offset};
-  }
-  return static_cast<int64_t>(runs.size());
+  return plan_query(true, m, n_tensors, numel, out, cap);
 }
 
 int64_t slowmo_plan_outer(int32_t m, int32_t n_tensors, const int64_t *numel, slowmo_plan_run *out,
                           int64_t cap) {
-  if (m < 1 || n_tensors < 1 || !numel || cap < 0 || (cap > 0 && !out)) return -1;
-  for (int32_t j = 0; j < n_tensors; ++j)
-    if (numel[j] < 0) return -1;
-  std::vector<PlanRun> runs;
-  plan_outer(n_tensors, numel, outer_tile_elems(m), runs);
-  for (int64_t i = 0; i < std::min<int64_t>(cap, runs.size()); ++i) {
-    out[i] = {runs[i].tile, runs[i].worker, runs[i].tensor, runs[i].n, runs[i].offset};
-  }
-  return static_cast<int64_t>(runs.size());
+  return plan_query(false, m, n_tensors, numel, out, cap);
 }
 
 slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t n_tensors,
@@ -242,17 +247,13 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->n_tensors = n_tensors;
   ctx->numel.assign(numel, numel + n_tensors);
   ctx->layout = make_layout(n_tensors, numel);
-  ctx->tune.local_grid = env_flag("SLOWMO_LOCAL_GRID", 0);
-  ctx->tune.outer_grid = env_flag("SLOWMO_OUTER_GRID", 0);
   ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
-  ctx->tune.nontemporal = env_flag("SLOWMO_NT", 0) ? 1 : 0;
+  ctx->tune.nontemporal = env_flag("SLOWMO_NT", 1) ? 1 : 0;
 
-  std::vector<PlanRun> lruns, oruns;
-  std::vector<int32_t> tile_begin;
-  plan_local(m, n_tensors, numel, local_tile_elems(), lruns, tile_begin);
-  plan_outer(n_tensors, numel, outer_tile_elems(m), oruns);
-  const Sections sec = make_sections(*cfg, n_tensors, ctx->layout, lruns.size(),
-                                     tile_begin.size() - 1, oruns.size());
+  const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
+  const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
+  const Sections sec = make_sections(*cfg, n_tensors, ctx->layout, static_cast<size_t>(n_ltiles),
+                                     static_cast<size_t>(n_otiles));
   if (state_bytes < sec.total) {
     delete ctx;
     return fail(nullptr, SLOWMO_ERR_NOMEM, "state workspace is smaller than slowmo_state_bytes()");
@@ -278,13 +279,13 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->u = reinterpret_cast<float *>(base + sec.u);
   ctx->h = reinterpret_cast<float *>(base + sec.h);
   ctx->v = cfg->base == SLOWMO_ADAM ? reinterpret_cast<float *>(base + sec.v) : nullptr;
-  ctx->d_xtab = reinterpret_cast<float **>(base + sec.xtab);
+  ctx->d_xtab_t = reinterpret_cast<float **>(base + sec.xtab_t);
   for (int i = 0; i < kSlots; ++i) ctx->d_gtab[i] = reinterpret_cast<const void **>(base + sec.gtab[i]);
-  ctx->d_lruns = reinterpret_cast<LocalRun *>(base + sec.lruns);
-  ctx->d_tile_begin = reinterpret_cast<int32_t *>(base + sec.tile_begin);
-  ctx->d_oruns = reinterpret_cast<OuterRun *>(base + sec.oruns);
-  ctx->n_ltiles = static_cast<int32_t>(tile_begin.size()) - 1;
-  ctx->n_otiles = static_cast<int32_t>(oruns.size());
+  ctx->d_slots = reinterpret_cast<SlotInfo *>(base + sec.slots);
+  ctx->d_ltiles = reinterpret_cast<LocalTile *>(base + sec.ltiles);
+  ctx->d_otiles = reinterpret_cast<OuterTile *>(base + sec.otiles);
+  ctx->n_ltiles = static_cast<int32_t>(n_ltiles);
+  ctx->n_otiles = static_cast<int32_t>(n_otiles);
 
 #define CREATE_HIP(call, what)              \
   do {                                      \
@@ -303,37 +304,52 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   }
 
   // device tables
-  std::vector<LocalRun> dl(lruns.size());
   const Layout &L = ctx->layout;
-  for (size_t i = 0; i < lruns.size(); ++i) {
-    const PlanRun &r = lruns[i];
-    dl[i].x = params[static_cast<size_t>(r.worker) * n_tensors + r.tensor] + r.offset;
-    dl[i].so = static_cast<int64_t>(r.worker) * L.d_pad + L.arena_off[r.tensor] + r.offset;
-    dl[i].go = r.offset;
-    dl[i].slot = r.worker * n_tensors + r.tensor;
-    dl[i].n = r.n;
+  std::vector<SlotInfo> slots(n_ptr);
+  std::vector<float *> xtab_t(n_ptr);
+  std::vector<int32_t> unaligned(n_tensors, 0);  // per tensor: some replica not 16-byte aligned
+  for (int32_t w = 0; w < m; ++w) {
+    for (int32_t j = 0; j < n_tensors; ++j) {
+      const size_t slot = static_cast<size_t>(w) * n_tensors + j;
+      slots[slot].x = params[slot];
+      slots[slot].so = static_cast<int64_t>(w) * L.d_pad + L.arena_off[j];
+      xtab_t[static_cast<size_t>(j) * m + w] = params[slot];
+      if (reinterpret_cast<uintptr_t>(params[slot]) & 15) unaligned[j] = 1;
+    }
   }
-  std::vector<OuterRun> dout(oruns.size());
-  for (size_t i = 0; i < oruns.size(); ++i) {
-    const PlanRun &r = oruns[i];
-    dout[i].fo = L.arena_off[r.tensor] + r.offset;
-    dout[i].eo = r.offset;
-    dout[i].tensor = r.tensor;
-    dout[i].n = r.n;
+  std::vector<LocalTile> lt;
+  std::vector<OuterTile> ot;
+  {
+    std::vector<PlanRun> runs;
+    plan_local(m, n_tensors, numel, runs);
+    lt.resize(runs.size());
+    for (size_t i = 0; i < runs.size(); ++i) {
+      lt[i].go = runs[i].offset;
+      lt[i].slot = runs[i].worker * n_tensors + runs[i].tensor;
+      lt[i].n = runs[i].n;
+    }
+    plan_outer(n_tensors, numel, runs);
+    ot.resize(runs.size());
+    for (size_t i = 0; i < runs.size(); ++i) {
+      ot[i].fo = L.arena_off[runs[i].tensor] + runs[i].offset;
+      ot[i].eo = runs[i].offset;
+      ot[i].tensor = runs[i].tensor;
+      ot[i].n = runs[i].n | (unaligned[runs[i].tensor] ? kOuterUnalignedBit : 0);
+    }
   }
-  if (!dl.empty())
-    CREATE_HIP(hipMemcpyAsync(ctx->d_lruns, dl.data(), dl.size() * sizeof(LocalRun),
+  if (!lt.empty())
+    CREATE_HIP(hipMemcpyAsync(ctx->d_ltiles, lt.data(), lt.size() * sizeof(LocalTile),
                               hipMemcpyHostToDevice, stream),
-               "upload of the local-step tiling");
-  CREATE_HIP(hipMemcpyAsync(ctx->d_tile_begin, tile_begin.data(),
-                            tile_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream),
-             "upload of the tile index");
-  if (!dout.empty())
-    CREATE_HIP(hipMemcpyAsync(ctx->d_oruns, dout.data(), dout.size() * sizeof(OuterRun),
+               "upload of the local-step tiles");
+  if (!ot.empty())
+    CREATE_HIP(hipMemcpyAsync(ctx->d_otiles, ot.data(), ot.size() * sizeof(OuterTile),
                               hipMemcpyHostToDevice, stream),
-               "upload of the outer-step tiling");
-  CREATE_HIP(hipMemcpyAsync(ctx->d_xtab, params, n_ptr * sizeof(float *), hipMemcpyHostToDevice,
-                            stream),
+               "upload of the outer-step tiles");
+  CREATE_HIP(hipMemcpyAsync(ctx->d_slots, slots.data(), n_ptr * sizeof(SlotInfo),
+                            hipMemcpyHostToDevice, stream),
+             "upload of the slot table");
+  CREATE_HIP(hipMemcpyAsync(ctx->d_xtab_t, xtab_t.data(), n_ptr * sizeof(float *),
+                            hipMemcpyHostToDevice, stream),
              "upload of the replica pointers");
 
   // u_0 = 0, h = v = 0 (Algorithm 1, "Input"; Table C.1 caption)
@@ -403,8 +419,8 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   }
 
   LocalArgs a{};
-  a.runs = ctx->d_lruns;
-  a.tile_begin = ctx->d_tile_begin;
+  a.tiles = ctx->d_ltiles;
+  a.slots = ctx->d_slots;
   a.ntiles = ctx->n_ltiles;
   a.gtab = ctx->d_gtab[slot];
   a.h = ctx->h;
@@ -439,11 +455,10 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
   const slowmo_config &c = ctx->cfg;
   OuterArgs a{};
-  a.runs = ctx->d_oruns;
+  a.tiles = ctx->d_otiles;
   a.ntiles = ctx->n_otiles;
-  a.xtab = ctx->d_xtab;
+  a.xtab_t = ctx->d_xtab_t;
   a.m = c.m;
-  a.n_tensors = ctx->n_tensors;
   a.x0 = ctx->x0;
   a.u = ctx->u;
   a.lr = lr;

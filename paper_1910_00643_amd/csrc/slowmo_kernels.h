@@ -10,10 +10,10 @@
 namespace slowmo {
 
 struct LocalArgs {
-  const LocalRun *runs;        // device
-  const int32_t *tile_begin;   // device, ntiles + 1 entries
-  int32_t ntiles;
+  const LocalTile *tiles;      // device, ntiles entries
+  const SlotInfo *slots;       // device, m * n_tensors entries
   const void *const *gtab;     // device: m * n_tensors gradient pointers of this call
+  int32_t ntiles;
   float *h;                    // device: h arena, m * d_pad
   float *v;                    // device: v arena (Adam) or nullptr
   float lr;
@@ -25,11 +25,10 @@ struct LocalArgs {
 };
 
 struct OuterArgs {
-  const OuterRun *runs;        // device, one per tile
+  const OuterTile *tiles;      // device, ntiles entries
+  float *const *xtab_t;        // device: replica pointers, tensor-major: [tensor * m + worker]
   int32_t ntiles;
-  float *const *xtab;          // device: m * n_tensors replica pointers (worker-major)
   int32_t m;
-  int32_t n_tensors;
   float *x0;                   // device: arena d_pad
   float *u;                    // device: arena d_pad
   float lr;                    // gamma_t
@@ -39,8 +38,6 @@ struct OuterArgs {
 };
 
 struct LaunchTuning {
-  int32_t local_grid;   // 0: one workgroup per tile; else a persistent grid of this many
-  int32_t outer_grid;
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
 };

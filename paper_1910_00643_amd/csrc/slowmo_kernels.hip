@@ -2,57 +2,81 @@
 //
 // Both kernels are pure streams: every byte is read once and written once, no
 // element is reused, so there is no dense contraction and the matrix cores are
-// not involved.  What matters is (i) 16-byte per-lane accesses that make each
-// wavefront instruction one contiguous 1 KiB burst, (ii) enough independent
-// loads in flight per CU to cover HBM latency, (iii) tiles of equal cost so
-// that all 256 CUs drain together, and (iv) a tile -> workgroup mapping that
-// keeps neighbouring tiles on one XCD.
+// not involved.  The shape that measured fastest on MI355X for this read/write
+// mix:
+//   * one 16-byte vector per lane and per stream -- a wavefront instruction is
+//     one contiguous 1 KiB burst;
+//   * small workgroups that load, compute, store and retire (no loop): their
+//     stores do not hold a wave slot, reads and writes of neighbouring
+//     workgroups interleave, and the set of addresses in flight is a compact
+//     window that moves through memory in order;
+//   * non-temporal loads and stores (nothing is reused);
+//   * workgroup -> tile mapping that gives each XCD one contiguous range of
+//     tiles (workgroups are dealt to the 8 XCDs round-robin);
+//   * tile descriptors and pointer tables read with scalar loads: they are
+//     uniform over the workgroup, so they live in SGPRs, not in LDS.
 //
 // Compiled with -ffp-contract=off: products and sums are rounded separately,
 // in the order written here, which is the order of Table C.1 and Eq. (2)-(3).
 #include "slowmo_kernels.h"
 
-#include "../../include/slowmo.h"
-
 namespace slowmo {
 
 namespace {
 
-constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes
-constexpr int kXcd = 8;      // XCDs per MI355X; workgroups are dealt to them round-robin
+constexpr int kXcd = 8;  // XCDs per MI355X; workgroups are dealt to them round-robin
 
 typedef float V4 __attribute__((ext_vector_type(4)));
 typedef uint32_t U2 __attribute__((ext_vector_type(2)));
 
+// Pointers that were themselves loaded from memory (replica and gradient
+// tables) have no known address space, and the compiler would use flat
+// accesses for them.  They are global memory: say so, to get global_load /
+// global_store.
+#define SLOWMO_GLOBAL __attribute__((address_space(1)))
+typedef SLOWMO_GLOBAL V4 GV4;
+typedef SLOWMO_GLOBAL U2 GU2;
+typedef SLOWMO_GLOBAL float GF;
+typedef SLOWMO_GLOBAL uint16_t GH;
+
+template <typename T>
+__device__ __forceinline__ SLOWMO_GLOBAL T *as_global(const void *p) {
+  return (SLOWMO_GLOBAL T *)(reinterpret_cast<uintptr_t>(p));
+}
+
 template <bool NT>
 __device__ __forceinline__ V4 ld4(const float *p) {
-  if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const V4 *>(p));
-  return *reinterpret_cast<const V4 *>(p);
+  const GV4 *q = as_global<V4>(p);
+  if constexpr (NT) return __builtin_nontemporal_load(q);
+  return *q;
 }
 template <bool NT>
 __device__ __forceinline__ void st4(float *p, V4 v) {
+  GV4 *q = as_global<V4>(p);
   if constexpr (NT) {
-    __builtin_nontemporal_store(v, reinterpret_cast<V4 *>(p));
+    __builtin_nontemporal_store(v, q);
   } else {
-    *reinterpret_cast<V4 *>(p) = v;
+    *q = v;
   }
 }
+__device__ __forceinline__ float ld1(const float *p) { return *as_global<float>(p); }
+__device__ __forceinline__ void st1(float *p, float v) { *as_global<float>(p) = v; }
 
 // Gradient access: fp32 as is, bf16 widened exactly (the 16 bits become the
 // high half of an fp32 word).
 template <bool BF16>
 __device__ __forceinline__ float ldg1(const void *g, int j) {
   if constexpr (BF16) {
-    uint32_t w = reinterpret_cast<const uint16_t *>(g)[j];
+    uint32_t w = as_global<uint16_t>(g)[j];
     return __uint_as_float(w << 16);
   } else {
-    return reinterpret_cast<const float *>(g)[j];
+    return as_global<float>(g)[j];
   }
 }
 template <bool BF16, bool NT>
 __device__ __forceinline__ V4 ldg4(const void *g, int vec) {
   if constexpr (BF16) {
-    const U2 *p = reinterpret_cast<const U2 *>(g) + vec;
+    const GU2 *p = as_global<U2>(g) + vec;
     U2 w = NT ? __builtin_nontemporal_load(p) : *p;
     V4 r;
     r.x = __uint_as_float(w.x << 16);
@@ -65,12 +89,11 @@ __device__ __forceinline__ V4 ldg4(const void *g, int vec) {
   }
 }
 
-// Tile visited by the v-th unit of the launch.  Workgroup b runs on XCD
-// b mod 8; with the remap, XCD c walks the contiguous tile range
-// [c * chunk, (c + 1) * chunk), so each XCD's L2 and TLB see one compact
-// window of every stream instead of a 1-in-8 comb over all of it.
-__device__ __forceinline__ int tile_of(int v, int chunk, int remap) {
-  return remap ? (v % kXcd) * chunk + v / kXcd : v;
+// Tile of workgroup b.  Workgroup b runs on XCD b mod 8; with the remap, XCD c
+// walks the contiguous tile range [c * chunk, (c + 1) * chunk), so each XCD's
+// L2 and TLB see one compact window of every stream instead of a 1-in-8 comb.
+__device__ __forceinline__ int tile_of(int b, int chunk, int remap) {
+  return remap ? (b % kXcd) * chunk + b / kXcd : b;
 }
 
 // ---- per-element arithmetic -------------------------------------------------
@@ -125,206 +148,147 @@ __device__ __forceinline__ float outer_elem(float s, float x0, float &u, const O
 }
 
 // ---- local step ---------------------------------------------------------------
+// One workgroup = one tile = up to 4 * blockDim elements of one (worker,
+// tensor).  Lane t owns elements [4t, 4t + 4) of the tile.
 
-template <int BASE, bool BF16, bool FIRST, bool NT, int U>
-__device__ __forceinline__ void local_run(float *__restrict__ x, float *__restrict__ h,
-                                          float *__restrict__ v, const void *__restrict__ g, int n,
-                                          const SgdP &sp, const AdamP &ap) {
-  const int tid = threadIdx.x;
-  uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(h);
-  if constexpr (BASE == 1) bits |= reinterpret_cast<uintptr_t>(v);
-  bits |= BF16 ? (reinterpret_cast<uintptr_t>(g) << 1) : reinterpret_cast<uintptr_t>(g);
-  int done = 0;
-  if ((bits & 15) == 0) {
-    const int nv = n >> 2;
-    for (int base = 0; base < nv; base += kBlock * U) {
-      V4 xv[U], hv[U], vv[U], gv[U];
-#pragma unroll
-      for (int q = 0; q < U; ++q) {
-        int idx = base + q * kBlock + tid;
-        if (idx < nv) {
-          xv[q] = ld4<NT>(x + 4 * idx);
-          if constexpr (!FIRST) hv[q] = ld4<NT>(h + 4 * idx);
-          if constexpr (!FIRST && BASE == 1) vv[q] = ld4<NT>(v + 4 * idx);
-          gv[q] = ldg4<BF16, NT>(g, idx);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < U; ++q) {
-        int idx = base + q * kBlock + tid;
-        if (idx < nv) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            float xe = xv[q][c], he = FIRST ? 0.f : hv[q][c];
-            if constexpr (BASE == 0) {
-              sgd_elem<FIRST>(xe, he, gv[q][c], sp);
-            } else {
-              float ve = FIRST ? 0.f : vv[q][c];
-              adam_elem<FIRST>(xe, he, ve, gv[q][c], ap);
-              vv[q][c] = ve;
-            }
-            xv[q][c] = xe;
-            hv[q][c] = he;
-          }
-          st4<NT>(x + 4 * idx, xv[q]);
-          st4<NT>(h + 4 * idx, hv[q]);
-          if constexpr (BASE == 1) st4<NT>(v + 4 * idx, vv[q]);
-        }
-      }
-    }
-    done = nv << 2;
-  }
-  // element-wise path: the ragged tail of an aligned run, or a whole run
-  // whose pointers are not 16-byte aligned
-  for (int j = done + tid; j < n; j += kBlock) {
-    float xe = x[j], he = FIRST ? 0.f : h[j];
-    float ge = ldg1<BF16>(g, j);
-    if constexpr (BASE == 0) {
-      sgd_elem<FIRST>(xe, he, ge, sp);
-    } else {
-      float ve = FIRST ? 0.f : v[j];
-      adam_elem<FIRST>(xe, he, ve, ge, ap);
-      v[j] = ve;
-    }
-    x[j] = xe;
-    h[j] = he;
-  }
-}
-
-template <int BASE, bool BF16, bool FIRST, bool NT, int U>
-__global__ __launch_bounds__(kBlock) void k_local_step(LocalArgs a, int chunk, int nunits,
-                                                       int remap) {
-  // The descriptors of the runs in this workgroup's tile, staged once in LDS
-  // and then read by all four wavefronts as broadcasts.
-  __shared__ LocalRun s_run[kMaxRunsPerTile];
-  __shared__ const void *s_g[kMaxRunsPerTile];
-  const SgdP sp{a.lr, a.mu, a.wd};
-  const AdamP ap{a.lr, a.wd, a.b1, a.b2, a.omb1, a.omb2, a.rc1, a.rc2, a.eps};
+template <int BASE, bool BF16, bool FIRST, bool NT>
+__global__ __launch_bounds__(kLocalBlock) void k_local_step(
+    const LocalTile *__restrict__ tiles, const SlotInfo *__restrict__ slots,
+    const void *const *__restrict__ gtab, float *__restrict__ hbase, float *__restrict__ vbase,
+    int ntiles, int chunk, int remap, SgdP sp, AdamP ap) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const LocalTile t = tiles[tile];       // uniform: scalar loads
+  const SlotInfo s = slots[t.slot];
   constexpr int gsize = BF16 ? 2 : 4;
-  for (int unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
-    const int tile = tile_of(unit, chunk, remap);
-    if (tile >= a.ntiles) continue;  // uniform over the workgroup
-    const int rb = a.tile_begin[tile];
-    const int nr = a.tile_begin[tile + 1] - rb;
-    if (static_cast<int>(threadIdx.x) < nr) {
-      LocalRun r = a.runs[rb + threadIdx.x];
-      s_run[threadIdx.x] = r;
-      s_g[threadIdx.x] = static_cast<const char *>(a.gtab[r.slot]) + r.go * gsize;
+  const void *g = static_cast<const char *>(gtab[t.slot]) + t.go * gsize;
+  float *x = s.x + t.go;
+  float *h = hbase + s.so + t.go;
+  float *v = BASE == 1 ? vbase + s.so + t.go : nullptr;
+  const int n = t.n;
+  // h and v are 16-byte aligned by construction of the arena
+  uintptr_t bits = reinterpret_cast<uintptr_t>(x) |
+                   (BF16 ? reinterpret_cast<uintptr_t>(g) << 1 : reinterpret_cast<uintptr_t>(g));
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if ((bits & 15) == 0 && e0 + 4 <= n) {
+    const int idx = threadIdx.x;
+    V4 xv = ld4<NT>(x + e0), hv, vv;
+    if constexpr (!FIRST) hv = ld4<NT>(h + e0);
+    if constexpr (!FIRST && BASE == 1) vv = ld4<NT>(v + e0);
+    V4 gv = ldg4<BF16, NT>(g, idx);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float xe = xv[c], he = FIRST ? 0.f : hv[c];
+      if constexpr (BASE == 0) {
+        sgd_elem<FIRST>(xe, he, gv[c], sp);
+      } else {
+        float ve = FIRST ? 0.f : vv[c];
+        adam_elem<FIRST>(xe, he, ve, gv[c], ap);
+        vv[c] = ve;
+      }
+      xv[c] = xe;
+      hv[c] = he;
     }
-    __syncthreads();
-    for (int i = 0; i < nr; ++i) {
-      const LocalRun r = s_run[i];
-      local_run<BASE, BF16, FIRST, NT, U>(r.x, a.h + r.so, BASE == 1 ? a.v + r.so : nullptr,
-                                          s_g[i], r.n, sp, ap);
+    st4<NT>(x + e0, xv);
+    st4<NT>(h + e0, hv);
+    if constexpr (BASE == 1) st4<NT>(v + e0, vv);
+  } else {
+    // element-wise: the ragged tail of a tensor, or pointers that are not
+    // 16-byte aligned
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      float xe = ld1(x + j), he = FIRST ? 0.f : ld1(h + j);
+      float ge = ldg1<BF16>(g, j);
+      if constexpr (BASE == 0) {
+        sgd_elem<FIRST>(xe, he, ge, sp);
+      } else {
+        float ve = FIRST ? 0.f : ld1(v + j);
+        adam_elem<FIRST>(xe, he, ve, ge, ap);
+        st1(v + j, ve);
+      }
+      st1(x + j, xe);
+      st1(h + j, he);
     }
-    __syncthreads();  // LDS is rewritten by the next tile
   }
 }
 
 // ---- outer step -----------------------------------------------------------------
+// One workgroup = one tile = up to 4 * blockDim elements of one tensor; lane t
+// owns elements [4t, 4t + 4) in all m replicas, x0 and u.
 
-template <bool NT, int U>
-__global__ __launch_bounds__(kBlock) void k_outer_step(OuterArgs a, int chunk, int nunits,
-                                                       int remap) {
-  __shared__ float *s_xp[SLOWMO_MAX_WORKERS];  // replica pointers of this tile's run
-  __shared__ int s_unaligned;
-  const int tid = threadIdx.x;
-  const int m = a.m;
-  const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
-  for (int unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
-    const int tile = tile_of(unit, chunk, remap);
-    if (tile >= a.ntiles) continue;  // uniform over the workgroup
-    const OuterRun r = a.runs[tile];
-    if (tid == 0) s_unaligned = 0;
-    __syncthreads();
-    for (int i = tid; i < m; i += kBlock) {
-      float *xp = a.xtab[static_cast<int64_t>(i) * a.n_tensors + r.tensor] + r.eo;
-      s_xp[i] = xp;
-      if (reinterpret_cast<uintptr_t>(xp) & 15) s_unaligned = 1;
+template <bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_outer_step(
+    const OuterTile *__restrict__ tiles, float *const *__restrict__ xtab_t,
+    float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap, int m,
+    OuterP p) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const OuterTile t = tiles[tile];       // uniform: scalar loads
+  const int n = t.n & ~kOuterUnalignedBit;
+  const bool aligned = (t.n & kOuterUnalignedBit) == 0;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.tensor) * m;  // m replica pointers
+  float *x0 = x0base + t.fo;
+  float *u = ubase + t.fo;
+  const int64_t eo = t.eo;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (aligned && e0 + 4 <= n) {
+    // line 6: ordered sum over the replicas, i = 0, 1, ..., m-1
+    V4 acc = ld4<NT>(xp[0] + eo + e0);
+#pragma unroll 8
+    for (int i = 1; i < m; ++i) acc = acc + ld4<NT>(xp[i] + eo + e0);
+    V4 x0v = ld4<NT>(x0 + e0);
+    V4 uv = ld4<NT>(u + e0);
+    V4 xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[c], x0v[c], ue, p);
+      uv[c] = ue;
     }
-    __syncthreads();
-    float *__restrict__ x0 = a.x0 + r.fo;  // 16-byte aligned by construction of the arena
-    float *__restrict__ u = a.u + r.fo;
-    const int n = r.n;
-    int done = 0;
-    if (!s_unaligned) {
-      const int nv = n >> 2;
-      for (int base = 0; base < nv; base += kBlock * U) {
-        V4 acc[U];
-        // line 6: ordered sum over the replicas, i = 0, 1, ..., m-1
-#pragma unroll 4
-        for (int i = 0; i < m; ++i) {
-          const float *xp = s_xp[i];
-#pragma unroll
-          for (int q = 0; q < U; ++q) {
-            int idx = base + q * kBlock + tid;
-            if (idx < nv) {
-              V4 t = ld4<NT>(xp + 4 * idx);
-              acc[q] = (i == 0) ? t : acc[q] + t;
-            }
-          }
-        }
-        V4 xn[U];
-#pragma unroll
-        for (int q = 0; q < U; ++q) {
-          int idx = base + q * kBlock + tid;
-          if (idx < nv) {
-            V4 x0v = ld4<NT>(x0 + 4 * idx);
-            V4 uv = ld4<NT>(u + 4 * idx);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              float ue = uv[c];
-              xn[q][c] = outer_elem(acc[q][c], x0v[c], ue, p);
-              uv[c] = ue;
-            }
-            st4<NT>(u + 4 * idx, uv);
-            st4<NT>(x0 + 4 * idx, xn[q]);
-          }
-        }
-        for (int i = 0; i < m; ++i) {
-          float *xp = s_xp[i];
-#pragma unroll
-          for (int q = 0; q < U; ++q) {
-            int idx = base + q * kBlock + tid;
-            if (idx < nv) st4<NT>(xp + 4 * idx, xn[q]);
-          }
-        }
-      }
-      done = nv << 2;
+    st4<NT>(u + e0, uv);
+    st4<NT>(x0 + e0, xn);
+#pragma unroll 8
+    for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      float s = ld1(xp[0] + eo + j);
+      for (int i = 1; i < m; ++i) s = s + ld1(xp[i] + eo + j);
+      float ue = ld1(u + j);
+      float xn = outer_elem(s, ld1(x0 + j), ue, p);
+      st1(u + j, ue);
+      st1(x0 + j, xn);
+      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
     }
-    for (int j = done + tid; j < n; j += kBlock) {
-      float s = s_xp[0][j];
-      for (int i = 1; i < m; ++i) s = s + s_xp[i][j];
-      float ue = u[j];
-      float xn = outer_elem(s, x0[j], ue, p);
-      u[j] = ue;
-      x0[j] = xn;
-      for (int i = 0; i < m; ++i) s_xp[i][j] = xn;
-    }
-    __syncthreads();  // s_xp is rewritten by the next tile
   }
 }
 
 struct Grid {
-  int chunk, nunits, blocks;
+  int chunk;
+  unsigned blocks;
 };
-Grid make_grid(int ntiles, int persistent, int remap) {
+Grid make_grid(int ntiles, int remap) {
   Grid g;
   g.chunk = (ntiles + kXcd - 1) / kXcd;
-  g.nunits = remap ? g.chunk * kXcd : ntiles;
-  g.blocks = (persistent > 0 && persistent < g.nunits) ? persistent : g.nunits;
+  g.blocks = static_cast<unsigned>(remap ? g.chunk * kXcd : ntiles);
   return g;
 }
 
 template <int BASE, bool BF16, bool FIRST>
 hipError_t launch_local_t(const LocalArgs &a, const LaunchTuning &t, hipStream_t s) {
-  Grid g = make_grid(a.ntiles, t.local_grid, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const SgdP sp{a.lr, a.mu, a.wd};
+  const AdamP ap{a.lr, a.wd, a.b1, a.b2, a.omb1, a.omb2, a.rc1, a.rc2, a.eps};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, true, 4>), dim3(g.blocks), dim3(kBlock), 0,
-                       s, a, g.chunk, g.nunits, t.xcd_remap);
+    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, true>), dim3(g.blocks), dim3(kLocalBlock),
+                       0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles, g.chunk, t.xcd_remap,
+                       sp, ap);
   } else {
-    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, false, 4>), dim3(g.blocks), dim3(kBlock),
-                       0, s, a, g.chunk, g.nunits, t.xcd_remap);
+    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, false>), dim3(g.blocks),
+                       dim3(kLocalBlock), 0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles,
+                       g.chunk, t.xcd_remap, sp, ap);
   }
   return hipGetLastError();
 }
@@ -348,13 +312,14 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
 
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
-  Grid g = make_grid(a.ntiles, t.outer_grid, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_outer_step<true, 2>), dim3(g.blocks), dim3(kBlock), 0, s, a, g.chunk,
-                       g.nunits, t.xcd_remap);
+    hipLaunchKernelGGL((k_outer_step<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   } else {
-    hipLaunchKernelGGL((k_outer_step<false, 2>), dim3(g.blocks), dim3(kBlock), 0, s, a, g.chunk,
-                       g.nunits, t.xcd_remap);
+    hipLaunchKernelGGL((k_outer_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   }
   return hipGetLastError();
 }
