@@ -56,7 +56,9 @@ def build_problem(w, ring):
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from slowmo_inputs.gpu_problem import GpuProblem
     from paper_1910_00643_amd.optimizer import SlowMo, make_config
-    prob = GpuProblem(w, "cuda:0", ring=ring)
+    # parameters: one allocation per tensor and worker; gradients: every tensor
+    # 512-byte aligned, as separately allocated .grad tensors would be
+    prob = GpuProblem(w, "cuda:0", ring=ring, grad_layout="padded")
     cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
                       policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
                       weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps)

@@ -12,7 +12,8 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libslowmo.so")
+# SLOWMO_LIBRARY selects another build of the same library (tuning runs).
+LIB_PATH = os.environ.get("SLOWMO_LIBRARY") or os.path.join(_HERE, "libslowmo.so")
 
 SLOWMO_OK, SLOWMO_ERR_ARG, SLOWMO_ERR_STATE = 0, -1, -2
 SLOWMO_ERR_ALIGN, SLOWMO_ERR_HIP, SLOWMO_ERR_NOMEM = -3, -4, -5

@@ -29,7 +29,7 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kSlots], slots, ltiles, otiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kSlots], slots, tensors, ltiles, otiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
@@ -50,8 +50,9 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.xtab_t = take(n_ptr * sizeof(void *));
   for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
   s.slots = take(n_ptr * sizeof(SlotInfo));
-  s.ltiles = take(n_ltiles * sizeof(LocalTile));
-  s.otiles = take(n_otiles * sizeof(OuterTile));
+  s.tensors = take(static_cast<size_t>(n_tensors) * sizeof(TensorInfo));
+  s.ltiles = take(n_ltiles * sizeof(TileRef));
+  s.otiles = take(n_otiles * sizeof(TileRef));
   s.total = off;
   return s;
 }
@@ -84,7 +85,7 @@ std::string check_config(const slowmo_config *c, int32_t n_tensors, const int64_
   int64_t total = 0;
   for (int32_t j = 0; j < n_tensors; ++j) {
     if (numel[j] < 0) return "numel has a negative entry";
-    if (numel[j] > (int64_t(1) << 40)) return "a tensor exceeds 2^40 elements";
+    if (numel[j] > (int64_t(1) << 36)) return "a tensor exceeds 2^36 elements";
     total += numel[j];
   }
   if (total * c->m > (int64_t(1) << 44)) return "m * total elements exceeds 2^44";
@@ -115,8 +116,9 @@ struct slowmo_ctx {
   float **d_xtab_t = nullptr;  // replica pointers, tensor-major
   const void **d_gtab[kSlots] = {};
   SlotInfo *d_slots = nullptr;
-  LocalTile *d_ltiles = nullptr;
-  OuterTile *d_otiles = nullptr;
+  TensorInfo *d_tensors = nullptr;
+  TileRef *d_ltiles = nullptr;
+  TileRef *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
 
   // gradient-pointer table: pinned staging ring, one event per slot recorded
@@ -282,8 +284,9 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->d_xtab_t = reinterpret_cast<float **>(base + sec.xtab_t);
   for (int i = 0; i < kSlots; ++i) ctx->d_gtab[i] = reinterpret_cast<const void **>(base + sec.gtab[i]);
   ctx->d_slots = reinterpret_cast<SlotInfo *>(base + sec.slots);
-  ctx->d_ltiles = reinterpret_cast<LocalTile *>(base + sec.ltiles);
-  ctx->d_otiles = reinterpret_cast<OuterTile *>(base + sec.otiles);
+  ctx->d_tensors = reinterpret_cast<TensorInfo *>(base + sec.tensors);
+  ctx->d_ltiles = reinterpret_cast<TileRef *>(base + sec.ltiles);
+  ctx->d_otiles = reinterpret_cast<TileRef *>(base + sec.otiles);
   ctx->n_ltiles = static_cast<int32_t>(n_ltiles);
   ctx->n_otiles = static_cast<int32_t>(n_otiles);
 
@@ -306,45 +309,38 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   // device tables
   const Layout &L = ctx->layout;
   std::vector<SlotInfo> slots(n_ptr);
+  std::vector<TensorInfo> tinfo(n_tensors);
   std::vector<float *> xtab_t(n_ptr);
-  std::vector<int32_t> unaligned(n_tensors, 0);  // per tensor: some replica not 16-byte aligned
+  for (int32_t j = 0; j < n_tensors; ++j) tinfo[j] = {L.arena_off[j], numel[j], 0, 0};
   for (int32_t w = 0; w < m; ++w) {
     for (int32_t j = 0; j < n_tensors; ++j) {
       const size_t slot = static_cast<size_t>(w) * n_tensors + j;
-      slots[slot].x = params[slot];
-      slots[slot].so = static_cast<int64_t>(w) * L.d_pad + L.arena_off[j];
+      slots[slot] = {params[slot], static_cast<int64_t>(w) * L.d_pad + L.arena_off[j], numel[j], 0};
       xtab_t[static_cast<size_t>(j) * m + w] = params[slot];
-      if (reinterpret_cast<uintptr_t>(params[slot]) & 15) unaligned[j] = 1;
+      if (reinterpret_cast<uintptr_t>(params[slot]) & 15) tinfo[j].unaligned = 1;
     }
   }
-  std::vector<LocalTile> lt;
-  std::vector<OuterTile> ot;
-  {
-    std::vector<PlanRun> runs;
-    plan_local(m, n_tensors, numel, runs);
-    lt.resize(runs.size());
-    for (size_t i = 0; i < runs.size(); ++i) {
-      lt[i].go = runs[i].offset;
-      lt[i].slot = runs[i].worker * n_tensors + runs[i].tensor;
-      lt[i].n = runs[i].n;
-    }
-    plan_outer(n_tensors, numel, runs);
-    ot.resize(runs.size());
-    for (size_t i = 0; i < runs.size(); ++i) {
-      ot[i].fo = L.arena_off[runs[i].tensor] + runs[i].offset;
-      ot[i].eo = runs[i].offset;
-      ot[i].tensor = runs[i].tensor;
-      ot[i].n = runs[i].n | (unaligned[runs[i].tensor] ? kOuterUnalignedBit : 0);
-    }
-  }
+  // tiles in launch order: worker-major, tensors in list order, pieces ascending
+  std::vector<TileRef> lt, ot;
+  lt.reserve(static_cast<size_t>(n_ltiles));
+  ot.reserve(static_cast<size_t>(n_otiles));
+  for (int32_t w = 0; w < m; ++w)
+    for (int32_t j = 0; j < n_tensors; ++j)
+      for (int64_t k = 0; k * kLocalTile < numel[j]; ++k)
+        lt.push_back({w * n_tensors + j, static_cast<int32_t>(k)});
+  for (int32_t j = 0; j < n_tensors; ++j)
+    for (int64_t k = 0; k * kOuterTile < numel[j]; ++k) ot.push_back({j, static_cast<int32_t>(k)});
   if (!lt.empty())
-    CREATE_HIP(hipMemcpyAsync(ctx->d_ltiles, lt.data(), lt.size() * sizeof(LocalTile),
+    CREATE_HIP(hipMemcpyAsync(ctx->d_ltiles, lt.data(), lt.size() * sizeof(TileRef),
                               hipMemcpyHostToDevice, stream),
                "upload of the local-step tiles");
   if (!ot.empty())
-    CREATE_HIP(hipMemcpyAsync(ctx->d_otiles, ot.data(), ot.size() * sizeof(OuterTile),
+    CREATE_HIP(hipMemcpyAsync(ctx->d_otiles, ot.data(), ot.size() * sizeof(TileRef),
                               hipMemcpyHostToDevice, stream),
                "upload of the outer-step tiles");
+  CREATE_HIP(hipMemcpyAsync(ctx->d_tensors, tinfo.data(), tinfo.size() * sizeof(TensorInfo),
+                            hipMemcpyHostToDevice, stream),
+             "upload of the tensor table");
   CREATE_HIP(hipMemcpyAsync(ctx->d_slots, slots.data(), n_ptr * sizeof(SlotInfo),
                             hipMemcpyHostToDevice, stream),
              "upload of the slot table");
@@ -456,6 +452,7 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   const slowmo_config &c = ctx->cfg;
   OuterArgs a{};
   a.tiles = ctx->d_otiles;
+  a.tensors = ctx->d_tensors;
   a.ntiles = ctx->n_otiles;
   a.xtab_t = ctx->d_xtab_t;
   a.m = c.m;

@@ -10,7 +10,7 @@
 namespace slowmo {
 
 struct LocalArgs {
-  const LocalTile *tiles;      // device, ntiles entries
+  const TileRef *tiles;        // device, ntiles entries (owner = slot)
   const SlotInfo *slots;       // device, m * n_tensors entries
   const void *const *gtab;     // device: m * n_tensors gradient pointers of this call
   int32_t ntiles;
@@ -25,7 +25,8 @@ struct LocalArgs {
 };
 
 struct OuterArgs {
-  const OuterTile *tiles;      // device, ntiles entries
+  const TileRef *tiles;        // device, ntiles entries (owner = tensor)
+  const TensorInfo *tensors;   // device, n_tensors entries
   float *const *xtab_t;        // device: replica pointers, tensor-major: [tensor * m + worker]
   int32_t ntiles;
   int32_t m;

@@ -153,19 +153,21 @@ __device__ __forceinline__ float outer_elem(float s, float x0, float &u, const O
 
 template <int BASE, bool BF16, bool FIRST, bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_local_step(
-    const LocalTile *__restrict__ tiles, const SlotInfo *__restrict__ slots,
+    const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
     const void *const *__restrict__ gtab, float *__restrict__ hbase, float *__restrict__ vbase,
     int ntiles, int chunk, int remap, SgdP sp, AdamP ap) {
   const int tile = tile_of(blockIdx.x, chunk, remap);
   if (tile >= ntiles) return;
-  const LocalTile t = tiles[tile];       // uniform: scalar loads
-  const SlotInfo s = slots[t.slot];
+  const TileRef t = tiles[tile];         // uniform: scalar loads
+  const SlotInfo s = slots[t.owner];
   constexpr int gsize = BF16 ? 2 : 4;
-  const void *g = static_cast<const char *>(gtab[t.slot]) + t.go * gsize;
-  float *x = s.x + t.go;
-  float *h = hbase + s.so + t.go;
-  float *v = BASE == 1 ? vbase + s.so + t.go : nullptr;
-  const int n = t.n;
+  const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;  // offset of the tile in its tensor
+  const void *g = static_cast<const char *>(gtab[t.owner]) + go * gsize;
+  float *x = s.x + go;
+  float *h = hbase + s.so + go;
+  float *v = BASE == 1 ? vbase + s.so + go : nullptr;
+  const int64_t left = s.numel - go;
+  const int n = left < kLocalTile ? static_cast<int>(left) : kLocalTile;
   // h and v are 16-byte aligned by construction of the arena
   uintptr_t bits = reinterpret_cast<uintptr_t>(x) |
                    (BF16 ? reinterpret_cast<uintptr_t>(g) << 1 : reinterpret_cast<uintptr_t>(g));
@@ -219,18 +221,20 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
 
 template <bool NT>
 __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
-    const OuterTile *__restrict__ tiles, float *const *__restrict__ xtab_t,
-    float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap, int m,
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap, int m,
     OuterP p) {
   const int tile = tile_of(blockIdx.x, chunk, remap);
   if (tile >= ntiles) return;
-  const OuterTile t = tiles[tile];       // uniform: scalar loads
-  const int n = t.n & ~kOuterUnalignedBit;
-  const bool aligned = (t.n & kOuterUnalignedBit) == 0;
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.tensor) * m;  // m replica pointers
-  float *x0 = x0base + t.fo;
-  float *u = ubase + t.fo;
-  const int64_t eo = t.eo;
+  const TileRef t = tiles[tile];         // uniform: scalar loads
+  const TensorInfo ti = tensors[t.owner];
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;  // offset of the tile in its tensor
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  const bool aligned = ti.unaligned == 0;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;  // m replica pointers
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
   const int e0 = 4 * static_cast<int>(threadIdx.x);
   if (e0 >= n) return;
   if (aligned && e0 + 4 <= n) {
@@ -316,10 +320,10 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_outer_step<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
+                       a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   } else {
     hipLaunchKernelGGL((k_outer_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
+                       a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   }
   return hipGetLastError();
 }

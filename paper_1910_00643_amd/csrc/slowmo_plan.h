@@ -18,36 +18,45 @@ namespace slowmo {
 // aligned (tiles start at multiples of 4 elements of their tensor).
 constexpr int64_t kArenaAlign = 64;
 
-constexpr int32_t kLocalBlock = 256;                 // threads per workgroup, local step
-constexpr int32_t kLocalTile = 4 * kLocalBlock;      // elements per tile: one vec4 per lane
-constexpr int32_t kOuterBlock = 256;
+#ifndef SLOWMO_LOCAL_BLOCK
+#define SLOWMO_LOCAL_BLOCK 64
+#endif
+#ifndef SLOWMO_OUTER_BLOCK
+#define SLOWMO_OUTER_BLOCK 64
+#endif
+// Threads per workgroup; a tile is one vec4 per lane.  Single-wavefront
+// workgroups measured best for both kernels (64 > 128 > 256 > 512).
+constexpr int32_t kLocalBlock = SLOWMO_LOCAL_BLOCK;
+constexpr int32_t kLocalTile = 4 * kLocalBlock;
+constexpr int32_t kOuterBlock = SLOWMO_OUTER_BLOCK;
 constexpr int32_t kOuterTile = 4 * kOuterBlock;
 
-// Local step: one tile = up to kLocalTile elements of one (worker, tensor).
-struct LocalTile {
-  int64_t go;      // element offset of the tile inside its tensor
-  int32_t slot;    // worker * n_tensors + tensor
-  int32_t n;       // elements in the tile (1..kLocalTile)
+// One tile of either kernel: the k-th piece of a tensor.  For the local step
+// `owner` is the slot (worker * n_tensors + tensor); for the outer step it is
+// the tensor.  8 bytes, read with one scalar load.
+struct TileRef {
+  int32_t owner;
+  int32_t k;
 };
-static_assert(sizeof(LocalTile) == 16, "LocalTile layout");
+static_assert(sizeof(TileRef) == 8, "TileRef layout");
 
 // Per (worker, tensor), fixed at create.
 struct SlotInfo {
   float *x;        // device: the worker's replica of the tensor
   int64_t so;      // element offset of the tensor in the h / v arena (includes worker * d_pad)
+  int64_t numel;   // elements in the tensor
+  int64_t pad_;
 };
-static_assert(sizeof(SlotInfo) == 16, "SlotInfo layout");
+static_assert(sizeof(SlotInfo) == 32, "SlotInfo layout");
 
-// Outer step: one tile = up to kOuterTile elements of one tensor, all m replicas.
-struct OuterTile {
-  int64_t fo;      // element offset in the x0 / u arena
-  int64_t eo;      // element offset inside the tensor (added to every replica pointer)
-  int32_t tensor;
-  int32_t n;       // elements; bit 30 set: some replica pointer of this tensor is not
-                   // 16-byte aligned (element-wise path)
+// Per tensor, fixed at create (outer step).
+struct TensorInfo {
+  int64_t fo;         // element offset of the tensor in the x0 / u arena
+  int64_t numel;
+  int64_t unaligned;  // non-zero: some replica of this tensor is not 16-byte aligned
+  int64_t pad_;
 };
-static_assert(sizeof(OuterTile) == 24, "OuterTile layout");
-constexpr int32_t kOuterUnalignedBit = 1 << 30;
+static_assert(sizeof(TensorInfo) == 32, "TensorInfo layout");
 
 struct Layout {
   std::vector<int64_t> arena_off;  // per tensor, start in the per-worker arena (elements)

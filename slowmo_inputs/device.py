@@ -61,3 +61,18 @@ def fill(out, first_index: int, seed: int, worker: int, step: int, scale: float,
                                   torch.cuda.current_stream(out.device).cuda_stream)
     if rc != 0:
         raise RuntimeError(f"slowmo_inputs_fill failed with hipError {rc}")
+
+
+def fill_strided(buf, col0: int, n: int, first_index: int, seed: int, step: int, scale: float,
+                 n_workers: int) -> None:
+    """Fills buf[w, col0:col0+n] for workers w = 0..n_workers-1 (buf is a
+    contiguous 2-D CUDA tensor with one row per worker) in one launch."""
+    import torch
+    assert buf.is_cuda and buf.is_contiguous() and buf.dim() == 2 and buf.shape[0] == n_workers
+    assert 0 <= col0 and col0 + n <= buf.shape[1]
+    bf16 = {torch.float32: 0, torch.bfloat16: 1}[buf.dtype]
+    rc = lib().slowmo_inputs_fill(buf.data_ptr() + col0 * buf.element_size(), n, first_index, seed,
+                                  0, n_workers, buf.stride(0), step, scale, bf16,
+                                  torch.cuda.current_stream(buf.device).cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"slowmo_inputs_fill failed with hipError {rc}")

@@ -23,7 +23,11 @@ class GpuProblem:
       "flat"      one allocation per worker, tensors back to back without
                   padding, so tensors after an odd-sized one are not 16-byte
                   aligned; gradients of one step are then produced by a single
-                  launch over all workers.
+                  launch over all workers;
+      "padded"    (gradients) one allocation, every tensor starting at a
+                  multiple of 512 bytes as the caching allocator would place a
+                  separate allocation; one generator launch per tensor covers
+                  all workers.
     """
 
     def __init__(self, w: Workload, device="cuda:0", ring: int = 1,
@@ -56,6 +60,16 @@ class GpuProblem:
             self._gflat = [torch.zeros((w.m, max(self.d, 1)), dtype=self.gdtype, device=dev)
                            for _ in range(ring)]
             self.grads = [[views(g[i]) for i in range(w.m)] for g in self._gflat]
+        elif grad_layout == "padded":
+            unit = 512 // (2 if w.grad_dtype == "bf16" else 4)
+            sizes = np.asarray(self.numel, dtype=np.int64)
+            padded = (sizes + unit - 1) // unit * unit
+            self._goff = np.concatenate([[0], np.cumsum(padded)[:-1]]).astype(np.int64)
+            width = int(max(padded.sum(), unit))
+            self._gflat = [torch.zeros((w.m, width), dtype=self.gdtype, device=dev)
+                           for _ in range(ring)]
+            self.grads = [[[g[i][int(o):int(o) + n] for o, n in zip(self._goff, self.numel)]
+                           for i in range(w.m)] for g in self._gflat]
         else:
             self.grads = [[[torch.zeros(n, dtype=self.gdtype, device=dev) for n in self.numel]
                            for _ in range(w.m)] for _ in range(ring)]
@@ -68,6 +82,12 @@ class GpuProblem:
         if self.grad_layout == "flat":
             g = self._gflat[slot]
             _device.fill(g if w.m > 1 else g[0], 0, w.seed, 0, step, w.sigma, n_workers=w.m)
+        elif self.grad_layout == "padded":
+            g = self._gflat[slot]
+            for j, n in enumerate(self.numel):
+                if n:
+                    _device.fill_strided(g, int(self._goff[j]), n, int(self.starts[j]), w.seed,
+                                         step, w.sigma, w.m)
         else:
             for i in range(w.m):
                 for j, t in enumerate(self.grads[slot][i]):

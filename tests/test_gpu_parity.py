@@ -26,16 +26,21 @@ def _problem(w, **kw):
     return GpuProblem(w, "cuda:0", **kw)
 
 
-def _tile_edges(w):
-    """Global element indices where a local-step or outer-step run begins."""
+def _tile_edges(w, count=256):
+    """Global element indices where local-step / outer-step tiles begin (a
+    seeded sample of them).  Tiles are fixed-size pieces of a tensor; the size
+    is read off the library's own plan."""
     import paper_1910_00643_amd as P
-    starts = w.tensor_starts
+    t_local = max(r[3] for r in P.slowmo_plan_local(1, [100_000]))
+    t_outer = max(r[3] for r in P.slowmo_plan_outer(1, [100_000]))
+    rng = np.random.default_rng(w.seed)
+    starts, numel = w.tensor_starts, np.asarray(w.numel, dtype=np.int64)
     edges = set()
-    for (_, worker, tensor, n, off) in P.slowmo_plan_local(w.m, w.numel):
-        if worker == 0:
-            edges.add(int(starts[tensor] + off))
-    for (_, _, tensor, n, off) in P.slowmo_plan_outer(w.m, w.numel):
-        edges.add(int(starts[tensor] + off))
+    big = np.nonzero(numel > 0)[0]
+    for j in rng.choice(big, size=count, p=numel[big] / numel[big].sum()):
+        for t in (t_local, t_outer):
+            k = int(rng.integers(0, -(-numel[j] // t)))
+            edges.add(int(starts[j] + k * t))
     return sorted(edges)
 
 
@@ -79,6 +84,8 @@ def test_tiny_config_every_element():
     ("adam", "bf16", "maintain", "separate", "separate"),
     ("adam", "f32", "reset", "flat", "separate"),
     ("adam", "bf16", "maintain", "flat", "flat"),
+    ("sgd_nesterov", "f32", "reset", "separate", "padded"),
+    ("adam", "bf16", "maintain", "separate", "padded"),
 ])
 def test_ragged_tensor_list_every_element(base, grad_dtype, policy, param_layout, grad_layout):
     """26 tensors with lengths 0, 1, 2, 3, 5, ... 131077: ragged tails, empty
@@ -173,10 +180,9 @@ def test_call_sequence_errors_leave_state_unchanged():
 
 # ---- full sizes, sampled elements ------------------------------------------------
 def _sampled(w, rounds, n_random, ring=2, halo=4):
-    prob = _problem(w, ring=ring)
+    prob = _problem(w, ring=ring, grad_layout="padded")     # the layout bench.py times
     opt = PU.make_gpu(w, prob)
-    idx = prob.sample_indices(n_random, edges=_tile_edges(w)[:: max(1, len(_tile_edges(w)) // 256)],
-                              halo=halo, seed=w.seed)
+    idx = prob.sample_indices(n_random, edges=_tile_edges(w), halo=halo, seed=w.seed)
     worst = PU.compare_run(w, prob, opt, idx, rounds, bitwise_f32=(w.base == "sgd_nesterov"))
     print(w.name, "sampled", idx.size, "worst errors", worst)
     opt.close()
