@@ -26,7 +26,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "resnet50": 16407840067,            # profiles/resnet50_local_step_outer_step.md
+    "transformer_big": 43766540753,     # profiles/transformer_big_local_step_outer_step.md
+}
 
 
 def local_bytes_per_update(w, first: bool) -> int:
@@ -115,9 +118,10 @@ def time_workload(w, steps, warmup, ring=None):
     return wall, kern_ms
 
 
-def cpu_baseline(w, budget_s=15.0):
+def cpu_baseline(w, budget_s=12.0):
     """The fp32 build of the CPU oracle, as it stands, timed on this host's
-    cores over one outer iteration of a contiguous slice of the workload."""
+    cores over whole outer iterations of a contiguous slice of the workload
+    (about budget_s seconds of oracle time; gradient generation not timed)."""
     import numpy as np
     import torch
     from oracle import slowmo_oracle as O
@@ -125,36 +129,34 @@ def cpu_baseline(w, budget_s=15.0):
     lib = O.load("f32")
     cores = int(lib.oracle_num_threads())
     bf16 = w.grad_dtype == "bf16"
-
-    def one_round(n):
-        idx = np.arange(n, dtype=np.int64)
-        o = O.SlowMoOracle(G.initial_params(w.seed, idx), m=w.m, tau=w.tau, alpha=w.f32("alpha"),
-                           beta=w.f32("beta"), base=w.base, policy=w.policy,
-                           momentum=w.f32("momentum"), weight_decay=w.f32("weight_decay"),
-                           beta1=w.f32("beta1"), beta2=w.f32("beta2"), eps=w.f32("eps"), prec="f32")
-        g_dev = torch.empty((w.m, n), dtype=torch.bfloat16 if bf16 else torch.float32,
-                            device="cuda:0")
-        spent = 0.0
+    # slice: the first n elements of the flat range, all m workers; n bounded
+    # so that the oracle's state (x, h[, v], g per worker) stays near 2 GiB
+    n = int(min(w.d, (2 << 30) // (16 * w.m)))
+    idx = np.arange(n, dtype=np.int64)
+    o = O.SlowMoOracle(G.initial_params(w.seed, idx), m=w.m, tau=w.tau, alpha=w.f32("alpha"),
+                       beta=w.f32("beta"), base=w.base, policy=w.policy,
+                       momentum=w.f32("momentum"), weight_decay=w.f32("weight_decay"),
+                       beta1=w.f32("beta1"), beta2=w.f32("beta2"), eps=w.f32("eps"), prec="f32")
+    g_dev = torch.empty((w.m, n), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda:0")
+    spent, rounds, step = 0.0, 0, 0
+    while spent < budget_s and rounds < 50:
         for k in range(w.tau):
-            device.fill(g_dev if w.m > 1 else g_dev[0], 0, w.seed, 0, k, w.sigma, n_workers=w.m)
-            g = g_dev.to(torch.float32).cpu().numpy()      # gradient generation is not timed
+            device.fill(g_dev if w.m > 1 else g_dev[0], 0, w.seed, 0, step, w.sigma, n_workers=w.m)
+            g = g_dev.to(torch.float32).cpu().numpy()
             t0 = time.perf_counter()
             o.local_step(g, w.f32("lr"))
             spent += time.perf_counter() - t0
+            step += 1
         t0 = time.perf_counter()
         o.outer_step(w.f32("lr"))
         spent += time.perf_counter() - t0
-        return spent
-
-    n = min(w.d, 1 << 16)
-    t = one_round(n)                                        # warm-up and rate estimate
-    rate = w.m * n * w.tau / max(t, 1e-9)
-    n = int(min(w.d, max(n, rate * budget_s / (w.m * w.tau)), (4 << 30) // (16 * w.m)))
-    t = one_round(n)
-    return {"value": w.m * n * w.tau / t, "unit": "updates/s", "cores": cores, "kind": "oracle",
-            "sample": f"fp32 build of the oracle (gcc -O2, OpenMP over elements), one outer "
-                      f"iteration (tau={w.tau} local steps + outer step) of the first {n} "
-                      f"elements of the flat range on all m={w.m} workers, {t:.2f} s"}
+        rounds += 1
+    return {"value": w.m * n * w.tau * rounds / spent, "unit": "updates/s", "cores": cores,
+            "kind": "oracle",
+            "sample": f"fp32 build of the oracle (gcc -O2, OpenMP over elements, {cores} threads), "
+                      f"{rounds} outer iterations (tau={w.tau} local steps + outer step each) of "
+                      f"the first {n} elements of the flat range on all m={w.m} workers, "
+                      f"{spent:.1f} s of oracle time"}
 
 
 def main():
@@ -166,6 +168,9 @@ def main():
                     choices=["tiny", "resnet18", "resnet50", "transformer_big", "stress"])
     ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB copy kernel three times (a kernel of known "
+                         "traffic for scaling rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (m logical workers share it); "
@@ -177,6 +182,15 @@ def main():
     w = W.BY_NAME[args.workload]()
     ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
                             2 if w.name == "stress" else w.tau)
+    if args.calibrate_copy:
+        from slowmo_inputs import device
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            device.calib_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
     wall, kern_ms = time_workload(w, args.steps, args.warmup, ring)
     ms_per_step = 1e3 * wall / args.steps
     value = w.updates_per_round * args.steps / wall

@@ -58,7 +58,27 @@ __global__ __launch_bounds__(256) void k_fill(void *out, int64_t n, int64_t firs
   }
 }
 
+// Plain copy of n 16-byte vectors: a kernel of known traffic (16 n bytes
+// read, 16 n bytes written) against which hardware counters are scaled.
+__global__ __launch_bounds__(256) void k_calib_copy(const float4 *__restrict__ src,
+                                                    float4 *__restrict__ dst, int64_t n) {
+  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
 }  // namespace
+
+// Copies `bytes` (a multiple of 16, both pointers 16-byte aligned) from src to
+// dst on the device with k_calib_copy.  Returns 0 or a hipError_t value.
+extern "C" int slowmo_inputs_calib_copy(const void *src, void *dst, int64_t bytes, void *stream) {
+  if (bytes <= 0) return 0;
+  if (!src || !dst || bytes % 16) return static_cast<int>(hipErrorInvalidValue);
+  const int64_t n = bytes / 16;
+  hipLaunchKernelGGL(k_calib_copy, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const float4 *>(src),
+                     static_cast<float4 *>(dst), n);
+  return static_cast<int>(hipGetLastError());
+}
 
 // out[w * worker_stride + j] = scale * n(seed, worker0 + w, step, first_index + j)
 // for w in [0, n_workers), j in [0, n).  `out` is a device pointer of fp32

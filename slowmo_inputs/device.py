@@ -37,6 +37,8 @@ def lib() -> C.CDLL:
                                             C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                             C.c_float, C.c_int32, C.c_void_p]
         _lib.slowmo_inputs_fill.restype = C.c_int
+        _lib.slowmo_inputs_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.slowmo_inputs_calib_copy.restype = C.c_int
     return _lib
 
 
@@ -76,3 +78,16 @@ def fill_strided(buf, col0: int, n: int, first_index: int, seed: int, step: int,
                                   torch.cuda.current_stream(buf.device).cuda_stream)
     if rc != 0:
         raise RuntimeError(f"slowmo_inputs_fill failed with hipError {rc}")
+
+
+def calib_copy(src, dst) -> None:
+    """dst <- src with the plain copy kernel k_calib_copy (known traffic:
+    src.nbytes read, the same written), for scaling hardware counters."""
+    import torch
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size() and nbytes % 16 == 0
+    rc = lib().slowmo_inputs_calib_copy(src.data_ptr(), dst.data_ptr(), nbytes,
+                                        torch.cuda.current_stream(src.device).cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"slowmo_inputs_calib_copy failed with hipError {rc}")
