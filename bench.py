@@ -32,14 +32,15 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def local_bytes_per_update(w, first: bool) -> int:
+def local_bytes_per_update(w, first: bool, last: bool = False) -> int:
     """Algorithmic HBM bytes of one base-optimizer update of one (worker,
     element): x, h (and v) read and written, the gradient read; the first step
-    after a reset does not read the buffers."""
+    after a reset does not read the buffers, the last step before a reset does
+    not write them."""
     g = 2 if w.grad_dtype == "bf16" else 4
     nbuf = 2 if w.base == "adam" else 1
     reads = 4 + (0 if first else 4 * nbuf) + g
-    writes = 4 + 4 * nbuf
+    writes = 4 + (0 if last else 4 * nbuf)
     return reads + writes
 
 
@@ -49,8 +50,8 @@ def outer_bytes_per_element(w) -> int:
 
 def round_bytes(w) -> int:
     reset = w.policy == "reset"
-    per_worker_elem = (local_bytes_per_update(w, reset) +
-                       (w.tau - 1) * local_bytes_per_update(w, False))
+    per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0, reset and k == w.tau - 1)
+                          for k in range(w.tau))
     return w.d * (w.m * per_worker_elem + outer_bytes_per_element(w))
 
 
@@ -85,7 +86,10 @@ def run_rounds(w, opt, arrays, rounds, events=None):
             opt.local_step(arrays[k % ring], w.lr)
             if events is not None:
                 b.record()
-                events["local_first" if (k == 0 and w.policy == "reset") else "local"].append((a, b))
+                reset = w.policy == "reset"
+                kind = ("local_first" if (reset and k == 0) else
+                        "local_last" if (reset and k == w.tau - 1) else "local")
+                events[kind].append((a, b))
         if events is not None:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
@@ -107,7 +111,7 @@ def time_workload(w, steps, warmup, ring=None):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     # second pass: per-kernel durations from HIP events around every launch
-    events = {"local": [], "local_first": [], "outer": []}
+    events = {"local": [], "local_first": [], "local_last": [], "outer": []}
     run_rounds(w, opt, arrays, steps, events)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)

@@ -146,7 +146,9 @@ const char *slowmo_last_error(const slowmo_ctx *ctx);
  * Inspection (tests, checkpointing): device pointer to the first element of
  * an internal buffer of `tensor`: x0 / u (worker ignored), h / v of `worker`.
  * The numel[tensor] elements are contiguous.  Under the RESET policy h and v
- * are undefined between an outer step and the next local step.  ARG if the
+ * are undefined from the last local step of an outer iteration (whose buffer
+ * values nothing reads again, so they are not stored) until the next local
+ * step.  ARG if the
  * buffer does not exist (v without Adam) or an index is out of range.
  */
 slowmo_status slowmo_get_buffer(slowmo_ctx *ctx, int32_t which, int32_t worker, int32_t tensor,

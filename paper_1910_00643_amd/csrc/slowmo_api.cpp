@@ -251,6 +251,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->layout = make_layout(n_tensors, numel);
   ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
   ctx->tune.nontemporal = env_flag("SLOWMO_NT", 1) ? 1 : 0;
+  ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
   const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
@@ -435,8 +436,11 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
     a.rc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta1), static_cast<double>(l_next))));
     a.rc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta2), static_cast<double>(l_next))));
   }
+  // Under the reset policy the buffers written by the last step of an outer
+  // iteration are discarded before they are read again: skip those stores.
+  const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
   hipError_t e = launch_local_step(a, c.base, c.grad_dtype == SLOWMO_BF16, ctx->buffers_zero,
-                                   ctx->tune, stream);
+                                   dead_after, ctx->tune, stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
   ctx->k += 1;
   ctx->l = l_next;

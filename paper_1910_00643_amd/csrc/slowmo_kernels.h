@@ -41,11 +41,14 @@ struct OuterArgs {
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
+  int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
+                        // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
 
 // base: 0 SGD-Nesterov, 1 Adam.  bf16: gradient dtype.  first: the stored
 // h (and v) are to be read as zero (first step after a reset / after create).
-hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first,
+// last: h (and v) are dead after this step and are not written.
+hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
 

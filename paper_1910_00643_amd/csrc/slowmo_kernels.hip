@@ -151,7 +151,10 @@ __device__ __forceinline__ float outer_elem(float s, float x0, float &u, const O
 // One workgroup = one tile = up to 4 * blockDim elements of one (worker,
 // tensor).  Lane t owns elements [4t, 4t + 4) of the tile.
 
-template <int BASE, bool BF16, bool FIRST, bool NT>
+// FIRST: the stored buffers are to be read as zero (not loaded).  LAST: the
+// buffers are dead after this step (the reset policy discards them before
+// their next use), so they are not stored.
+template <int BASE, bool BF16, bool FIRST, bool LAST, bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_local_step(
     const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
     const void *const *__restrict__ gtab, float *__restrict__ hbase, float *__restrict__ vbase,
@@ -193,8 +196,8 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
       hv[c] = he;
     }
     st4<NT>(x + e0, xv);
-    st4<NT>(h + e0, hv);
-    if constexpr (BASE == 1) st4<NT>(v + e0, vv);
+    if constexpr (!LAST) st4<NT>(h + e0, hv);
+    if constexpr (!LAST && BASE == 1) st4<NT>(v + e0, vv);
   } else {
     // element-wise: the ragged tail of a tensor, or pointers that are not
     // 16-byte aligned
@@ -207,10 +210,10 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
       } else {
         float ve = FIRST ? 0.f : ld1(v + j);
         adam_elem<FIRST>(xe, he, ve, ge, ap);
-        st1(v + j, ve);
+        if constexpr (!LAST) st1(v + j, ve);
       }
       st1(x + j, xe);
-      st1(h + j, he);
+      if constexpr (!LAST) st1(h + j, he);
     }
   }
 }
@@ -218,6 +221,19 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
 // ---- outer step -----------------------------------------------------------------
 // One workgroup = one tile = up to 4 * blockDim elements of one tensor; lane t
 // owns elements [4t, 4t + 4) in all m replicas, x0 and u.
+
+#ifndef SLOWMO_OUTER_UNROLL
+#define SLOWMO_OUTER_UNROLL 8
+#endif
+#ifndef SLOWMO_OUTER_NTL
+#define SLOWMO_OUTER_NTL 1
+#endif
+#ifndef SLOWMO_OUTER_NTS
+#define SLOWMO_OUTER_NTS 1
+#endif
+#define SLOWMO_STR2(x) #x
+#define SLOWMO_STR(x) SLOWMO_STR2(x)
+#define SLOWMO_PRAGMA_UNROLL_OUTER _Pragma(SLOWMO_STR(unroll SLOWMO_OUTER_UNROLL))
 
 template <bool NT>
 __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
@@ -239,11 +255,12 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
   if (e0 >= n) return;
   if (aligned && e0 + 4 <= n) {
     // line 6: ordered sum over the replicas, i = 0, 1, ..., m-1
-    V4 acc = ld4<NT>(xp[0] + eo + e0);
-#pragma unroll 8
-    for (int i = 1; i < m; ++i) acc = acc + ld4<NT>(xp[i] + eo + e0);
-    V4 x0v = ld4<NT>(x0 + e0);
-    V4 uv = ld4<NT>(u + e0);
+    constexpr bool NTL = NT && SLOWMO_OUTER_NTL, NTS = NT && SLOWMO_OUTER_NTS;
+    V4 acc = ld4<NTL>(xp[0] + eo + e0);
+    SLOWMO_PRAGMA_UNROLL_OUTER
+    for (int i = 1; i < m; ++i) acc = acc + ld4<NTL>(xp[i] + eo + e0);
+    V4 x0v = ld4<NTL>(x0 + e0);
+    V4 uv = ld4<NTL>(u + e0);
     V4 xn;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -251,10 +268,10 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       xn[c] = outer_elem(acc[c], x0v[c], ue, p);
       uv[c] = ue;
     }
-    st4<NT>(u + e0, uv);
-    st4<NT>(x0 + e0, xn);
-#pragma unroll 8
-    for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
+    st4<NTS>(u + e0, uv);
+    st4<NTS>(x0 + e0, xn);
+    SLOWMO_PRAGMA_UNROLL_OUTER
+    for (int i = 0; i < m; ++i) st4<NTS>(xp[i] + eo + e0, xn);
   } else {
     const int e1 = e0 + 4 < n ? e0 + 4 : n;
     for (int j = e0; j < e1; ++j) {
@@ -280,38 +297,45 @@ Grid make_grid(int ntiles, int remap) {
   return g;
 }
 
-template <int BASE, bool BF16, bool FIRST>
+template <int BASE, bool BF16, bool FIRST, bool LAST>
 hipError_t launch_local_t(const LocalArgs &a, const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(a.ntiles, t.xcd_remap);
   const SgdP sp{a.lr, a.mu, a.wd};
   const AdamP ap{a.lr, a.wd, a.b1, a.b2, a.omb1, a.omb2, a.rc1, a.rc2, a.eps};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, true>), dim3(g.blocks), dim3(kLocalBlock),
-                       0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles, g.chunk, t.xcd_remap,
-                       sp, ap);
+    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, LAST, true>), dim3(g.blocks),
+                       dim3(kLocalBlock), 0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles,
+                       g.chunk, t.xcd_remap, sp, ap);
   } else {
-    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, false>), dim3(g.blocks),
+    hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, LAST, false>), dim3(g.blocks),
                        dim3(kLocalBlock), 0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles,
                        g.chunk, t.xcd_remap, sp, ap);
   }
   return hipGetLastError();
 }
 
+template <int BASE, bool BF16>
+hipError_t launch_local_b(const LocalArgs &a, bool first, bool last, const LaunchTuning &t,
+                          hipStream_t s) {
+  if (first) {
+    return last ? launch_local_t<BASE, BF16, true, true>(a, t, s)
+                : launch_local_t<BASE, BF16, true, false>(a, t, s);
+  }
+  return last ? launch_local_t<BASE, BF16, false, true>(a, t, s)
+              : launch_local_t<BASE, BF16, false, false>(a, t, s);
+}
+
 }  // namespace
 
-hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first,
+hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
   if (base == 0) {
-    if (bf16) {
-      return first ? launch_local_t<0, true, true>(a, t, s) : launch_local_t<0, true, false>(a, t, s);
-    }
-    return first ? launch_local_t<0, false, true>(a, t, s) : launch_local_t<0, false, false>(a, t, s);
+    return bf16 ? launch_local_b<0, true>(a, first, last, t, s)
+                : launch_local_b<0, false>(a, first, last, t, s);
   }
-  if (bf16) {
-    return first ? launch_local_t<1, true, true>(a, t, s) : launch_local_t<1, true, false>(a, t, s);
-  }
-  return first ? launch_local_t<1, false, true>(a, t, s) : launch_local_t<1, false, false>(a, t, s);
+  return bf16 ? launch_local_b<1, true>(a, first, last, t, s)
+              : launch_local_b<1, false>(a, first, last, t, s);
 }
 
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
@@ -319,10 +343,10 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   const Grid g = make_grid(a.ntiles, t.xcd_remap);
   const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_outer_step<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+    hipLaunchKernelGGL((k_outer_step<true>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s, a.tiles,
                        a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   } else {
-    hipLaunchKernelGGL((k_outer_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+    hipLaunchKernelGGL((k_outer_step<false>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s, a.tiles,
                        a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
   }
   return hipGetLastError();

@@ -20,6 +20,8 @@ class GpuProblem:
 
     param_layout / grad_layout:
       "separate"  every tensor is its own allocation (the allocator aligns it);
+      "arena"     (parameters) one allocation for all workers, every tensor
+                  512-byte aligned;
       "flat"      one allocation per worker, tensors back to back without
                   padding, so tensors after an odd-sized one are not 16-byte
                   aligned; gradients of one step are then produced by a single
@@ -50,6 +52,15 @@ class GpuProblem:
         if param_layout == "separate":
             self.params = [[torch.zeros(n, dtype=torch.float32, device=dev) for n in self.numel]
                            for _ in range(w.m)]
+        elif param_layout == "arena":
+            # one allocation for all workers, every tensor 512-byte aligned
+            sizes = np.asarray(self.numel, dtype=np.int64)
+            padded = (sizes + 127) // 128 * 128
+            poff = np.concatenate([[0], np.cumsum(padded)[:-1]]).astype(np.int64)
+            self._pflat = torch.zeros((w.m, int(max(padded.sum(), 128))), dtype=torch.float32,
+                                      device=dev)
+            self.params = [[self._pflat[i][int(o):int(o) + n] for o, n in zip(poff, self.numel)]
+                           for i in range(w.m)]
         else:
             self._pflat = torch.zeros((w.m, max(self.d, 1)), dtype=torch.float32, device=dev)
             self.params = [views(self._pflat[i]) for i in range(w.m)]
