@@ -138,3 +138,22 @@ void oracle_outer_step(REAL *xw, int m, int64_t d, REAL *x0, REAL *u,
             xw[(int64_t)i * d + j] = xn;
     }
 }
+
+/*
+ * Buffer strategy "average" (Appendix B.4, strategy 3; for the momentum
+ * buffer also Algorithm C.4, "double averaging"): every worker's buffer is
+ * replaced by the mean of the m workers' buffers, summed in worker order.
+ *   bw : m buffers, worker-major, buffer i at bw + i*d
+ */
+void oracle_average_buffers(REAL *bw, int m, int64_t d)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d; ++j) {
+        REAL s = bw[j];
+        for (int i = 1; i < m; ++i)
+            s = s + bw[(int64_t)i * d + j];
+        REAL mean = s / (REAL)m;
+        for (int i = 0; i < m; ++i)
+            bw[(int64_t)i * d + j] = mean;
+    }
+}

@@ -16,7 +16,9 @@ the bias-corrected second moment; the learning rate is a per-call scalar (the
 one given to the outer step is gamma_t of Eq. (2)-(3)); the mean is a
 left-to-right sum over workers 0..m-1 followed by a division by m; "reset"
 zeroes the buffers (and Adam's step counter) at the start of every outer
-iteration, "maintain" leaves them alone.
+iteration, "maintain" leaves them alone, "average" replaces every worker's
+buffers by their mean over the workers (same summation order as the
+parameters; Adam's step counter runs on).
 
 Parity pins: tests/test_oracle_pins.py.
 """
@@ -71,6 +73,8 @@ def load(prec: str = "f64", path: Optional[str] = None) -> C.CDLL:
     lib.oracle_adam_step.restype = None
     lib.oracle_outer_step.argtypes = [p, C.c_int, i64, p, p, dbl, dbl, dbl]
     lib.oracle_outer_step.restype = None
+    lib.oracle_average_buffers.argtypes = [p, C.c_int, i64]
+    lib.oracle_average_buffers.restype = None
     _loaded[key] = lib
     return lib
 
@@ -96,7 +100,7 @@ class SlowMoOracle:
         assert base in ("sgd_nesterov", "adam")
         if policy is None:      # the paper's defaults (Section 4, Appendix B.4)
             policy = "reset" if base == "sgd_nesterov" else "maintain"
-        assert policy in ("reset", "maintain")
+        assert policy in ("reset", "maintain", "average")
         assert m >= 1 and tau >= 1
         self.lib = lib if lib is not None else load(prec)
         self.dtype = np.float64 if prec == "f64" else np.float32
@@ -123,6 +127,10 @@ class SlowMoOracle:
             if self.v is not None:
                 self.v[...] = 0
             self.l = 0
+        elif self.policy == "average":
+            self.lib.oracle_average_buffers(_ptr(self.h), self.m, self.d)
+            if self.v is not None:
+                self.lib.oracle_average_buffers(_ptr(self.v), self.m, self.d)
         # "maintain": nothing to do
 
     # Algorithm 1 lines 3-5: one base-optimizer step on every worker

@@ -421,4 +421,84 @@ def pin_outer_uses_lr_of_outer_call(make):
     _close(outs[0][1], 4.0 * outs[1][1], rtol=1e-12, what="u scales with 1/gamma")
 
 
+# --------------------------- buffer strategy "average" (Appendix B.4, Alg. C.4)
+
+def pin_average_policy_degenerate_cases(make):
+    """Averaging over one worker, or over workers that all see the same
+    gradients, changes nothing: the run equals the "maintain" run."""
+    rng = _rng(20)
+    T, tau, d, lr = 3, 3, 7, 0.05
+    x_init = rng.standard_normal(d)
+    for base, kw in (("sgd_nesterov", dict(momentum=0.9, weight_decay=1e-3)),
+                     ("adam", dict(beta2=0.98))):
+        g1 = _grads(rng, T, tau, 1, d)
+        same = np.repeat(g1, 3, axis=2)
+        for m, g in ((1, g1), (3, same)):
+            res = []
+            for policy in ("maintain", "average"):
+                o = make(x_init, m=m, tau=tau, alpha=0.8, beta=0.5, base=base, policy=policy, **kw)
+                o.run(lambda t, k: g[t, k], lr, T)
+                res.append((o.x0.copy(), o.h.copy()))
+            _close(res[0][0], res[1][0], rtol=1e-13, what=f"average == maintain ({base}, m={m})")
+            _close(res[0][1], res[1][1], rtol=1e-13, what="buffers")
+
+
+def pin_average_policy_mean_iterate_is_single_worker_nesterov(make):
+    """The Nesterov base is linear in (x, h, g), and averaging parameters and
+    buffers leaves their worker-means unchanged; so with alpha = 1, beta = 0
+    the outer iterate follows the library's Nesterov SGD driven by the
+    worker-mean gradient, momentum running across the outer iterations
+    (Algorithm C.4 with its two AllReduces)."""
+    rng = _rng(21)
+    T, tau, m, d, lr, mu, wd = 4, 3, 4, 9, 0.05, 0.9, 1e-2
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.0, momentum=mu, weight_decay=wd,
+             policy="average")
+    p = torch.tensor(x_init, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, nesterov=True, weight_decay=wd)
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+            p.grad = torch.tensor(g[t, k].astype(np.float64).mean(axis=0))
+            opt.step()
+        o.outer_step(lr)
+        _close(o.x0, p.detach().numpy(), rtol=1e-11, atol=1e-12, what=f"mean iterate, t={t}")
+    hbar = opt.state[p]["momentum_buffer"].numpy()
+    _close(o.h.mean(axis=0), hbar, rtol=1e-11, atol=1e-12, what="mean momentum buffer")
+
+
+def pin_average_policy_makes_buffers_common(make):
+    """At the start of outer iteration t >= 1 every worker holds the same
+    buffers, the mean of the previous ones: after one more step,
+    h_i - g_i = mu * mean(h_prev) for all i (SGD, wd = 0), and for Adam
+    h_i - (1-b1) g_i = b1 * mean(h_prev), v_i - (1-b2) g_i^2 = b2 * mean(v_prev)."""
+    rng = _rng(22)
+    tau, m, d, lr, mu, b1, b2 = 3, 4, 6, 0.05, 0.9, 0.9, 0.98
+    g = _grads(rng, 2, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.3, momentum=mu, policy="average")
+    for k in range(tau):
+        o.local_step(g[0, k], lr)
+    h_prev = o.h.mean(axis=0)
+    assert np.abs(o.h - h_prev).max() > 1e-3
+    o.outer_step(lr)
+    o.local_step(g[1, 0], lr)
+    for i in range(m):
+        _close(o.h[i] - g[1, 0, i].astype(np.float64), mu * h_prev, rtol=1e-11, atol=1e-12,
+               what=f"SGD buffer of worker {i}")
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.3, base="adam", beta1=b1, beta2=b2,
+             policy="average")
+    for k in range(tau):
+        o.local_step(g[0, k], lr)
+    h_prev, v_prev, l_prev = o.h.mean(axis=0), o.v.mean(axis=0), o.l
+    o.outer_step(lr)
+    o.local_step(g[1, 0], lr)
+    assert o.l == l_prev + 1            # the step count runs on
+    gi = g[1, 0].astype(np.float64)
+    for i in range(m):
+        _close(o.h[i] - (1 - b1) * gi[i], b1 * h_prev, rtol=1e-10, atol=1e-12, what="Adam h")
+        _close(o.v[i] - (1 - b2) * gi[i] ** 2, b2 * v_prev, rtol=1e-10, atol=1e-12, what="Adam v")
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

@@ -47,6 +47,10 @@ C_MUTANTS = [
     ("outer_u_not_stored", "u[j] = un;", "u[j] = u[j];", 0),
     ("outer_broadcasts_mean", "xw[(int64_t)i * d + j] = xn;", "xw[(int64_t)i * d + j] = xbar;", 0),
     ("outer_no_broadcast", "xw[(int64_t)i * d + j] = xn;", ";", 0),
+    ("average_no_division", "REAL mean = s / (REAL)m;", "REAL mean = s;", 0),
+    ("average_drops_last_worker", "for (int i = 1; i < m; ++i)", "for (int i = 1; i < m - 1; ++i)", 1),
+    ("average_not_written_back", "bw[(int64_t)i * d + j] = mean;", ";", 0),
+    ("average_writes_sum", "bw[(int64_t)i * d + j] = mean;", "bw[(int64_t)i * d + j] = s;", 0),
     ("outer_transposed_replicas", "s = s + xw[(int64_t)i * d + j];", "s = s + xw[(int64_t)j * m + i];", 0),
 ]
 
@@ -64,6 +68,9 @@ PY_MUTANTS = [
      "_ptr(self.x[i]), _ptr(self.h[0]), _ptr(g[i]), self.d,", 0),
     ("adam_all_workers_use_grad0", "_ptr(self.v[i]), _ptr(g[i]),", "_ptr(self.v[i]), _ptr(g[0]),", 0),
     ("outer_alpha_beta_swapped", "lr, self.alpha, self.beta)", "lr, self.beta, self.alpha)", 0),
+    ("average_skips_v", "            if self.v is not None:\n                self.lib.oracle_average_buffers(_ptr(self.v), self.m, self.d)\n", "", 0),
+    ("average_skips_h", "            self.lib.oracle_average_buffers(_ptr(self.h), self.m, self.d)\n", "            pass\n", 0),
+    ("average_resets_step_count", '        elif self.policy == "average":\n', '        elif self.policy == "average":\n            self.l = 0\n', 0),
     ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
      'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
 ]
