@@ -45,7 +45,10 @@ def local_bytes_per_update(w, first: bool, last: bool = False) -> int:
 
 
 def outer_bytes_per_element(w) -> int:
-    return 8 * w.m + 16         # m replicas + x0 + u read, the same written
+    b = 8 * w.m + 16            # m replicas + x0 + u read, the same written
+    if w.policy == "average":   # + every worker's h (and v) read and written
+        b += 8 * w.m * (2 if w.base == "adam" else 1)
+    return b
 
 
 def round_bytes(w) -> int:
@@ -171,6 +174,8 @@ def main():
     ap.add_argument("--workload", default="resnet50",
                     choices=["tiny", "resnet18", "resnet50", "transformer_big", "stress"])
     ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
+    ap.add_argument("--policy", default=None, choices=["reset", "maintain", "average"],
+                    help="override the workload's buffer strategy")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (a kernel of known "
@@ -184,6 +189,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     w = W.BY_NAME[args.workload]()
+    if args.policy:
+        import dataclasses
+        w = dataclasses.replace(w, policy=args.policy)
     ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
                             2 if w.name == "stress" else w.tau)
     if args.calibrate_copy:

@@ -56,8 +56,12 @@ typedef enum { SLOWMO_SGD_NESTEROV = 0, SLOWMO_ADAM = 1 } slowmo_base;
 /* What happens to the base optimizer's buffers at the start of an outer
  * iteration (Algorithm 1 line 2; Appendix B.4).  RESET: h (and v, and Adam's
  * step count) restart from zero -- the paper's default for SGD.  MAINTAIN:
- * they carry over -- the paper's default for Adam. */
-typedef enum { SLOWMO_BUF_RESET = 0, SLOWMO_BUF_MAINTAIN = 1 } slowmo_bufpolicy;
+ * they carry over -- the paper's default for Adam.  AVERAGE: every worker's
+ * h (and v) is replaced by the mean over the workers, summed in worker order
+ * (Appendix B.4 strategy 3; with alpha = 1, beta = 0 and the SGD base this is
+ * the double-averaging scheme of Algorithm C.4); Adam's step count runs on.
+ * The averaging is done by slowmo_outer_step in the same kernel. */
+typedef enum { SLOWMO_BUF_RESET = 0, SLOWMO_BUF_MAINTAIN = 1, SLOWMO_BUF_AVERAGE = 2 } slowmo_bufpolicy;
 
 typedef enum { SLOWMO_F32 = 0, SLOWMO_BF16 = 1 } slowmo_dtype; /* gradient element type */
 
@@ -125,7 +129,9 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
  *   u   <- beta * u + (x0 - xbar) / lr                     Eq. (2)
  *   x0  <- x0 - (alpha * lr) * u                           Eq. (3)
  *   x^{(i)} <- x0 for every worker i,
- * and arms the buffer policy for the next outer iteration (line 2).
+ * and applies the buffer policy for the next outer iteration (line 2): RESET
+ * arms a flag (no memory is touched), AVERAGE replaces h^{(i)} (and v^{(i)})
+ * by their mean over i in the same pass.
  *   lr : gamma_t, finite and > 0 (Eq. (2) divides by it).
  * Errors: ARG, HIP; STATE unless exactly tau local steps were taken since the
  * previous outer step (or since creation).

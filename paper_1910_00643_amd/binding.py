@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("SLOWMO_LIBRARY") or os.path.join(_HERE, "libslowmo.so
 SLOWMO_OK, SLOWMO_ERR_ARG, SLOWMO_ERR_STATE = 0, -1, -2
 SLOWMO_ERR_ALIGN, SLOWMO_ERR_HIP, SLOWMO_ERR_NOMEM = -3, -4, -5
 SLOWMO_SGD_NESTEROV, SLOWMO_ADAM = 0, 1
-SLOWMO_BUF_RESET, SLOWMO_BUF_MAINTAIN = 0, 1
+SLOWMO_BUF_RESET, SLOWMO_BUF_MAINTAIN, SLOWMO_BUF_AVERAGE = 0, 1, 2
 SLOWMO_F32, SLOWMO_BF16 = 0, 1
 SLOWMO_BUF_X0, SLOWMO_BUF_U, SLOWMO_BUF_H, SLOWMO_BUF_V = 0, 1, 2, 3
 SLOWMO_MAX_WORKERS = 1024

@@ -70,7 +70,8 @@ std::string check_config(const slowmo_config *c, int32_t n_tensors, const int64_
   if (!finite_pos(c->alpha)) return "alpha must be finite and > 0";
   if (!unit_interval(c->beta)) return "beta must satisfy 0 <= beta < 1";
   if (c->base != SLOWMO_SGD_NESTEROV && c->base != SLOWMO_ADAM) return "unknown base optimizer";
-  if (c->policy != SLOWMO_BUF_RESET && c->policy != SLOWMO_BUF_MAINTAIN)
+  if (c->policy != SLOWMO_BUF_RESET && c->policy != SLOWMO_BUF_MAINTAIN &&
+      c->policy != SLOWMO_BUF_AVERAGE)
     return "unknown buffer policy";
   if (c->grad_dtype != SLOWMO_F32 && c->grad_dtype != SLOWMO_BF16) return "unknown gradient dtype";
   if (!(std::isfinite(c->weight_decay) && c->weight_decay >= 0.f))
@@ -466,6 +467,11 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   a.alpha_lr = c.alpha * lr;  // one fp32 rounding, as (alpha * gamma_t) in Eq. (3)
   a.beta = c.beta;
   a.m_f = static_cast<float>(c.m);
+  if (c.policy == SLOWMO_BUF_AVERAGE) {  // Algorithm 1 line 2 of the next outer iteration
+    a.avg_h = ctx->h;
+    a.avg_v = ctx->v;  // nullptr unless Adam
+    a.d_pad = ctx->layout.d_pad;
+  }
   hipError_t e = launch_outer_step(a, ctx->tune, static_cast<hipStream_t>(stream_));
   if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
   ctx->k = 0;

@@ -36,6 +36,10 @@ struct OuterArgs {
   float alpha_lr;              // alpha * gamma_t, rounded once to fp32
   float beta;
   float m_f;                   // (float) m
+  // buffer strategy "average": arenas to average over the workers (nullptr = skip)
+  float *avg_h;
+  float *avg_v;
+  int64_t d_pad;               // worker stride of the arenas, elements
 };
 
 struct LaunchTuning {

@@ -235,11 +235,38 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
 #define SLOWMO_STR(x) SLOWMO_STR2(x)
 #define SLOWMO_PRAGMA_UNROLL_OUTER _Pragma(SLOWMO_STR(unroll SLOWMO_OUTER_UNROLL))
 
-template <bool NT>
+// Buffer strategy "average" for this lane's elements of one arena (h or v):
+// every worker's value becomes the ordered mean over the workers.  The arena
+// is 16-byte aligned by construction, so only a ragged tail is element-wise.
+template <bool NTL, bool NTS>
+__device__ __forceinline__ void average_arena(float *__restrict__ b0, int64_t stride, int m,
+                                              float m_f, int e0, int n) {
+  if (e0 + 4 <= n) {
+    V4 acc = ld4<NTL>(b0 + e0);
+    SLOWMO_PRAGMA_UNROLL_OUTER
+    for (int i = 1; i < m; ++i) acc = acc + ld4<NTL>(b0 + i * stride + e0);
+    V4 mean;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) mean[c] = acc[c] / m_f;
+    SLOWMO_PRAGMA_UNROLL_OUTER
+    for (int i = 0; i < m; ++i) st4<NTS>(b0 + i * stride + e0, mean);
+  } else {
+    for (int j = e0; j < n; ++j) {
+      float s = ld1(b0 + j);
+      for (int i = 1; i < m; ++i) s = s + ld1(b0 + i * stride + j);
+      float mean = s / m_f;
+      for (int i = 0; i < m; ++i) st1(b0 + i * stride + j, mean);
+    }
+  }
+}
+
+// AVG: 0 = lines 6-8 only; 1 = also average h over the workers; 2 = h and v.
+template <bool NT, int AVG>
 __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
-    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap, int m,
-    OuterP p) {
+    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
+    float *__restrict__ hbase, float *__restrict__ vbase, int64_t d_pad, int ntiles, int chunk,
+    int remap, int m, OuterP p) {
   const int tile = tile_of(blockIdx.x, chunk, remap);
   if (tile >= ntiles) return;
   const TileRef t = tiles[tile];         // uniform: scalar loads
@@ -253,9 +280,9 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
   float *u = ubase + ti.fo + eo;
   const int e0 = 4 * static_cast<int>(threadIdx.x);
   if (e0 >= n) return;
+  constexpr bool NTL = NT && SLOWMO_OUTER_NTL, NTS = NT && SLOWMO_OUTER_NTS;
   if (aligned && e0 + 4 <= n) {
     // line 6: ordered sum over the replicas, i = 0, 1, ..., m-1
-    constexpr bool NTL = NT && SLOWMO_OUTER_NTL, NTS = NT && SLOWMO_OUTER_NTS;
     V4 acc = ld4<NTL>(xp[0] + eo + e0);
     SLOWMO_PRAGMA_UNROLL_OUTER
     for (int i = 1; i < m; ++i) acc = acc + ld4<NTL>(xp[i] + eo + e0);
@@ -284,6 +311,9 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
     }
   }
+  // line 2 of the next outer iteration, strategy "average"
+  if constexpr (AVG >= 1) average_arena<NTL, NTS>(hbase + ti.fo + eo, d_pad, m, p.m_f, e0, n);
+  if constexpr (AVG >= 2) average_arena<NTL, NTS>(vbase + ti.fo + eo, d_pad, m, p.m_f, e0, n);
 }
 
 struct Grid {
@@ -338,18 +368,25 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
               : launch_local_b<1, false>(a, first, last, t, s);
 }
 
-hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.ntiles <= 0) return hipSuccess;
+template <bool NT, int AVG>
+hipError_t launch_outer_t(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(a.ntiles, t.xcd_remap);
   const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
-  if (t.nontemporal) {
-    hipLaunchKernelGGL((k_outer_step<true>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s, a.tiles,
-                       a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
-  } else {
-    hipLaunchKernelGGL((k_outer_step<false>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s, a.tiles,
-                       a.tensors, a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, a.m, p);
-  }
+  hipLaunchKernelGGL((k_outer_step<NT, AVG>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s,
+                     a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad, a.ntiles,
+                     g.chunk, t.xcd_remap, a.m, p);
   return hipGetLastError();
+}
+
+hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
+  if (t.nontemporal) {
+    return avg == 0 ? launch_outer_t<true, 0>(a, t, s)
+                    : avg == 1 ? launch_outer_t<true, 1>(a, t, s) : launch_outer_t<true, 2>(a, t, s);
+  }
+  return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
+                  : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
 }
 
 }  // namespace slowmo

@@ -12,7 +12,8 @@ import torch
 from . import binding as B
 
 _BASE = {"sgd_nesterov": B.SLOWMO_SGD_NESTEROV, "adam": B.SLOWMO_ADAM}
-_POLICY = {"reset": B.SLOWMO_BUF_RESET, "maintain": B.SLOWMO_BUF_MAINTAIN}
+_POLICY = {"reset": B.SLOWMO_BUF_RESET, "maintain": B.SLOWMO_BUF_MAINTAIN,
+           "average": B.SLOWMO_BUF_AVERAGE}
 _DTYPE = {"f32": B.SLOWMO_F32, "bf16": B.SLOWMO_BF16}
 _TORCH_GRAD = {"f32": torch.float32, "bf16": torch.bfloat16}
 

@@ -84,6 +84,10 @@ def test_tiny_config_every_element():
     ("adam", "bf16", "maintain", "separate", "separate"),
     ("adam", "f32", "reset", "flat", "separate"),
     ("adam", "bf16", "maintain", "flat", "flat"),
+    ("sgd_nesterov", "f32", "average", "separate", "separate"),   # Alg. C.4-style buffers
+    ("sgd_nesterov", "bf16", "average", "flat", "flat"),
+    ("adam", "bf16", "average", "separate", "padded"),
+    ("adam", "f32", "average", "flat", "flat"),
     ("sgd_nesterov", "f32", "reset", "separate", "padded"),
     ("adam", "bf16", "maintain", "separate", "padded"),
 ])
@@ -201,6 +205,13 @@ def test_resnet50_shaped_sampled():
 def test_transformer_big_shaped_sampled():
     w = W.transformer_big()
     _sampled(w, w.rounds, 3000)
+
+
+def test_resnet50_shaped_average_policy_sampled():
+    """Buffer strategy "average" at full size (the outer kernel also averages
+    the m momentum buffers)."""
+    w = dataclasses.replace(W.resnet50(), policy="average", rounds=4)
+    _sampled(w, w.rounds, 1500)
 
 
 def test_stress_1e9_sampled():
