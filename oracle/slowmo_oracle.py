@@ -18,7 +18,8 @@ left-to-right sum over workers 0..m-1 followed by a division by m; "reset"
 zeroes the buffers (and Adam's step counter) at the start of every outer
 iteration, "maintain" leaves them alone, "average" replaces every worker's
 buffers by their mean over the workers (same summation order as the
-parameters; Adam's step counter runs on).
+parameters; Adam's step counter runs on).  exact_average=False is the
+"SlowMo-noaverage" variant of Section 6: no line 6, per-worker x0 and u.
 
 Parity pins: tests/test_oracle_pins.py.
 """
@@ -96,7 +97,8 @@ class SlowMoOracle:
                  base: str = "sgd_nesterov", policy: Optional[str] = None,
                  momentum: float = 0.0, weight_decay: float = 0.0,
                  beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
-                 prec: str = "f64", lib: Optional[C.CDLL] = None):
+                 prec: str = "f64", lib: Optional[C.CDLL] = None,
+                 exact_average: bool = True):
         assert base in ("sgd_nesterov", "adam")
         if policy is None:      # the paper's defaults (Section 4, Appendix B.4)
             policy = "reset" if base == "sgd_nesterov" else "maintain"
@@ -111,9 +113,15 @@ class SlowMoOracle:
         self.base, self.policy = base, policy
         self.momentum, self.weight_decay = float(momentum), float(weight_decay)
         self.beta1, self.beta2, self.eps = float(beta1), float(beta2), float(eps)
+        self.exact_average = bool(exact_average)
         self.x0 = x_init.astype(self.dtype).reshape(self.d).copy()
         self.x = np.tile(self.x0, (self.m, 1))
         self.u = np.zeros(self.d, self.dtype)
+        if not self.exact_average:
+            # Section 6, "SlowMo-noaverage": line 6 is skipped and every worker
+            # keeps its own outer iterate and slow momentum buffer
+            self.x0 = self.x.copy()
+            self.u = np.zeros((self.m, self.d), self.dtype)
         self.h = np.zeros((self.m, self.d), self.dtype)
         self.v = np.zeros((self.m, self.d), self.dtype) if base == "adam" else None
         self.t = 0      # outer iteration
@@ -157,8 +165,15 @@ class SlowMoOracle:
     # Algorithm 1 lines 6-8 (+ copy of x_{t+1,0} into every replica)
     def outer_step(self, lr: float) -> None:
         assert self.k == self.tau, "outer step needs exactly tau local steps"
-        self.lib.oracle_outer_step(_ptr(self.x), self.m, self.d, _ptr(self.x0),
-                                   _ptr(self.u), lr, self.alpha, self.beta)
+        if self.exact_average:
+            self.lib.oracle_outer_step(_ptr(self.x), self.m, self.d, _ptr(self.x0),
+                                       _ptr(self.u), lr, self.alpha, self.beta)
+        else:
+            # lines 7-8 on each worker's own replica: the "average" over that
+            # one replica is the replica itself
+            for i in range(self.m):
+                self.lib.oracle_outer_step(_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),
+                                           _ptr(self.u[i]), lr, self.alpha, self.beta)
         self.k = 0
         self.t += 1
 

@@ -501,4 +501,44 @@ def pin_average_policy_makes_buffers_common(make):
         _close(o.v[i] - (1 - b2) * gi[i] ** 2, b2 * v_prev, rtol=1e-10, atol=1e-12, what="Adam v")
 
 
+# ------------------------------------ Section 6: SlowMo without the exact average
+
+def pin_noaverage_is_m_independent_single_worker_runs(make):
+    """Section 6 (SlowMo-noaverage): without line 6 each worker applies lines
+    7-8 to its own replica, so the m workers never interact: the run equals m
+    separate single-worker runs on each worker's gradients."""
+    rng = _rng(30)
+    T, tau, m, d, lr = 3, 4, 3, 8, 0.05
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    for base, kw in (("sgd_nesterov", dict(momentum=0.9, weight_decay=1e-3, policy="reset")),
+                     ("adam", dict(beta2=0.98, policy="maintain"))):
+        o = make(x_init, m=m, tau=tau, alpha=0.9, beta=0.6, base=base, exact_average=False, **kw)
+        o.run(lambda t, k: g[t, k], lr, T)
+        assert o.x0.shape == (m, d) and o.u.shape == (m, d)
+        for i in range(m):
+            s = make(x_init, m=1, tau=tau, alpha=0.9, beta=0.6, base=base, **kw)
+            s.run(lambda t, k: g[t, k, i:i + 1], lr, T)
+            _close(o.x0[i], s.x0, rtol=1e-13, what=f"x0 of worker {i} ({base})")
+            _close(o.u[i], s.u, rtol=1e-13, what=f"u of worker {i}")
+            _close(o.x[i], s.x[0], rtol=1e-13, what=f"replica of worker {i}")
+        assert np.abs(o.x0[0] - o.x0[1]).max() > 1e-3      # no consensus without line 6
+
+
+def pin_noaverage_with_common_gradients_equals_slowmo(make):
+    """If all workers see the same gradients their replicas coincide, the
+    average changes nothing, and both variants give the same iterates."""
+    rng = _rng(31)
+    T, tau, m, d, lr = 3, 3, 4, 6, 0.05
+    g = np.repeat(_grads(rng, T, tau, 1, d), m, axis=2)
+    x_init = rng.standard_normal(d)
+    a = make(x_init, m=m, tau=tau, alpha=0.8, beta=0.5, momentum=0.9)
+    b = make(x_init, m=m, tau=tau, alpha=0.8, beta=0.5, momentum=0.9, exact_average=False)
+    a.run(lambda t, k: g[t, k], lr, T)
+    b.run(lambda t, k: g[t, k], lr, T)
+    for i in range(m):
+        _close(b.x0[i], a.x0, rtol=1e-13, what="x0")
+        _close(b.u[i], a.u, rtol=1e-13, what="u")
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

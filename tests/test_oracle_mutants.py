@@ -71,6 +71,9 @@ PY_MUTANTS = [
     ("average_skips_v", "            if self.v is not None:\n                self.lib.oracle_average_buffers(_ptr(self.v), self.m, self.d)\n", "", 0),
     ("average_skips_h", "            self.lib.oracle_average_buffers(_ptr(self.h), self.m, self.d)\n", "            pass\n", 0),
     ("average_resets_step_count", '        elif self.policy == "average":\n', '        elif self.policy == "average":\n            self.l = 0\n', 0),
+    ("noaverage_shares_x0", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[0]),", 0),
+    ("noaverage_shares_u", "_ptr(self.u[i]), lr, self.alpha, self.beta)", "_ptr(self.u[0]), lr, self.alpha, self.beta)", 0),
+    ("noaverage_only_worker0", "            for i in range(self.m):\n                self.lib.oracle_outer_step(", "            for i in range(1):\n                self.lib.oracle_outer_step(", 0),
     ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
      'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
 ]
