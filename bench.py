@@ -45,6 +45,8 @@ def local_bytes_per_update(w, first: bool, last: bool = False) -> int:
 
 
 def outer_bytes_per_element(w) -> int:
+    if not w.exact_average:     # per worker: x, x0, u read and written
+        return 24 * w.m
     b = 8 * w.m + 16            # m replicas + x0 + u read, the same written
     if w.policy == "average":   # + every worker's h (and v) read and written
         b += 8 * w.m * (2 if w.base == "adam" else 1)
@@ -68,7 +70,8 @@ def build_problem(w, ring):
     prob = GpuProblem(w, "cuda:0", ring=ring, grad_layout="padded")
     cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
                       policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
-                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
+                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                      no_average=not w.exact_average)
     opt = SlowMo(prob.params, cfg)
     for s in range(ring):
         prob.fill_grads(s, s)
@@ -176,6 +179,8 @@ def main():
     ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
     ap.add_argument("--policy", default=None, choices=["reset", "maintain", "average"],
                     help="override the workload's buffer strategy")
+    ap.add_argument("--no-average", action="store_true",
+                    help="the variant without the exact average (Section 6 of the paper)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (a kernel of known "
@@ -189,9 +194,11 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     w = W.BY_NAME[args.workload]()
+    import dataclasses
     if args.policy:
-        import dataclasses
         w = dataclasses.replace(w, policy=args.policy)
+    if args.no_average:
+        w = dataclasses.replace(w, exact_average=False)
     ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
                             2 if w.name == "stress" else w.tau)
     if args.calibrate_copy:
@@ -215,7 +222,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}-shaped tensor list ({len(w.numel)} tensors, d={w.d}), "
                                f"m={w.m}, tau={w.tau}, base={w.base}, grads={w.grad_dtype}, "
-                               f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}",
+                               f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}"
+                               + ("" if w.exact_average else ", no exact average"),
                    "step": "one outer iteration: tau local steps on all m workers + outer step",
                    "gradient_sets_resident": ring},
         "hbm_gbps_whole_round": round_bytes(w) / wall * args.steps / 1e9,

@@ -78,6 +78,11 @@ typedef struct {
   float weight_decay;  /* coupled L2 term added to the gradient: g + wd * x, >= 0 */
   float beta1, beta2;  /* Adam moment factors, 0 <= . < 1 */
   float eps;           /* Adam epsilon (added after the square root), >= 0 */
+  int32_t no_average;  /* 0: Algorithm 1 as printed (exact average, line 6).
+                          1: the "SlowMo-noaverage" variant of Section 6: line 6 is
+                          skipped, every worker applies lines 7-8 to its own replica
+                          and keeps its own x0 and u (the workspace grows by
+                          2 (m - 1) d floats); not combinable with SLOWMO_BUF_AVERAGE */
 } slowmo_config;
 
 #define SLOWMO_MAX_WORKERS 1024
@@ -129,6 +134,8 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
  *   u   <- beta * u + (x0 - xbar) / lr                     Eq. (2)
  *   x0  <- x0 - (alpha * lr) * u                           Eq. (3)
  *   x^{(i)} <- x0 for every worker i,
+ * (with cfg.no_average: per worker i, xbar := x^{(i)}, u^{(i)}, x0^{(i)} in place
+ * of the shared ones, x^{(i)} <- x0^{(i)}; Section 6)
  * and applies the buffer policy for the next outer iteration (line 2): RESET
  * arms a flag (no memory is touched), AVERAGE replaces h^{(i)} (and v^{(i)})
  * by their mean over i in the same pass.
@@ -150,7 +157,8 @@ const char *slowmo_last_error(const slowmo_ctx *ctx);
 
 /*
  * Inspection (tests, checkpointing): device pointer to the first element of
- * an internal buffer of `tensor`: x0 / u (worker ignored), h / v of `worker`.
+ * an internal buffer of `tensor`: x0 / u (worker ignored, unless cfg.no_average
+ * gave every worker its own), h / v of `worker`.
  * The numel[tensor] elements are contiguous.  Under the RESET policy h and v
  * are undefined from the last local step of an outer iteration (whose buffer
  * values nothing reads again, so they are not stored) until the next local

@@ -36,7 +36,8 @@ class slowmo_config(C.Structure):
     _fields_ = [("m", C.c_int32), ("tau", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
                 ("base", C.c_int32), ("policy", C.c_int32), ("grad_dtype", C.c_int32),
                 ("momentum", C.c_float), ("weight_decay", C.c_float),
-                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("no_average", C.c_int32)]
 
 
 class slowmo_plan_run(C.Structure):

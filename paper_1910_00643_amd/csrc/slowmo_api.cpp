@@ -43,8 +43,9 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   };
   const size_t arena = static_cast<size_t>(L.d_pad) * sizeof(float);
   const size_t n_ptr = static_cast<size_t>(c.m) * n_tensors;
-  s.x0 = take(arena);
-  s.u = take(arena);
+  const size_t outer_copies = c.no_average ? static_cast<size_t>(c.m) : 1;
+  s.x0 = take(arena * outer_copies);
+  s.u = take(arena * outer_copies);
   s.h = take(arena * c.m);
   s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
   s.xtab_t = take(n_ptr * sizeof(void *));
@@ -74,6 +75,9 @@ std::string check_config(const slowmo_config *c, int32_t n_tensors, const int64_
       c->policy != SLOWMO_BUF_AVERAGE)
     return "unknown buffer policy";
   if (c->grad_dtype != SLOWMO_F32 && c->grad_dtype != SLOWMO_BF16) return "unknown gradient dtype";
+  if (c->no_average != 0 && c->no_average != 1) return "no_average must be 0 or 1";
+  if (c->no_average && c->policy == SLOWMO_BUF_AVERAGE)
+    return "no_average cannot be combined with the AVERAGE buffer policy";
   if (!(std::isfinite(c->weight_decay) && c->weight_decay >= 0.f))
     return "weight_decay must be finite and >= 0";
   if (c->base == SLOWMO_SGD_NESTEROV) {
@@ -352,17 +356,20 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
 
   // u_0 = 0, h = v = 0 (Algorithm 1, "Input"; Table C.1 caption)
   const size_t arena = static_cast<size_t>(L.d_pad) * sizeof(float);
-  CREATE_HIP(hipMemsetAsync(ctx->x0, 0, arena, stream), "clearing x0");
-  CREATE_HIP(hipMemsetAsync(ctx->u, 0, arena, stream), "clearing u");
+  const size_t outer_copies = cfg->no_average ? static_cast<size_t>(m) : 1;
+  CREATE_HIP(hipMemsetAsync(ctx->x0, 0, arena * outer_copies, stream), "clearing x0");
+  CREATE_HIP(hipMemsetAsync(ctx->u, 0, arena * outer_copies, stream), "clearing u");
   CREATE_HIP(hipMemsetAsync(ctx->h, 0, arena * m, stream), "clearing h");
   if (ctx->v) CREATE_HIP(hipMemsetAsync(ctx->v, 0, arena * m, stream), "clearing v");
   // common starting point x_{0,0}: worker 0's replica
   for (int32_t j = 0; j < n_tensors; ++j) {
     const size_t bytes = static_cast<size_t>(numel[j]) * sizeof(float);
     if (!bytes) continue;
-    CREATE_HIP(hipMemcpyAsync(ctx->x0 + L.arena_off[j], params[j], bytes, hipMemcpyDeviceToDevice,
-                              stream),
-               "copy of x_{0,0} into x0");
+    for (size_t w = 0; w < outer_copies; ++w) {
+      CREATE_HIP(hipMemcpyAsync(ctx->x0 + w * L.d_pad + L.arena_off[j], params[j], bytes,
+                                hipMemcpyDeviceToDevice, stream),
+                 "copy of x_{0,0} into x0");
+    }
     for (int32_t w = 1; w < m; ++w) {
       CREATE_HIP(hipMemcpyAsync(params[static_cast<size_t>(w) * n_tensors + j], params[j], bytes,
                                 hipMemcpyDeviceToDevice, stream),
@@ -455,6 +462,26 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (ctx->k != ctx->cfg.tau)
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
   const slowmo_config &c = ctx->cfg;
+  if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
+    OuterNoAvgArgs na{};
+    na.tiles = ctx->d_ltiles;
+    na.slots = ctx->d_slots;
+    na.ntiles = ctx->n_ltiles;
+    na.x0 = ctx->x0;
+    na.u = ctx->u;
+    na.lr = lr;
+    na.alpha_lr = c.alpha * lr;
+    na.beta = c.beta;
+    hipError_t e = launch_outer_noavg_step(na, ctx->tune, static_cast<hipStream_t>(stream_));
+    if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
+    ctx->k = 0;
+    ctx->t += 1;
+    if (c.policy == SLOWMO_BUF_RESET) {
+      ctx->buffers_zero = true;
+      ctx->l = 0;
+    }
+    return SLOWMO_OK;
+  }
   OuterArgs a{};
   a.tiles = ctx->d_otiles;
   a.tensors = ctx->d_tensors;
@@ -496,8 +523,16 @@ slowmo_status slowmo_get_buffer(slowmo_ctx *ctx, int32_t which, int32_t worker, 
   if (tensor < 0 || tensor >= ctx->n_tensors) return fail(ctx, SLOWMO_ERR_ARG, "tensor index out of range");
   const int64_t off = ctx->layout.arena_off[tensor];
   switch (which) {
-    case SLOWMO_BUF_X0: *device_ptr = ctx->x0 + off; return SLOWMO_OK;
-    case SLOWMO_BUF_U: *device_ptr = ctx->u + off; return SLOWMO_OK;
+    case SLOWMO_BUF_X0:
+    case SLOWMO_BUF_U: {
+      int64_t woff = 0;
+      if (ctx->cfg.no_average) {
+        if (worker < 0 || worker >= ctx->cfg.m) return fail(ctx, SLOWMO_ERR_ARG, "worker index out of range");
+        woff = static_cast<int64_t>(worker) * ctx->layout.d_pad;
+      }
+      *device_ptr = (which == SLOWMO_BUF_X0 ? ctx->x0 : ctx->u) + woff + off;
+      return SLOWMO_OK;
+    }
     case SLOWMO_BUF_H:
     case SLOWMO_BUF_V: {
       if (worker < 0 || worker >= ctx->cfg.m) return fail(ctx, SLOWMO_ERR_ARG, "worker index out of range");

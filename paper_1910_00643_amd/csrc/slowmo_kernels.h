@@ -42,6 +42,17 @@ struct OuterArgs {
   int64_t d_pad;               // worker stride of the arenas, elements
 };
 
+// Outer step without the exact average: lines 7-8 per (worker, element) with
+// per-worker x0 and u arenas (m * d_pad each), over the local-step tiles.
+struct OuterNoAvgArgs {
+  const TileRef *tiles;        // device (owner = slot)
+  const SlotInfo *slots;       // device
+  int32_t ntiles;
+  float *x0;                   // device: m * d_pad
+  float *u;                    // device: m * d_pad
+  float lr, alpha_lr, beta;
+};
+
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
@@ -55,5 +66,7 @@ struct LaunchTuning {
 hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
+                                   hipStream_t stream);
 
 }  // namespace slowmo

@@ -316,6 +316,50 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
   if constexpr (AVG >= 2) average_arena<NTL, NTS>(vbase + ti.fo + eo, d_pad, m, p.m_f, e0, n);
 }
 
+// ---- outer step without the exact average (Section 6) ---------------------------
+// Same tiling as the local step: one workgroup = 256 elements of one (worker,
+// tensor); 3 streams read, 3 written.  "xbar" is the worker's own replica
+// (a one-term sum divided by 1, which is exact).
+template <bool NT>
+__global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
+    const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
+    float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap,
+    OuterP p) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const SlotInfo s = slots[t.owner];
+  const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;
+  float *x = s.x + go;
+  float *x0 = x0base + s.so + go;
+  float *u = ubase + s.so + go;
+  const int64_t left = s.numel - go;
+  const int n = left < kLocalTile ? static_cast<int>(left) : kLocalTile;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && e0 + 4 <= n) {
+    V4 xv = ld4<NT>(x + e0), x0v = ld4<NT>(x0 + e0), uv = ld4<NT>(u + e0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xv[c] = outer_elem(xv[c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<NT>(u + e0, uv);
+    st4<NT>(x0 + e0, xv);
+    st4<NT>(x + e0, xv);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      float ue = ld1(u + j);
+      float xn = outer_elem(ld1(x + j), ld1(x0 + j), ue, p);
+      st1(u + j, ue);
+      st1(x0 + j, xn);
+      st1(x + j, xn);
+    }
+  }
+}
+
 struct Grid {
   int chunk;
   unsigned blocks;
@@ -387,6 +431,20 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   }
   return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
                   : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
+}
+
+hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const OuterP p{a.lr, a.alpha_lr, a.beta, 1.0f};
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_outer_noavg<true>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles,
+                       a.slots, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, p);
+  } else {
+    hipLaunchKernelGGL((k_outer_noavg<false>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles,
+                       a.slots, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, p);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace slowmo

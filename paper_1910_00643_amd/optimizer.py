@@ -21,13 +21,13 @@ _TORCH_GRAD = {"f32": torch.float32, "bf16": torch.bfloat16}
 def make_config(m: int, tau: int, alpha: float, beta: float, base: str = "sgd_nesterov",
                 policy: Optional[str] = None, grad_dtype: str = "f32", momentum: float = 0.0,
                 weight_decay: float = 0.0, beta1: float = 0.9, beta2: float = 0.999,
-                eps: float = 1e-8) -> B.slowmo_config:
+                eps: float = 1e-8, no_average: bool = False) -> B.slowmo_config:
     if policy is None:
         policy = "reset" if base == "sgd_nesterov" else "maintain"
     return B.slowmo_config(m=m, tau=tau, alpha=alpha, beta=beta, base=_BASE[base],
                            policy=_POLICY[policy], grad_dtype=_DTYPE[grad_dtype],
                            momentum=momentum, weight_decay=weight_decay,
-                           beta1=beta1, beta2=beta2, eps=eps)
+                           beta1=beta1, beta2=beta2, eps=eps, no_average=int(no_average))
 
 
 class SlowMo:

@@ -38,6 +38,7 @@ class Workload:
     grad_dtype: str = "f32"        # "f32" | "bf16"
     sigma: float = 1.0             # gradient standard deviation
     rounds: int = 3
+    exact_average: bool = True     # False: the variant without line 6 of Algorithm 1 (Section 6)
 
     @property
     def seed(self) -> int:

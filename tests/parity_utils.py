@@ -51,7 +51,8 @@ def make_oracle(w, index, prec="f64"):
                           alpha=w.f32("alpha"), beta=w.f32("beta"), base=w.base,
                           policy=w.policy, momentum=w.f32("momentum"),
                           weight_decay=w.f32("weight_decay"), beta1=w.f32("beta1"),
-                          beta2=w.f32("beta2"), eps=w.f32("eps"), prec=prec)
+                          beta2=w.f32("beta2"), eps=w.f32("eps"), prec=prec,
+                          exact_average=w.exact_average)
 
 
 def oracle_grads(w, index, step):
@@ -90,7 +91,8 @@ def make_gpu(w, prob):
     from paper_1910_00643_amd.optimizer import SlowMo, make_config
     cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
                       policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
-                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps)
+                      weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                      no_average=not w.exact_average)
     return SlowMo(prob.params, cfg)
 
 
@@ -128,9 +130,13 @@ def gpu_state(w, prob, opt, index, with_outer=True):
     if w.base == "adam":
         out["v"] = np.stack([prob.gather([opt.buffer("v", j, i) for j in range(nt)], index)
                              for i in range(w.m)])
-    if with_outer:
+    if with_outer and w.exact_average:
         out["x0"] = prob.gather([opt.buffer("x0", j) for j in range(nt)], index)
         out["u"] = prob.gather([opt.buffer("u", j) for j in range(nt)], index)
+    elif with_outer:            # every worker has its own x0 and u
+        for key in ("x0", "u"):
+            out[key] = np.stack([prob.gather([opt.buffer(key, j, i) for j in range(nt)], index)
+                                 for i in range(w.m)])
     return out
 
 
@@ -150,7 +156,8 @@ def compare_run(w, prob, opt, index, rounds, bitwise_f32=False):
     worst["x0"] = assert_params_close(final["x0"], o64.x0, "x0 after the run")
     worst["u"] = assert_u_close(final["u"], o64.u, lr, "u after the run")
     for i in range(w.m):                 # Section 2: identical on all workers
-        assert np.array_equal(final["x"][i], final["x0"]), f"replica {i} differs from x0"
+        own = final["x0"] if w.exact_average else final["x0"][i]
+        assert np.array_equal(final["x"][i], own), f"replica {i} differs from x0"
     if bitwise_f32:
         # The SGD and outer kernels round every product and sum separately in
         # the order of the formulas, as the fp32 build of the oracle does.

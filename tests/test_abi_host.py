@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_config_struct_matches_header_layout():
-    assert C.sizeof(B.slowmo_config) == 48
+    assert C.sizeof(B.slowmo_config) == 52
     assert C.sizeof(B.slowmo_plan_run) == 24
 
 
@@ -40,7 +40,7 @@ def _cfg(**kw):
                                 dict(alpha=0.0), dict(alpha=float("inf")), dict(beta=1.0),
                                 dict(beta=-0.1), dict(momentum=1.0), dict(weight_decay=-1.0),
                                 dict(base="adam", beta1=1.0), dict(base="adam", eps=-1.0),
-                                dict(beta=float("nan"))])
+                                dict(beta=float("nan")), dict(no_average=True, policy="average")])
 def test_bad_hyperparameters_are_rejected(kw):
     cfg = _cfg(**kw)
     assert P.slowmo_state_bytes(cfg, [16]) == 0

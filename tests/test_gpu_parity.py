@@ -104,6 +104,22 @@ def test_ragged_tensor_list_every_element(base, grad_dtype, policy, param_layout
     opt.close()
 
 
+@pytest.mark.parametrize("base,grad_dtype,policy,param_layout", [
+    ("sgd_nesterov", "f32", "reset", "separate"),
+    ("sgd_nesterov", "bf16", "maintain", "flat"),
+    ("adam", "bf16", "maintain", "separate"),
+])
+def test_noaverage_variant_every_element(base, grad_dtype, policy, param_layout):
+    """Section 6: no exact average; per-worker x0 and u."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy=policy),
+                            exact_average=False)
+    prob = _problem(w, ring=2, param_layout=param_layout, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"))
+    opt.close()
+
+
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
@@ -205,6 +221,11 @@ def test_resnet50_shaped_sampled():
 def test_transformer_big_shaped_sampled():
     w = W.transformer_big()
     _sampled(w, w.rounds, 3000)
+
+
+def test_resnet50_shaped_noaverage_sampled():
+    w = dataclasses.replace(W.resnet50(), exact_average=False, rounds=4)
+    _sampled(w, w.rounds, 1500)
 
 
 def test_resnet50_shaped_average_policy_sampled():
