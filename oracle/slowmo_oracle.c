@@ -157,3 +157,43 @@ void oracle_average_buffers(REAL *bw, int m, int64_t d)
             bw[(int64_t)i * d + j] = mean;
     }
 }
+
+/*
+ * One mixing step of stochastic gradient push among the m workers
+ * (Algorithm C.1: send / receive / "update model parameters" / "update
+ * de-biased factors"; matrix form X_{k+1} = X_{k+1/2} P^T of Appendix C.1).
+ * Every worker i has at most one in-neighbour in_peer[i] besides itself
+ * (in_peer[i] == i: none), and a sender splits its mass uniformly over itself
+ * and its receivers, which makes P column-stochastic:
+ *     p(i,j) = 1 / (1 + outdeg(j))  for j == i or j == in_peer[i],  else 0.
+ *   xw : m replicas (worker-major), mixed in place
+ *   w  : the m push-sum weights, mixed with the same P
+ */
+void oracle_mix_step(REAL *xw, REAL *w, int m, int64_t d, const int32_t *in_peer)
+{
+    REAL share[m];                      /* 1 / (1 + outdeg(j)) */
+    for (int j = 0; j < m; ++j) {
+        int outdeg = 0;
+        for (int i = 0; i < m; ++i)
+            if (i != j && in_peer[i] == j) ++outdeg;
+        share[j] = (REAL)1 / (REAL)(1 + outdeg);
+    }
+    REAL wold[m];
+    for (int i = 0; i < m; ++i) wold[i] = w[i];
+    for (int i = 0; i < m; ++i) {
+        int j = in_peer[i];
+        w[i] = share[i] * wold[i];
+        if (j != i) w[i] = w[i] + share[j] * wold[j];
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < d; ++e) {
+        REAL old[m];
+        for (int i = 0; i < m; ++i) old[i] = xw[(int64_t)i * d + e];
+        for (int i = 0; i < m; ++i) {
+            int j = in_peer[i];
+            REAL v = share[i] * old[i];
+            if (j != i) v = v + share[j] * old[j];
+            xw[(int64_t)i * d + e] = v;
+        }
+    }
+}

@@ -76,8 +76,21 @@ def load(prec: str = "f64", path: Optional[str] = None) -> C.CDLL:
     lib.oracle_outer_step.restype = None
     lib.oracle_average_buffers.argtypes = [p, C.c_int, i64]
     lib.oracle_average_buffers.restype = None
+    lib.oracle_mix_step.argtypes = [p, p, C.c_int, i64, p]
+    lib.oracle_mix_step.restype = None
     _loaded[key] = lib
     return lib
+
+
+def exponential_graph_in_peers(m: int, step: int) -> np.ndarray:
+    """Appendix C.1: with the workers ordered by rank, each one communicates in
+    turn with the peer 2^0, 2^1, ..., 2^floor(log2(m-1)) hops away, one peer
+    per iteration.  Worker i receives from worker (i - hop) mod m."""
+    if m < 2:
+        return np.zeros(max(m, 1), dtype=np.int32)
+    n_hops = int(np.floor(np.log2(m - 1))) + 1 if m > 2 else 1
+    hop = 1 << (step % n_hops)
+    return ((np.arange(m) - hop) % m).astype(np.int32)
 
 
 def _ptr(a: np.ndarray) -> C.c_void_p:
@@ -124,6 +137,7 @@ class SlowMoOracle:
             self.u = np.zeros((self.m, self.d), self.dtype)
         self.h = np.zeros((self.m, self.d), self.dtype)
         self.v = np.zeros((self.m, self.d), self.dtype) if base == "adam" else None
+        self.w = np.ones(self.m, self.dtype)    # push-sum weights (Algorithm C.1), 1 unless mixing
         self.t = 0      # outer iteration
         self.k = 0      # inner step within the outer iteration
         self.l = 0      # Adam moment updates applied so far (bias-correction exponent)
@@ -162,6 +176,19 @@ class SlowMoOracle:
                     self.weight_decay, self.l)
         self.k += 1
 
+    # Algorithm C.1, communication half of a stochastic-gradient-push step
+    def mix_step(self, in_peer) -> None:
+        """x^{(i)} <- sum_j p(i,j) x^{(j)} and the same for the push-sum
+        weights, with the column-stochastic P described by in_peer (worker i
+        receives from in_peer[i]; in_peer[i] == i: from nobody)."""
+        peers = np.ascontiguousarray(in_peer, dtype=np.int32)
+        assert peers.shape == (self.m,) and peers.min() >= 0 and peers.max() < self.m
+        self.lib.oracle_mix_step(_ptr(self.x), _ptr(self.w), self.m, self.d, _ptr(peers))
+
+    def debiased(self) -> np.ndarray:
+        """z^{(i)} = x^{(i)} / w_i (Algorithm C.1, last line)."""
+        return self.x / self.w[:, None]
+
     # Algorithm 1 lines 6-8 (+ copy of x_{t+1,0} into every replica)
     def outer_step(self, lr: float) -> None:
         assert self.k == self.tau, "outer step needs exactly tau local steps"
@@ -174,6 +201,8 @@ class SlowMoOracle:
             for i in range(self.m):
                 self.lib.oracle_outer_step(_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),
                                            _ptr(self.u[i]), lr, self.alpha, self.beta)
+        if self.exact_average:
+            self.w[...] = 1     # all mass is shared equally again after the exact average
         self.k = 0
         self.t += 1
 

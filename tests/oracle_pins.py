@@ -541,4 +541,82 @@ def pin_noaverage_with_common_gradients_equals_slowmo(make):
         _close(b.u[i], a.u, rtol=1e-13, what="u")
 
 
+# ------------------------------ Appendix C.1: the mixing step of gradient push
+
+def _mixing_matrix(in_peer):
+    m = len(in_peer)
+    P = np.zeros((m, m))
+    for j in range(m):
+        receivers = [i for i in range(m) if i != j and in_peer[i] == j]
+        for i in [j] + receivers:
+            P[i, j] = 1.0 / (1 + len(receivers))
+    return P
+
+
+def pin_mixing_is_the_matrix_product(make):
+    """Appendix C.1, matrix form: X_{k+1} = X P^T with a column-stochastic P;
+    checked against a library matrix product for a permutation (every node
+    one sender, one receiver), a star-like map and a map with idle nodes."""
+    rng = _rng(40)
+    m, d = 6, 11
+    for in_peer in ([5, 0, 1, 2, 3, 4], [2, 0, 3, 1, 5, 4], [0, 0, 0, 1, 1, 5], [0, 1, 2, 3, 4, 5]):
+        o = make(rng.standard_normal(d), m=m, tau=3, alpha=1.0, beta=0.5)
+        o.x[...] = rng.standard_normal((m, d))
+        o.w[...] = rng.uniform(0.5, 1.5, m)
+        X, w = o.x.copy(), o.w.copy()
+        P = _mixing_matrix(in_peer)
+        _close(P.sum(axis=0), np.ones(m), what="P is column-stochastic")
+        o.mix_step(in_peer)
+        _close(o.x, P @ X, rtol=1e-13, what=f"mixing {in_peer}")
+        _close(o.w, P @ w, rtol=1e-13, what="push-sum weights")
+        _close(o.x.sum(axis=0), X.sum(axis=0), rtol=1e-12, atol=1e-13, what="mass is conserved")
+
+
+def pin_exponential_graph_averages_exactly_in_log2_m_steps(make):
+    """On m = 2^p nodes the one-peer exponential graph (hops 1, 2, ..., 2^(p-1))
+    is a butterfly: after p mixing steps every node holds the exact average,
+    the push-sum weights stay 1 and z = x."""
+    import oracle.slowmo_oracle as O
+    rng = _rng(41)
+    for m in (2, 4, 8, 16):
+        d = 7
+        o = make(rng.standard_normal(d), m=m, tau=3, alpha=1.0, beta=0.5)
+        o.x[...] = rng.standard_normal((m, d))
+        mean = o.x.mean(axis=0)
+        p = int(np.log2(m))
+        seen = set()
+        for step in range(p):
+            peers = O.exponential_graph_in_peers(m, step)
+            assert sorted(peers.tolist()) == list(range(m))      # a permutation
+            seen.add(int((0 - peers[0]) % m))
+            o.mix_step(peers)
+        assert seen == {1 << k for k in range(p)}
+        for i in range(m):
+            _close(o.x[i], mean, rtol=1e-13, atol=1e-14, what=f"consensus on {m} nodes")
+        _close(o.w, np.ones(m), what="weights")
+        _close(o.debiased(), o.x, what="z = x")
+    peers = O.exponential_graph_in_peers(6, 2)          # m = 6: hops 1, 2, 4
+    assert peers.tolist() == [(i - 4) % 6 for i in range(6)]
+    assert O.exponential_graph_in_peers(6, 3).tolist() == [(i - 1) % 6 for i in range(6)]
+
+
+def pin_mixing_debiased_iterates_reach_consensus(make):
+    """Push-sum: with column- but not row-stochastic mixing matrices whose
+    union over time is strongly connected, x_i / w_i converges to the average
+    of the initial values although x_i itself does not (the reason the
+    algorithm keeps w)."""
+    rng = _rng(42)
+    m, d = 5, 4
+    o = make(rng.standard_normal(d), m=m, tau=3, alpha=1.0, beta=0.5)
+    o.x[...] = rng.standard_normal((m, d))
+    mean = o.x.mean(axis=0)
+    for _ in range(300):
+        o.mix_step([4, 0, 0, 2, 3])      # node 0 has two receivers, node 1 none
+        o.mix_step([1, 2, 3, 4, 0])      # a ring in the other direction
+    assert abs(o.w.sum() - m) < 1e-12 and np.abs(o.w - 1).max() > 1e-2
+    assert np.abs(o.x - mean).max() > 1e-2
+    for i in range(m):
+        _close(o.debiased()[i], mean, rtol=1e-9, atol=1e-10, what="push-sum consensus")
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

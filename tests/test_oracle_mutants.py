@@ -51,6 +51,11 @@ C_MUTANTS = [
     ("average_drops_last_worker", "for (int i = 1; i < m; ++i)", "for (int i = 1; i < m - 1; ++i)", 1),
     ("average_not_written_back", "bw[(int64_t)i * d + j] = mean;", ";", 0),
     ("average_writes_sum", "bw[(int64_t)i * d + j] = mean;", "bw[(int64_t)i * d + j] = s;", 0),
+    ("mix_uses_receiver_share", "if (j != i) v = v + share[j] * old[j];", "if (j != i) v = v + share[i] * old[j];", 0),
+    ("mix_in_place_hazard", "if (j != i) v = v + share[j] * old[j];", "if (j != i) v = v + share[j] * xw[(int64_t)j * d + e];", 0),
+    ("mix_weights_not_mixed", "if (j != i) w[i] = w[i] + share[j] * wold[j];", ";", 0),
+    ("mix_counts_self_loops", "if (i != j && in_peer[i] == j) ++outdeg;", "if (in_peer[i] == j) ++outdeg;", 0),
+    ("mix_drops_own_share", "REAL v = share[i] * old[i];", "REAL v = old[i];", 0),
     ("outer_transposed_replicas", "s = s + xw[(int64_t)i * d + j];", "s = s + xw[(int64_t)j * m + i];", 0),
 ]
 
@@ -74,6 +79,8 @@ PY_MUTANTS = [
     ("noaverage_shares_x0", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[0]),", 0),
     ("noaverage_shares_u", "_ptr(self.u[i]), lr, self.alpha, self.beta)", "_ptr(self.u[0]), lr, self.alpha, self.beta)", 0),
     ("noaverage_only_worker0", "            for i in range(self.m):\n                self.lib.oracle_outer_step(", "            for i in range(1):\n                self.lib.oracle_outer_step(", 0),
+    ("expgraph_sends_forward", "return ((np.arange(m) - hop) % m)", "return ((np.arange(m) + hop) % m)", 0),
+    ("expgraph_hop_linear", "hop = 1 << (step % n_hops)", "hop = 1 + (step % n_hops)", 0),
     ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
      'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
 ]
