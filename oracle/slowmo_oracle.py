@@ -176,6 +176,8 @@ class SlowMoOracle:
                     self.weight_decay, self.l)
         self.k += 1
 
+    exponential_graph_in_peers = staticmethod(exponential_graph_in_peers)
+
     # Algorithm C.1, communication half of a stochastic-gradient-push step
     def mix_step(self, in_peer) -> None:
         """x^{(i)} <- sum_j p(i,j) x^{(j)} and the same for the push-sum

@@ -576,11 +576,11 @@ def pin_exponential_graph_averages_exactly_in_log2_m_steps(make):
     """On m = 2^p nodes the one-peer exponential graph (hops 1, 2, ..., 2^(p-1))
     is a butterfly: after p mixing steps every node holds the exact average,
     the push-sum weights stay 1 and z = x."""
-    import oracle.slowmo_oracle as O
     rng = _rng(41)
     for m in (2, 4, 8, 16):
         d = 7
         o = make(rng.standard_normal(d), m=m, tau=3, alpha=1.0, beta=0.5)
+        O = type(o)
         o.x[...] = rng.standard_normal((m, d))
         mean = o.x.mean(axis=0)
         p = int(np.log2(m))
