@@ -57,6 +57,8 @@ def round_bytes(w) -> int:
     reset = w.policy == "reset"
     per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0, reset and k == w.tau - 1)
                           for k in range(w.tau))
+    if w.mix == "expgraph":     # every replica read and written once per gossip step
+        per_worker_elem += 8 * w.tau
     return w.d * (w.m * per_worker_elem + outer_bytes_per_element(w))
 
 
@@ -83,7 +85,9 @@ def run_rounds(w, opt, arrays, rounds, events=None):
     """`rounds` outer iterations.  With `events`, brackets every call with HIP
     events on the stream the kernels are launched on (torch's current one)."""
     import torch
+    import paper_1910_00643_amd as P
     ring = len(arrays)
+    peers = [P.slowmo_expgraph_in_peers(w.m, s) for s in range(16)] if w.mix == "expgraph" else None
     for _ in range(rounds):
         for k in range(w.tau):
             if events is not None:
@@ -96,6 +100,14 @@ def run_rounds(w, opt, arrays, rounds, events=None):
                 kind = ("local_first" if (reset and k == 0) else
                         "local_last" if (reset and k == w.tau - 1) else "local")
                 events[kind].append((a, b))
+            if peers is not None:           # SGP as base optimizer: gossip after every step
+                if events is not None:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                opt.mix_step(peers[k % len(peers)])
+                if events is not None:
+                    b.record()
+                    events["mix"].append((a, b))
         if events is not None:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
@@ -117,7 +129,7 @@ def time_workload(w, steps, warmup, ring=None):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     # second pass: per-kernel durations from HIP events around every launch
-    events = {"local": [], "local_first": [], "local_last": [], "outer": []}
+    events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": []}
     run_rounds(w, opt, arrays, steps, events)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
@@ -155,6 +167,8 @@ def cpu_baseline(w, budget_s=12.0):
             g = g_dev.to(torch.float32).cpu().numpy()
             t0 = time.perf_counter()
             o.local_step(g, w.f32("lr"))
+            if w.mix == "expgraph":
+                o.mix_step(O.exponential_graph_in_peers(w.m, step))
             spent += time.perf_counter() - t0
             step += 1
         t0 = time.perf_counter()
@@ -179,6 +193,9 @@ def main():
     ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
     ap.add_argument("--policy", default=None, choices=["reset", "maintain", "average"],
                     help="override the workload's buffer strategy")
+    ap.add_argument("--mix", default=None, choices=["expgraph"],
+                    help="stochastic gradient push as base: a gossip step on the one-peer "
+                         "exponential graph after every local step")
     ap.add_argument("--no-average", action="store_true",
                     help="the variant without the exact average (Section 6 of the paper)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -199,6 +216,8 @@ def main():
         w = dataclasses.replace(w, policy=args.policy)
     if args.no_average:
         w = dataclasses.replace(w, exact_average=False)
+    if args.mix:
+        w = dataclasses.replace(w, mix=args.mix)
     ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
                             2 if w.name == "stress" else w.tau)
     if args.calibrate_copy:
@@ -223,7 +242,8 @@ def main():
         "config": {"workload": f"{w.name}-shaped tensor list ({len(w.numel)} tensors, d={w.d}), "
                                f"m={w.m}, tau={w.tau}, base={w.base}, grads={w.grad_dtype}, "
                                f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}"
-                               + ("" if w.exact_average else ", no exact average"),
+                               + ("" if w.exact_average else ", no exact average")
+                               + ("" if w.mix == "none" else f", gossip={w.mix}"),
                    "step": "one outer iteration: tau local steps on all m workers + outer step",
                    "gradient_sets_resident": ring},
         "hbm_gbps_whole_round": round_bytes(w) / wall * args.steps / 1e9,
@@ -240,6 +260,11 @@ def main():
         out["outer_kernel"] = {"achieved": ob / (kern_ms["outer"] * 1e-3) / 1e9, "unit": "GB/s",
                                "frac": ob / (kern_ms["outer"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                "algorithmic_bytes_per_launch": ob}
+    if kern_ms.get("mix"):
+        mb = 8 * w.m * w.d
+        out["mix_kernel"] = {"achieved": mb / (kern_ms["mix"] * 1e-3) / 1e9, "unit": "GB/s",
+                             "frac": mb / (kern_ms["mix"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                             "algorithmic_bytes_per_launch": mb}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

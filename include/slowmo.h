@@ -145,6 +145,32 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
  */
 slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream);
 
+/*
+ * One mixing (gossip) step of stochastic gradient push among the m logical
+ * workers: Algorithm C.1, "send / receive / update model parameters", i.e.
+ * X <- X P^T of Appendix C.1, for the case the paper runs: every worker sends
+ * one message and receives one per iteration.
+ *   in_peer : host array of m worker indices, a permutation of 0..m-1; worker
+ *             i receives from worker in_peer[i] (in_peer[i] == i: worker i
+ *             neither sends nor receives in this step).
+ * Every sender splits its mass evenly between itself and its receiver, so
+ *   x^{(i)} <- x^{(i)} / 2 + x^{(in_peer[i])} / 2      (old values on the right)
+ * for all i at once, in place.  This P is doubly stochastic: the push-sum
+ * weights w_i of Algorithm C.1 stay 1 and the de-biased iterates z^{(i)} equal
+ * x^{(i)}, so neither is stored.  May be called any number of times between
+ * local steps; it changes the replicas only.
+ * Errors: ARG (NULL, or in_peer is not a permutation), HIP.
+ */
+slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream);
+
+/*
+ * The communication pattern of Appendix C.1 (one-peer, time-varying directed
+ * exponential graph): at iteration `step` every worker receives from the
+ * worker 2^(step mod L) ranks below it (mod m), L = floor(log2(m-1)) + 1.
+ * Writes the m entries of in_peer (host).  Host-only.  Errors: ARG.
+ */
+slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer);
+
 /* Frees the context's host memory and its small device-side bookkeeping.
  * Never touches parameters, gradients or the workspace.  NULL is accepted. */
 slowmo_status slowmo_destroy(slowmo_ctx *ctx);

@@ -29,7 +29,8 @@ STATUS_NAMES = {0: "SLOWMO_OK", -1: "SLOWMO_ERR_ARG", -2: "SLOWMO_ERR_STATE",
 # every symbol include/slowmo.h declares
 EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_outer_step",
            "slowmo_destroy", "slowmo_last_error", "slowmo_get_buffer", "slowmo_get_counters",
-           "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version"]
+           "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version", "slowmo_mix_step",
+           "slowmo_expgraph_in_peers"]
 
 
 class slowmo_config(C.Structure):
@@ -87,6 +88,10 @@ def lib() -> C.CDLL:
     L.slowmo_plan_local.restype = i64
     L.slowmo_plan_outer.argtypes = [i32, i32, C.POINTER(i64), C.POINTER(slowmo_plan_run), i64]
     L.slowmo_plan_outer.restype = i64
+    L.slowmo_mix_step.argtypes = [vp, C.POINTER(i32), vp]
+    L.slowmo_mix_step.restype = C.c_int
+    L.slowmo_expgraph_in_peers.argtypes = [i32, i64, C.POINTER(i32)]
+    L.slowmo_expgraph_in_peers.restype = C.c_int
     L.slowmo_version.argtypes = []
     L.slowmo_version.restype = C.c_char_p
     _lib = L
@@ -145,6 +150,19 @@ def slowmo_local_step(ctx, grads, lr: float, stream: int = 0) -> None:
 
 def slowmo_outer_step(ctx, lr: float, stream: int = 0) -> None:
     _check(lib().slowmo_outer_step(ctx, lr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_mix_step(ctx, in_peer: Sequence[int], stream: int = 0) -> None:
+    """in_peer: m worker indices (a permutation); worker i receives from in_peer[i]."""
+    arr = (C.c_int32 * len(in_peer))(*[int(v) for v in in_peer]) if in_peer is not None else None
+    _check(lib().slowmo_mix_step(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_expgraph_in_peers(m: int, step: int):
+    """The one-peer exponential graph's in-neighbours at iteration `step`."""
+    arr = (C.c_int32 * max(m, 1))()
+    _check(lib().slowmo_expgraph_in_peers(m, step, arr), None)
+    return list(arr[:m])
 
 
 def slowmo_destroy(ctx) -> None:

@@ -29,7 +29,7 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kSlots], slots, tensors, ltiles, otiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kSlots], mixtab[kSlots], slots, tensors, ltiles, otiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
@@ -50,6 +50,7 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
   s.xtab_t = take(n_ptr * sizeof(void *));
   for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
+  for (int i = 0; i < kSlots; ++i) s.mixtab[i] = take(static_cast<size_t>(c.m) * sizeof(int32_t));
   s.slots = take(n_ptr * sizeof(SlotInfo));
   s.tensors = take(static_cast<size_t>(n_tensors) * sizeof(TensorInfo));
   s.ltiles = take(n_ltiles * sizeof(TileRef));
@@ -107,6 +108,51 @@ int32_t env_flag(const char *name, int32_t dflt) {
   return static_cast<int32_t>(std::strtol(s, nullptr, 10));
 }
 
+// A small host->device table that may change from call to call: a ring of
+// device slots (inside the caller's workspace) with pinned staging copies,
+// and one event per slot recorded after its upload, so that a staging copy is
+// not rewritten while an earlier upload may still be reading it.
+struct TableRing {
+  void *d[kSlots] = {};
+  void *h[kSlots] = {};
+  hipEvent_t ev[kSlots] = {};
+  bool used[kSlots] = {};
+  int cur = -1;  // slot of the most recent upload, -1 = none
+
+  hipError_t init(char *device_base, const size_t *offsets, size_t bytes) {
+    for (int i = 0; i < kSlots; ++i) {
+      d[i] = device_base + offsets[i];
+      hipError_t e = hipHostMalloc(&h[i], std::max<size_t>(bytes, 8), hipHostMallocDefault);
+      if (e != hipSuccess) return e;
+      e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  // Uploads `bytes` from src into the next slot; returns the slot or -1.
+  int upload(const void *src, size_t bytes, hipStream_t stream, hipError_t *err) {
+    const int slot = (cur + 1) % kSlots;
+    if (used[slot]) {
+      *err = hipEventSynchronize(ev[slot]);
+      if (*err != hipSuccess) return -1;
+    }
+    std::memcpy(h[slot], src, bytes);
+    *err = hipMemcpyAsync(d[slot], h[slot], bytes, hipMemcpyHostToDevice, stream);
+    if (*err != hipSuccess) return -1;
+    *err = hipEventRecord(ev[slot], stream);
+    if (*err != hipSuccess) return -1;
+    used[slot] = true;
+    cur = slot;
+    return slot;
+  }
+  void destroy() {
+    for (int i = 0; i < kSlots; ++i) {
+      if (ev[i]) (void)hipEventDestroy(ev[i]);
+      if (h[i]) (void)hipHostFree(h[i]);
+    }
+  }
+};
+
 }  // namespace
 
 struct slowmo_ctx {
@@ -119,20 +165,15 @@ struct slowmo_ctx {
   // sections of the caller's workspace (device pointers)
   float *x0 = nullptr, *u = nullptr, *h = nullptr, *v = nullptr;
   float **d_xtab_t = nullptr;  // replica pointers, tensor-major
-  const void **d_gtab[kSlots] = {};
   SlotInfo *d_slots = nullptr;
   TensorInfo *d_tensors = nullptr;
   TileRef *d_ltiles = nullptr;
   TileRef *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
 
-  // gradient-pointer table: pinned staging ring, one event per slot recorded
-  // after the slot's upload so that the host copy is not rewritten too early
-  const void **h_gtab[kSlots] = {};
-  hipEvent_t ev[kSlots] = {};
-  bool ev_used[kSlots] = {};
-  int cur_slot = -1;  // slot holding `last_grads`, -1 = none uploaded yet
-  std::vector<const void *> last_grads;
+  TableRing gtab;    // gradient pointers of the current call (m * n_tensors)
+  std::vector<const void *> last_grads;  // contents of gtab's current slot
+  TableRing mixtab;  // worker sequence of the current mixing step (m entries)
 
   int64_t t = 0;  // outer iterations done
   int32_t k = 0;  // local steps in the current outer iteration
@@ -160,10 +201,8 @@ slowmo_status fail_hip(slowmo_ctx *ctx, hipError_t e, const char *what) {
 }
 
 void release(slowmo_ctx *ctx) {
-  for (int i = 0; i < kSlots; ++i) {
-    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
-    if (ctx->h_gtab[i]) (void)hipHostFree(ctx->h_gtab[i]);
-  }
+  ctx->gtab.destroy();
+  ctx->mixtab.destroy();
   delete ctx;
 }
 
@@ -288,7 +327,6 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->h = reinterpret_cast<float *>(base + sec.h);
   ctx->v = cfg->base == SLOWMO_ADAM ? reinterpret_cast<float *>(base + sec.v) : nullptr;
   ctx->d_xtab_t = reinterpret_cast<float **>(base + sec.xtab_t);
-  for (int i = 0; i < kSlots; ++i) ctx->d_gtab[i] = reinterpret_cast<const void **>(base + sec.gtab[i]);
   ctx->d_slots = reinterpret_cast<SlotInfo *>(base + sec.slots);
   ctx->d_tensors = reinterpret_cast<TensorInfo *>(base + sec.tensors);
   ctx->d_ltiles = reinterpret_cast<TileRef *>(base + sec.ltiles);
@@ -305,12 +343,9 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
     }                                       \
   } while (0)
 
-  for (int i = 0; i < kSlots; ++i) {
-    CREATE_HIP(hipHostMalloc(reinterpret_cast<void **>(&ctx->h_gtab[i]), n_ptr * sizeof(void *),
-                             hipHostMallocDefault),
-               "hipHostMalloc");
-    CREATE_HIP(hipEventCreateWithFlags(&ctx->ev[i], hipEventDisableTiming), "hipEventCreate");
-  }
+  CREATE_HIP(ctx->gtab.init(base, sec.gtab, n_ptr * sizeof(void *)), "gradient-pointer ring");
+  CREATE_HIP(ctx->mixtab.init(base, sec.mixtab, static_cast<size_t>(m) * sizeof(int32_t)),
+             "mixing-table ring");
 
   // device tables
   const Layout &L = ctx->layout;
@@ -403,31 +438,21 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
   // gradient-pointer table: reuse the uploaded one if the pointers did not change
-  int slot = ctx->cur_slot;
+  int slot = ctx->gtab.cur;
   const bool same = slot >= 0 && ctx->last_grads.size() == n_ptr &&
                     std::memcmp(ctx->last_grads.data(), grads, n_ptr * sizeof(void *)) == 0;
   if (!same) {
-    slot = (ctx->cur_slot + 1) % kSlots;
-    if (ctx->ev_used[slot]) {
-      hipError_t e = hipEventSynchronize(ctx->ev[slot]);
-      if (e != hipSuccess) return fail_hip(ctx, e, "hipEventSynchronize");
-    }
-    std::memcpy(ctx->h_gtab[slot], grads, n_ptr * sizeof(void *));
-    hipError_t e = hipMemcpyAsync(ctx->d_gtab[slot], ctx->h_gtab[slot], n_ptr * sizeof(void *),
-                                  hipMemcpyHostToDevice, stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "upload of the gradient pointers");
-    e = hipEventRecord(ctx->ev[slot], stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_used[slot] = true;
+    hipError_t e = hipSuccess;
+    slot = ctx->gtab.upload(grads, n_ptr * sizeof(void *), stream, &e);
+    if (slot < 0) return fail_hip(ctx, e, "upload of the gradient pointers");
     ctx->last_grads.assign(grads, grads + n_ptr);
-    ctx->cur_slot = slot;
   }
 
   LocalArgs a{};
   a.tiles = ctx->d_ltiles;
   a.slots = ctx->d_slots;
   a.ntiles = ctx->n_ltiles;
-  a.gtab = ctx->d_gtab[slot];
+  a.gtab = static_cast<const void *const *>(ctx->gtab.d[slot]);
   a.h = ctx->h;
   a.v = ctx->v;
   a.lr = lr;
@@ -507,6 +532,61 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
     ctx->buffers_zero = true;
     ctx->l = 0;
   }
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer) {
+  if (m < 1 || step < 0 || !in_peer) return fail(nullptr, SLOWMO_ERR_ARG, "bad arguments");
+  if (m == 1) {
+    in_peer[0] = 0;
+    return SLOWMO_OK;
+  }
+  int n_hops = 1;  // hops 2^0 .. 2^floor(log2(m-1))
+  while ((int64_t(1) << n_hops) <= m - 1) ++n_hops;
+  const int64_t hop = int64_t(1) << (step % n_hops);
+  for (int32_t i = 0; i < m; ++i) in_peer[i] = static_cast<int32_t>(((i - hop) % m + m) % m);
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+  const int32_t m = ctx->cfg.m;
+  std::vector<char> hit(m, 0);
+  for (int32_t i = 0; i < m; ++i) {
+    if (in_peer[i] < 0 || in_peer[i] >= m || hit[in_peer[i]])
+      return fail(ctx, SLOWMO_ERR_ARG,
+                  "in_peer must be a permutation of 0..m-1 (one sender and one receiver per worker)");
+    hit[in_peer[i]] = 1;
+  }
+  // Workers listed cycle by cycle, each followed by the worker it receives
+  // from; bit 30 marks the first worker of a cycle.  Fixed points are idle.
+  std::vector<int32_t> seq;
+  std::vector<char> done(m, 0);
+  for (int32_t i = 0; i < m; ++i) {
+    if (done[i] || in_peer[i] == i) continue;
+    bool first = true;
+    for (int32_t j = i; !done[j]; j = in_peer[j]) {
+      done[j] = 1;
+      seq.push_back(first ? (j | kMixCycleStart) : j);
+      first = false;
+    }
+  }
+  if (seq.empty() || ctx->n_otiles == 0) return SLOWMO_OK;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipError_t e = hipSuccess;
+  const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(int32_t), stream, &e);
+  if (slot < 0) return fail_hip(ctx, e, "upload of the mixing sequence");
+  MixArgs a{};
+  a.tiles = ctx->d_otiles;
+  a.tensors = ctx->d_tensors;
+  a.xtab_t = ctx->d_xtab_t;
+  a.ntiles = ctx->n_otiles;
+  a.m = m;
+  a.seq = static_cast<const int32_t *>(ctx->mixtab.d[slot]);
+  a.len = static_cast<int32_t>(seq.size());
+  e = launch_mix_step(a, ctx->tune, stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
   return SLOWMO_OK;
 }
 

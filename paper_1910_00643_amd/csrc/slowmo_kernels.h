@@ -53,6 +53,19 @@ struct OuterNoAvgArgs {
   float lr, alpha_lr, beta;
 };
 
+// Mixing step of gradient push for a permutation: worker seq[t] receives from
+// worker seq[t+1] (cyclically inside a cycle); both get weight 1/2.
+constexpr int32_t kMixCycleStart = 1 << 30;
+struct MixArgs {
+  const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
+  const TensorInfo *tensors;   // device
+  float *const *xtab_t;        // device: replica pointers, tensor-major
+  int32_t ntiles;
+  int32_t m;
+  const int32_t *seq;          // device: len entries, bit 30 = first worker of a cycle
+  int32_t len;
+};
+
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
@@ -66,6 +79,7 @@ struct LaunchTuning {
 hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
                                    hipStream_t stream);
 

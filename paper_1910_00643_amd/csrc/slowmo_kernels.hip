@@ -360,6 +360,82 @@ __global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
   }
 }
 
+// ---- mixing step of stochastic gradient push (Algorithm C.1) ---------------------
+// x^{(i)} <- (x^{(i)} + x^{(in_peer(i))}) / 2 for a permutation in_peer, in
+// place.  The workers are visited cycle by cycle in the order "receiver, then
+// its sender": a worker's new value needs its own old value (held in a
+// register) and the next worker's (loaded next), so every replica is loaded
+// once and stored once; the cycle closes with the first worker's old value.
+// One workgroup = 256 elements of one tensor, all workers.
+constexpr int kMixBatch = 8;
+
+template <bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_mix_step(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const int32_t *__restrict__ seq, int len, int ntiles,
+    int chunk, int remap, int m) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (ti.unaligned == 0 && e0 + 4 <= n) {
+    V4 first = {0.f, 0.f, 0.f, 0.f}, cur = first;
+    float *prev = nullptr;
+    for (int base = 0; base < len; base += kMixBatch) {
+      V4 v[kMixBatch];
+      float *ptr[kMixBatch];
+#pragma unroll
+      for (int q = 0; q < kMixBatch; ++q) {
+        if (base + q < len) {
+          ptr[q] = xp[seq[base + q] & ~kMixCycleStart] + eo + e0;
+          v[q] = ld4<NT>(ptr[q]);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kMixBatch; ++q) {
+        if (base + q < len) {
+          const bool start = (seq[base + q] & kMixCycleStart) != 0;
+          if (start) {
+            if (prev) st4<NT>(prev, 0.5f * cur + 0.5f * first);
+            first = v[q];
+          } else {
+            st4<NT>(prev, 0.5f * cur + 0.5f * v[q]);
+          }
+          cur = v[q];
+          prev = ptr[q];
+        }
+      }
+    }
+    if (prev) st4<NT>(prev, 0.5f * cur + 0.5f * first);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      float first = 0.f, cur = 0.f;
+      float *prev = nullptr;
+      for (int i = 0; i < len; ++i) {
+        const int s = seq[i];
+        float *ptr = xp[s & ~kMixCycleStart] + eo + j;
+        const float v = ld1(ptr);
+        if (s & kMixCycleStart) {
+          if (prev) st1(prev, 0.5f * cur + 0.5f * first);
+          first = v;
+        } else {
+          st1(prev, 0.5f * cur + 0.5f * v);
+        }
+        cur = v;
+        prev = ptr;
+      }
+      if (prev) st1(prev, 0.5f * cur + 0.5f * first);
+    }
+  }
+}
+
 struct Grid {
   int chunk;
   unsigned blocks;
@@ -431,6 +507,19 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   }
   return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
                   : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
+}
+
+hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_mix_step<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+  } else {
+    hipLaunchKernelGGL((k_mix_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &t, hipStream_t s) {

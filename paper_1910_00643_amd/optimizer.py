@@ -74,6 +74,9 @@ class SlowMo:
         arr = grads if isinstance(grads, C.Array) else self.grad_pointer_array(grads)
         B.slowmo_local_step(self.ctx, arr, lr, torch.cuda.current_stream(self.device).cuda_stream)
 
+    def mix_step(self, in_peer: Sequence[int]) -> None:
+        B.slowmo_mix_step(self.ctx, in_peer, torch.cuda.current_stream(self.device).cuda_stream)
+
     def outer_step(self, lr: float) -> None:
         B.slowmo_outer_step(self.ctx, lr, torch.cuda.current_stream(self.device).cuda_stream)
 

@@ -39,6 +39,7 @@ class Workload:
     sigma: float = 1.0             # gradient standard deviation
     rounds: int = 3
     exact_average: bool = True     # False: the variant without line 6 of Algorithm 1 (Section 6)
+    mix: str = "none"              # "expgraph": a gossip step (Appendix C.1) after every local step
 
     @property
     def seed(self) -> int:

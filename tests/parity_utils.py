@@ -73,6 +73,8 @@ def run_oracles(w, index, rounds, precs=("f64",)):
             g = oracle_grads(w, index, t * w.tau + k)
             for p, o in os_.items():
                 o.local_step(g, lr)
+                if w.mix == "expgraph":     # stochastic gradient push: step, then gossip
+                    o.mix_step(O.exponential_graph_in_peers(w.m, t * w.tau + k))
                 if t == rounds - 1 and k == kb:
                     snaps[p].update(h=o.h.copy(), v=None if o.v is None else o.v.copy())
         for p, o in os_.items():
@@ -110,6 +112,9 @@ def run_gpu(w, prob, opt, rounds, index):
             s = step % prob.ring
             prob.fill_grads(s, step)
             opt.local_step(arrays[s], lr)
+            if w.mix == "expgraph":
+                import paper_1910_00643_amd as P
+                opt.mix_step(P.slowmo_expgraph_in_peers(w.m, step))
             step += 1
             if t == rounds - 1 and k == kb:
                 st = gpu_state(w, prob, opt, index, with_outer=False)

@@ -92,10 +92,24 @@ def test_create_rejects_bad_pointers_before_using_the_device():
     assert e.value.status == B.SLOWMO_ERR_ARG
 
 
+def test_exponential_graph_peers_match_the_oracles():
+    """Appendix C.1: hops 1, 2, 4, ..., 2^floor(log2(m-1)), one per iteration;
+    the library's table against the oracle's own implementation."""
+    from oracle import slowmo_oracle as O
+    for m in (1, 2, 3, 4, 5, 8, 19, 32, 33):
+        for step in range(9):
+            assert P.slowmo_expgraph_in_peers(m, step) == \
+                O.exponential_graph_in_peers(m, step).tolist()[:m], (m, step)
+    assert P.slowmo_expgraph_in_peers(32, 4) == [(i - 16) % 32 for i in range(32)]
+    with pytest.raises(P.SlowMoError):
+        P.slowmo_expgraph_in_peers(0, 0)
+
+
 def test_null_context_calls_fail_cleanly():
     lib = B.lib()
     assert lib.slowmo_local_step(None, None, 0.1, None) == B.SLOWMO_ERR_ARG
     assert lib.slowmo_outer_step(None, 0.1, None) == B.SLOWMO_ERR_ARG
+    assert lib.slowmo_mix_step(None, None, None) == B.SLOWMO_ERR_ARG
     assert lib.slowmo_destroy(None) == B.SLOWMO_OK
     assert lib.slowmo_get_counters(None, None, None, None) == B.SLOWMO_ERR_ARG
     assert "NULL" in P.slowmo_last_error(None)

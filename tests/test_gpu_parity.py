@@ -120,6 +120,45 @@ def test_noaverage_variant_every_element(base, grad_dtype, policy, param_layout)
     opt.close()
 
 
+@pytest.mark.parametrize("m,base,param_layout", [(4, "sgd_nesterov", "separate"),
+                                                 (8, "sgd_nesterov", "flat"),
+                                                 (6, "sgd_nesterov", "separate"),
+                                                 (19, "adam", "separate"), (1, "sgd_nesterov", "flat")])
+def test_gradient_push_mixing_every_element(m, base, param_layout):
+    """SGP as base optimizer (Algorithm C.1): every local step is followed by
+    a gossip step on the one-peer exponential graph; m = 6 and 19 give
+    permutations with several cycles, m = 1 an idle step."""
+    w = dataclasses.replace(W.ragged_mini(base=base, m=m, policy="maintain"), mix="expgraph",
+                            tau=7, rounds=2)
+    prob = _problem(w, ring=2, param_layout=param_layout, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"))
+    opt.close()
+
+
+def test_mixing_accepts_any_permutation_and_rejects_other_maps():
+    import paper_1910_00643_amd as P
+    w = dataclasses.replace(W.ragged_mini(m=5), tau=1, rounds=1)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    o = PU.make_oracle(w, idx)
+    prob.fill_grads(0, 0)
+    opt.local_step(prob.grads[0], w.lr)
+    o.local_step(PU.oracle_grads(w, idx, 0), w.f32("lr"))
+    for peers in ([1, 0, 2, 4, 3], [2, 3, 4, 0, 1], [0, 1, 2, 3, 4], [4, 0, 1, 2, 3]):
+        opt.mix_step(peers)
+        o.mix_step(peers)
+    got = np.stack([prob.gather(prob.params[i], idx) for i in range(w.m)])
+    PU.assert_params_close(got, o.x, "replicas after four mixing steps")
+    for bad in ([0, 0, 1, 2, 3], [1, 2, 3, 4, 5], [-1, 0, 1, 2, 3]):
+        with pytest.raises(P.SlowMoError) as e:
+            opt.mix_step(bad)
+        assert e.value.status == P.binding.SLOWMO_ERR_ARG
+    opt.close()
+
+
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
