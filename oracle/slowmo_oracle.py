@@ -111,7 +111,8 @@ class SlowMoOracle:
                  momentum: float = 0.0, weight_decay: float = 0.0,
                  beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
                  prec: str = "f64", lib: Optional[C.CDLL] = None,
-                 exact_average: bool = True):
+                 exact_average: bool = True, tensor_sizes=None,
+                 tensor_weight_decay=None, tensor_lr_scale=None):
         assert base in ("sgd_nesterov", "adam")
         if policy is None:      # the paper's defaults (Section 4, Appendix B.4)
             policy = "reset" if base == "sgd_nesterov" else "maintain"
@@ -126,6 +127,25 @@ class SlowMoOracle:
         self.base, self.policy = base, policy
         self.momentum, self.weight_decay = float(momentum), float(weight_decay)
         self.beta1, self.beta2, self.eps = float(beta1), float(beta2), float(eps)
+        # Optional per-tensor hyper-parameters ("parameter groups"): the flat
+        # range is cut into tensors of the given sizes; tensor j uses weight
+        # decay tensor_weight_decay[j] and the fast learning rate
+        # lr * tensor_lr_scale[j] wherever gamma_t appears (Algorithm 1 lines
+        # 4, 7 and 8).  The paper uses one value for all parameters.
+        if tensor_sizes is None:
+            assert tensor_weight_decay is None and tensor_lr_scale is None
+            self.bounds = None
+        else:
+            sizes = [int(n) for n in tensor_sizes]
+            assert sum(sizes) == self.d
+            ends = np.cumsum(sizes)
+            self.bounds = [(int(e - n), int(e)) for n, e in zip(sizes, ends)]
+            nt = len(sizes)
+            self.t_wd = [self.weight_decay] * nt if tensor_weight_decay is None \
+                else [float(v) for v in tensor_weight_decay]
+            self.t_lr = [1.0] * nt if tensor_lr_scale is None \
+                else [float(v) for v in tensor_lr_scale]
+            assert len(self.t_wd) == nt and len(self.t_lr) == nt
         self.exact_average = bool(exact_average)
         self.x0 = x_init.astype(self.dtype).reshape(self.d).copy()
         self.x = np.tile(self.x0, (self.m, 1))
@@ -165,16 +185,27 @@ class SlowMoOracle:
         if self.base == "adam":
             self.l += 1
         for i in range(self.m):
-            if self.base == "sgd_nesterov":
-                self.lib.oracle_sgd_nesterov_step(
-                    _ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,
-                    lr, self.momentum, self.weight_decay)
-            else:
-                self.lib.oracle_adam_step(
-                    _ptr(self.x[i]), _ptr(self.h[i]), _ptr(self.v[i]), _ptr(g[i]),
-                    self.d, lr, self.beta1, self.beta2, self.eps,
-                    self.weight_decay, self.l)
+            for a, b, lr_j, wd_j in self._groups(lr):
+                if self.base == "sgd_nesterov":
+                    self.lib.oracle_sgd_nesterov_step(
+                        _ptr(self.x[i][a:b]), _ptr(self.h[i][a:b]), _ptr(g[i][a:b]), b - a,
+                        lr_j, self.momentum, wd_j)
+                else:
+                    self.lib.oracle_adam_step(
+                        _ptr(self.x[i][a:b]), _ptr(self.h[i][a:b]), _ptr(self.v[i][a:b]),
+                        _ptr(g[i][a:b]), b - a, lr_j, self.beta1, self.beta2, self.eps,
+                        wd_j, self.l)
         self.k += 1
+
+    def _groups(self, lr: float):
+        """(begin, end, learning rate, weight decay) of every parameter group:
+        the whole range unless per-tensor hyper-parameters were given.  The
+        scaled learning rate is rounded to fp32, the precision in which it
+        reaches the kernels."""
+        if self.bounds is None:
+            return [(0, self.d, lr, self.weight_decay)]
+        return [(a, b, float(np.float32(np.float32(lr) * np.float32(s))), wd)
+                for (a, b), s, wd in zip(self.bounds, self.t_lr, self.t_wd) if b > a]
 
     exponential_graph_in_peers = staticmethod(exponential_graph_in_peers)
 
@@ -194,15 +225,25 @@ class SlowMoOracle:
     # Algorithm 1 lines 6-8 (+ copy of x_{t+1,0} into every replica)
     def outer_step(self, lr: float) -> None:
         assert self.k == self.tau, "outer step needs exactly tau local steps"
-        if self.exact_average:
+        if self.exact_average and self.bounds is None:
             self.lib.oracle_outer_step(_ptr(self.x), self.m, self.d, _ptr(self.x0),
                                        _ptr(self.u), lr, self.alpha, self.beta)
+        elif self.exact_average:
+            # per tensor, with that tensor's gamma_t; the C routine wants the m
+            # replicas of the range contiguous, so the range is copied out and back
+            for a, b, lr_j, _ in self._groups(lr):
+                xs = np.ascontiguousarray(self.x[:, a:b])
+                self.lib.oracle_outer_step(_ptr(xs), self.m, b - a, _ptr(self.x0[a:b]),
+                                           _ptr(self.u[a:b]), lr_j, self.alpha, self.beta)
+                self.x[:, a:b] = xs
         else:
             # lines 7-8 on each worker's own replica: the "average" over that
             # one replica is the replica itself
             for i in range(self.m):
-                self.lib.oracle_outer_step(_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),
-                                           _ptr(self.u[i]), lr, self.alpha, self.beta)
+                for a, b, lr_j, _ in self._groups(lr):
+                    self.lib.oracle_outer_step(_ptr(self.x[i][a:b]), 1, b - a,
+                                               _ptr(self.x0[i][a:b]), _ptr(self.u[i][a:b]),
+                                               lr_j, self.alpha, self.beta)
         if self.exact_average:
             self.w[...] = 1     # all mass is shared equally again after the exact average
         self.k = 0

@@ -619,4 +619,64 @@ def pin_mixing_debiased_iterates_reach_consensus(make):
         _close(o.debiased()[i], mean, rtol=1e-9, atol=1e-10, what="push-sum consensus")
 
 
+# ------------------------------------------- per-tensor hyper-parameters
+
+def pin_parameter_groups_vs_library(make):
+    """Per-tensor weight decay and learning-rate scale are the library
+    optimizers' parameter groups: m = 1, alpha = 1, beta = 0 leaves the bare
+    base optimizer, compared with torch.optim.SGD / Adam with one group per
+    tensor."""
+    rng = _rng(50)
+    T, tau, lr, mu = 2, 4, 0.05, 0.9
+    sizes = [5, 1, 7, 3]
+    wds = [1e-2, 0.0, 5e-3, 0.0]
+    scales = [1.0, 0.5, 2.0, 0.25]
+    d = sum(sizes)
+    g = _grads(rng, T, tau, 1, d)
+    x_init = rng.standard_normal(d)
+    bounds = np.cumsum([0] + sizes)
+    for base in ("sgd_nesterov", "adam"):
+        kw = dict(momentum=mu) if base == "sgd_nesterov" else dict(beta2=0.98)
+        o = make(x_init, m=1, tau=tau, alpha=1.0, beta=0.0, base=base, policy="maintain",
+                 tensor_sizes=sizes, tensor_weight_decay=wds, tensor_lr_scale=scales, **kw)
+        ps = [torch.tensor(x_init[a:b], dtype=torch.float64, requires_grad=True)
+              for a, b in zip(bounds[:-1], bounds[1:])]
+        # the oracle rounds lr * scale to fp32, as the kernels receive it
+        groups = [dict(params=[p], lr=float(np.float32(np.float32(lr) * np.float32(s))),
+                       weight_decay=w) for p, s, w in zip(ps, scales, wds)]
+        opt = torch.optim.SGD(groups, lr=lr, momentum=mu, nesterov=True) \
+            if base == "sgd_nesterov" else torch.optim.Adam(groups, lr=lr, betas=(0.9, 0.98))
+        for t in range(T):
+            for k in range(tau):
+                o.local_step(g[t, k], lr)
+                for p, a, b in zip(ps, bounds[:-1], bounds[1:]):
+                    p.grad = torch.tensor(g[t, k, 0, a:b].astype(np.float64))
+                opt.step()
+            o.outer_step(lr)
+        want = np.concatenate([p.detach().numpy() for p in ps])
+        _close(o.x0, want, rtol=1e-10, atol=1e-12, what=f"parameter groups ({base})")
+
+
+def pin_per_tensor_learning_rate_keeps_u_in_gradient_units(make):
+    """Section 2: dividing by gamma_t keeps u free of the fast learning rate.
+    With per-tensor gamma_t (plain SGD base) u must therefore not depend on
+    the scales at all, and each tensor's iterate moves as if it were alone."""
+    rng = _rng(51)
+    T, tau, m, lr = 3, 3, 3, float(np.float32(0.1))    # scaled rates are rounded to fp32
+    sizes = [4, 6]
+    d = sum(sizes)
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    ref = make(x_init, m=m, tau=tau, alpha=0.9, beta=0.6)
+    ref.run(lambda t, k: g[t, k], lr, T)
+    o = make(x_init, m=m, tau=tau, alpha=0.9, beta=0.6, tensor_sizes=sizes,
+             tensor_lr_scale=[1.0, 0.5])
+    o.run(lambda t, k: g[t, k], lr, T)
+    _close(o.u, ref.u, rtol=1e-10, atol=1e-11, what="u does not see the scales")
+    _close(o.x0[:4], ref.x0[:4], rtol=1e-12, what="tensor with scale 1")
+    half = make(x_init, m=m, tau=tau, alpha=0.9, beta=0.6)
+    half.run(lambda t, k: g[t, k], 0.5 * lr, T)
+    _close(o.x0[4:], half.x0[4:], rtol=1e-12, what="tensor with scale 1/2")
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

@@ -67,20 +67,25 @@ PY_MUTANTS = [
      "                self.v[...] = 0\n", 0),
     ("policy_only_first_iteration", "if self.k == 0:", "if self.k == 0 and self.t == 0:", 0),
     ("policy_every_step", "if self.k == 0:", "if True:", 0),
-    ("sgd_all_workers_use_grad0", "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,",
-     "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[0]), self.d,", 0),
-    ("sgd_workers_share_h", "_ptr(self.x[i]), _ptr(self.h[i]), _ptr(g[i]), self.d,",
-     "_ptr(self.x[i]), _ptr(self.h[0]), _ptr(g[i]), self.d,", 0),
-    ("adam_all_workers_use_grad0", "_ptr(self.v[i]), _ptr(g[i]),", "_ptr(self.v[i]), _ptr(g[0]),", 0),
+    ("sgd_all_workers_use_grad0", "_ptr(self.h[i][a:b]), _ptr(g[i][a:b]), b - a,",
+     "_ptr(self.h[i][a:b]), _ptr(g[0][a:b]), b - a,", 0),
+    ("sgd_workers_share_h", "_ptr(self.x[i][a:b]), _ptr(self.h[i][a:b]), _ptr(g[i][a:b]), b - a,",
+     "_ptr(self.x[i][a:b]), _ptr(self.h[0][a:b]), _ptr(g[i][a:b]), b - a,", 0),
+    ("adam_all_workers_use_grad0", "_ptr(g[i][a:b]), b - a, lr_j, self.beta1,",
+     "_ptr(g[0][a:b]), b - a, lr_j, self.beta1,", 0),
     ("outer_alpha_beta_swapped", "lr, self.alpha, self.beta)", "lr, self.beta, self.alpha)", 0),
     ("average_skips_v", "            if self.v is not None:\n                self.lib.oracle_average_buffers(_ptr(self.v), self.m, self.d)\n", "", 0),
     ("average_skips_h", "            self.lib.oracle_average_buffers(_ptr(self.h), self.m, self.d)\n", "            pass\n", 0),
     ("average_resets_step_count", '        elif self.policy == "average":\n', '        elif self.policy == "average":\n            self.l = 0\n', 0),
-    ("noaverage_shares_x0", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[i]),", "_ptr(self.x[i]), 1, self.d, _ptr(self.x0[0]),", 0),
-    ("noaverage_shares_u", "_ptr(self.u[i]), lr, self.alpha, self.beta)", "_ptr(self.u[0]), lr, self.alpha, self.beta)", 0),
-    ("noaverage_only_worker0", "            for i in range(self.m):\n                self.lib.oracle_outer_step(", "            for i in range(1):\n                self.lib.oracle_outer_step(", 0),
+    ("noaverage_shares_x0", "_ptr(self.x0[i][a:b]), _ptr(self.u[i][a:b]),", "_ptr(self.x0[0][a:b]), _ptr(self.u[i][a:b]),", 0),
+    ("noaverage_shares_u", "_ptr(self.x0[i][a:b]), _ptr(self.u[i][a:b]),", "_ptr(self.x0[i][a:b]), _ptr(self.u[0][a:b]),", 0),
+    ("noaverage_only_worker0", "            for i in range(self.m):\n                for a, b, lr_j, _ in self._groups(lr):", "            for i in range(1):\n                for a, b, lr_j, _ in self._groups(lr):", 0),
     ("expgraph_sends_forward", "return ((np.arange(m) - hop) % m)", "return ((np.arange(m) + hop) % m)", 0),
     ("expgraph_hop_linear", "hop = 1 << (step % n_hops)", "hop = 1 + (step % n_hops)", 0),
+    ("groups_ignore_lr_scale", "np.float32(lr) * np.float32(s)", "np.float32(lr)", 0),
+    ("groups_ignore_tensor_wd", "lr_j, self.momentum, wd_j)", "lr_j, self.momentum, self.weight_decay)", 0),
+    ("groups_outer_uses_global_lr", "_ptr(self.u[a:b]), lr_j, self.alpha, self.beta)", "_ptr(self.u[a:b]), lr, self.alpha, self.beta)", 0),
+    ("groups_outer_not_copied_back", "                self.x[:, a:b] = xs\n", "", 0),
     ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
      'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
 ]
