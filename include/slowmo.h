@@ -171,6 +171,37 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
  */
 slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer);
 
+/*
+ * Per-tensor hyper-parameters ("parameter groups").  The paper uses one
+ * weight decay and one gamma_t for all parameters; this lets tensor j use
+ *   weight decay weight_decay[j] instead of cfg.weight_decay, and
+ *   the fast learning rate lr * lr_scale[j] wherever gamma_t acts on its
+ *   elements: the local steps, Eq. (2) and Eq. (3) (so u stays in gradient
+ *   units for every tensor, as Section 2 intends).
+ * Host arrays of n_tensors entries; either may be NULL (left unchanged).
+ * Applies to all later calls.  Synchronizes `stream`.
+ * Errors: ARG (weight decay negative or non-finite, scale <= 0 or non-finite), HIP.
+ */
+slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_decay,
+                                        const float *lr_scale, void *stream);
+
+/*
+ * Checkpointing.  The optimizer's state is x0, u, h (and v) plus the counters
+ * t, k, l; slowmo_export_state packs it into one DEVICE buffer of
+ * slowmo_export_bytes() bytes (a 256-byte header, then the arrays), which the
+ * caller may copy anywhere; slowmo_import_state restores it into a context
+ * created with the same configuration and tensor list (otherwise ARG).  The
+ * replicas themselves belong to the caller and are not part of the blob; as
+ * slowmo_create overwrites replicas 1..m-1, restore them AFTER create when
+ * resuming inside an outer iteration.  Per-tensor hyper-parameters are
+ * configuration, not state: set them again.  Both calls synchronize `stream`.
+ * Errors: ARG, NOMEM (destination too small), HIP.
+ */
+size_t slowmo_export_bytes(const slowmo_ctx *ctx);
+slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst_device, size_t bytes, void *stream);
+slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src_device, size_t bytes,
+                                  void *stream);
+
 /* Frees the context's host memory and its small device-side bookkeeping.
  * Never touches parameters, gradients or the workspace.  NULL is accepted. */
 slowmo_status slowmo_destroy(slowmo_ctx *ctx);

@@ -30,7 +30,8 @@ STATUS_NAMES = {0: "SLOWMO_OK", -1: "SLOWMO_ERR_ARG", -2: "SLOWMO_ERR_STATE",
 EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_outer_step",
            "slowmo_destroy", "slowmo_last_error", "slowmo_get_buffer", "slowmo_get_counters",
            "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version", "slowmo_mix_step",
-           "slowmo_expgraph_in_peers"]
+           "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
+           "slowmo_export_state", "slowmo_import_state"]
 
 
 class slowmo_config(C.Structure):
@@ -92,6 +93,14 @@ def lib() -> C.CDLL:
     L.slowmo_mix_step.restype = C.c_int
     L.slowmo_expgraph_in_peers.argtypes = [i32, i64, C.POINTER(i32)]
     L.slowmo_expgraph_in_peers.restype = C.c_int
+    L.slowmo_set_tensor_hparams.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
+    L.slowmo_set_tensor_hparams.restype = C.c_int
+    L.slowmo_export_bytes.argtypes = [vp]
+    L.slowmo_export_bytes.restype = C.c_size_t
+    L.slowmo_export_state.argtypes = [vp, vp, C.c_size_t, vp]
+    L.slowmo_export_state.restype = C.c_int
+    L.slowmo_import_state.argtypes = [vp, vp, C.c_size_t, vp]
+    L.slowmo_import_state.restype = C.c_int
     L.slowmo_version.argtypes = []
     L.slowmo_version.restype = C.c_char_p
     _lib = L
@@ -163,6 +172,33 @@ def slowmo_expgraph_in_peers(m: int, step: int):
     arr = (C.c_int32 * max(m, 1))()
     _check(lib().slowmo_expgraph_in_peers(m, step, arr), None)
     return list(arr[:m])
+
+
+def _f32_array(values):
+    if values is None:
+        return None
+    return (C.c_float * len(values))(*[float(v) for v in values])
+
+
+def slowmo_set_tensor_hparams(ctx, weight_decay=None, lr_scale=None, stream: int = 0) -> None:
+    """Per-tensor weight decay / learning-rate scale (sequences of n_tensors or None)."""
+    _check(lib().slowmo_set_tensor_hparams(ctx, _f32_array(weight_decay), _f32_array(lr_scale),
+                                           C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_export_bytes(ctx) -> int:
+    return int(lib().slowmo_export_bytes(ctx))
+
+
+def slowmo_export_state(ctx, dst: int, nbytes: int, stream: int = 0) -> None:
+    """dst: device address of a buffer of at least slowmo_export_bytes(ctx)."""
+    _check(lib().slowmo_export_state(ctx, C.c_void_p(dst) if dst else None, nbytes,
+                                     C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_import_state(ctx, src: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().slowmo_import_state(ctx, C.c_void_p(src) if src else None, nbytes,
+                                     C.c_void_p(stream) if stream else None), ctx)
 
 
 def slowmo_destroy(ctx) -> None:

@@ -174,6 +174,8 @@ struct slowmo_ctx {
   TableRing gtab;    // gradient pointers of the current call (m * n_tensors)
   std::vector<const void *> last_grads;  // contents of gtab's current slot
   TableRing mixtab;  // worker sequence of the current mixing step (m entries)
+  std::vector<SlotInfo> slots;      // host copies of the per-slot / per-tensor tables
+  std::vector<TensorInfo> tinfo;
 
   int64_t t = 0;  // outer iterations done
   int32_t k = 0;  // local steps in the current outer iteration
@@ -349,14 +351,17 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
 
   // device tables
   const Layout &L = ctx->layout;
-  std::vector<SlotInfo> slots(n_ptr);
-  std::vector<TensorInfo> tinfo(n_tensors);
+  std::vector<SlotInfo> &slots = ctx->slots;
+  std::vector<TensorInfo> &tinfo = ctx->tinfo;
+  slots.resize(n_ptr);
+  tinfo.resize(n_tensors);
   std::vector<float *> xtab_t(n_ptr);
-  for (int32_t j = 0; j < n_tensors; ++j) tinfo[j] = {L.arena_off[j], numel[j], 0, 0};
+  for (int32_t j = 0; j < n_tensors; ++j) tinfo[j] = {L.arena_off[j], numel[j], 0, 1.0f, 0.f};
   for (int32_t w = 0; w < m; ++w) {
     for (int32_t j = 0; j < n_tensors; ++j) {
       const size_t slot = static_cast<size_t>(w) * n_tensors + j;
-      slots[slot] = {params[slot], static_cast<int64_t>(w) * L.d_pad + L.arena_off[j], numel[j], 0};
+      slots[slot] = {params[slot], static_cast<int64_t>(w) * L.d_pad + L.arena_off[j], numel[j],
+                     cfg->weight_decay, 1.0f};
       xtab_t[static_cast<size_t>(j) * m + w] = params[slot];
       if (reinterpret_cast<uintptr_t>(params[slot]) & 15) tinfo[j].unaligned = 1;
     }
@@ -495,7 +500,7 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
     na.x0 = ctx->x0;
     na.u = ctx->u;
     na.lr = lr;
-    na.alpha_lr = c.alpha * lr;
+    na.alpha = c.alpha;
     na.beta = c.beta;
     hipError_t e = launch_outer_noavg_step(na, ctx->tune, static_cast<hipStream_t>(stream_));
     if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
@@ -516,7 +521,7 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   a.x0 = ctx->x0;
   a.u = ctx->u;
   a.lr = lr;
-  a.alpha_lr = c.alpha * lr;  // one fp32 rounding, as (alpha * gamma_t) in Eq. (3)
+  a.alpha = c.alpha;
   a.beta = c.beta;
   a.m_f = static_cast<float>(c.m);
   if (c.policy == SLOWMO_BUF_AVERAGE) {  // Algorithm 1 line 2 of the next outer iteration
@@ -587,6 +592,137 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
   a.len = static_cast<int32_t>(seq.size());
   e = launch_mix_step(a, ctx->tune, stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_decay,
+                                        const float *lr_scale, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  const int32_t nt = ctx->n_tensors, m = ctx->cfg.m;
+  for (int32_t j = 0; j < nt; ++j) {
+    if (weight_decay && !(std::isfinite(weight_decay[j]) && weight_decay[j] >= 0.f))
+      return fail(ctx, SLOWMO_ERR_ARG, "weight_decay entries must be finite and >= 0");
+    if (lr_scale && !finite_pos(lr_scale[j]))
+      return fail(ctx, SLOWMO_ERR_ARG, "lr_scale entries must be finite and > 0");
+  }
+  for (int32_t j = 0; j < nt; ++j) {
+    if (lr_scale) ctx->tinfo[j].lr_scale = lr_scale[j];
+    for (int32_t w = 0; w < m; ++w) {
+      SlotInfo &s = ctx->slots[static_cast<size_t>(w) * nt + j];
+      if (weight_decay) s.wd = weight_decay[j];
+      if (lr_scale) s.lr_scale = lr_scale[j];
+    }
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipError_t e = hipMemcpyAsync(ctx->d_slots, ctx->slots.data(), ctx->slots.size() * sizeof(SlotInfo),
+                                hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(ctx->d_tensors, ctx->tinfo.data(), ctx->tinfo.size() * sizeof(TensorInfo),
+                       hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the host tables may change again
+  if (e != hipSuccess) return fail_hip(ctx, e, "upload of the per-tensor hyper-parameters");
+  return SLOWMO_OK;
+}
+
+namespace {
+
+// Header of an exported state blob (256 bytes), followed by the x0, u, h, v
+// arenas exactly as they lie in the workspace.
+struct BlobHeader {
+  char magic[8];
+  uint32_t version;
+  int32_t m, n_tensors, base, no_average, k, buffers_zero, reserved;
+  int64_t d, d_pad, t, l;
+  char pad_[256 - 8 - 4 * 8 - 8 * 4];
+};
+static_assert(sizeof(BlobHeader) == 256, "BlobHeader layout");
+constexpr char kBlobMagic[8] = {'S', 'L', 'O', 'W', 'M', 'O', 'S', 'T'};
+
+struct BlobParts {
+  size_t arena, outer_copies, n_v, total;
+};
+BlobParts blob_parts(const slowmo_ctx *ctx) {
+  BlobParts p;
+  p.arena = static_cast<size_t>(ctx->layout.d_pad) * sizeof(float);
+  p.outer_copies = ctx->cfg.no_average ? ctx->cfg.m : 1;
+  p.n_v = ctx->v ? ctx->cfg.m : 0;
+  p.total = sizeof(BlobHeader) + p.arena * (2 * p.outer_copies + ctx->cfg.m + p.n_v);
+  return p;
+}
+
+}  // namespace
+
+size_t slowmo_export_bytes(const slowmo_ctx *ctx) { return ctx ? blob_parts(ctx).total : 0; }
+
+slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst, size_t bytes, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!dst) return fail(ctx, SLOWMO_ERR_ARG, "dst is NULL");
+  const BlobParts p = blob_parts(ctx);
+  if (bytes < p.total) return fail(ctx, SLOWMO_ERR_NOMEM, "destination smaller than slowmo_export_bytes()");
+  BlobHeader hd{};
+  std::memcpy(hd.magic, kBlobMagic, 8);
+  hd.version = 1;
+  hd.m = ctx->cfg.m;
+  hd.n_tensors = ctx->n_tensors;
+  hd.base = ctx->cfg.base;
+  hd.no_average = ctx->cfg.no_average;
+  hd.d = ctx->layout.d;
+  hd.d_pad = ctx->layout.d_pad;
+  hd.t = ctx->t;
+  hd.l = ctx->l;
+  hd.k = ctx->k;
+  hd.buffers_zero = ctx->buffers_zero ? 1 : 0;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  char *out = static_cast<char *>(dst);
+  hipError_t e = hipMemcpyAsync(out, &hd, sizeof(hd), hipMemcpyHostToDevice, stream);
+  size_t off = sizeof(hd);
+  auto put = [&](const float *src, size_t n) {
+    if (e == hipSuccess && n)
+      e = hipMemcpyAsync(out + off, src, n, hipMemcpyDeviceToDevice, stream);
+    off += n;
+  };
+  put(ctx->x0, p.arena * p.outer_copies);
+  put(ctx->u, p.arena * p.outer_copies);
+  put(ctx->h, p.arena * ctx->cfg.m);
+  put(ctx->v, p.arena * p.n_v);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the header lives on this stack frame
+  if (e != hipSuccess) return fail_hip(ctx, e, "state export");
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!src) return fail(ctx, SLOWMO_ERR_ARG, "src is NULL");
+  const BlobParts p = blob_parts(ctx);
+  if (bytes < p.total) return fail(ctx, SLOWMO_ERR_ARG, "blob shorter than this context's state");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  BlobHeader hd{};
+  hipError_t e = hipMemcpyAsync(&hd, src, sizeof(hd), hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "reading the blob header");
+  if (std::memcmp(hd.magic, kBlobMagic, 8) != 0 || hd.version != 1)
+    return fail(ctx, SLOWMO_ERR_ARG, "not a state blob of this library version");
+  if (hd.m != ctx->cfg.m || hd.n_tensors != ctx->n_tensors || hd.base != ctx->cfg.base ||
+      hd.no_average != ctx->cfg.no_average || hd.d != ctx->layout.d || hd.d_pad != ctx->layout.d_pad)
+    return fail(ctx, SLOWMO_ERR_ARG, "the blob was exported from a different configuration or tensor list");
+  if (hd.k < 0 || hd.k > ctx->cfg.tau || hd.t < 0 || hd.l < 0)
+    return fail(ctx, SLOWMO_ERR_ARG, "the blob's counters do not fit this configuration");
+  const char *in = static_cast<const char *>(src);
+  size_t off = sizeof(hd);
+  auto get = [&](float *dst, size_t n) {
+    if (e == hipSuccess && n)
+      e = hipMemcpyAsync(dst, in + off, n, hipMemcpyDeviceToDevice, stream);
+    off += n;
+  };
+  get(ctx->x0, p.arena * p.outer_copies);
+  get(ctx->u, p.arena * p.outer_copies);
+  get(ctx->h, p.arena * ctx->cfg.m);
+  get(ctx->v, p.arena * p.n_v);
+  if (e != hipSuccess) return fail_hip(ctx, e, "state import");
+  ctx->t = hd.t;
+  ctx->k = hd.k;
+  ctx->l = hd.l;
+  ctx->buffers_zero = hd.buffers_zero != 0;
   return SLOWMO_OK;
 }
 

@@ -32,8 +32,8 @@ struct OuterArgs {
   int32_t m;
   float *x0;                   // device: arena d_pad
   float *u;                    // device: arena d_pad
-  float lr;                    // gamma_t
-  float alpha_lr;              // alpha * gamma_t, rounded once to fp32
+  float lr;                    // gamma_t (scaled per tensor in the kernel)
+  float alpha;                 // slow learning rate; (alpha * gamma_t) is rounded once to fp32
   float beta;
   float m_f;                   // (float) m
   // buffer strategy "average": arenas to average over the workers (nullptr = skip)
@@ -50,7 +50,7 @@ struct OuterNoAvgArgs {
   int32_t ntiles;
   float *x0;                   // device: m * d_pad
   float *u;                    // device: m * d_pad
-  float lr, alpha_lr, beta;
+  float lr, alpha, beta;
 };
 
 // Mixing step of gradient push for a permutation: worker seq[t] receives from

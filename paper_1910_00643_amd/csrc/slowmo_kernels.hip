@@ -135,8 +135,14 @@ __device__ __forceinline__ void adam_elem(float &x, float &h, float &v, float g,
 }
 
 struct OuterP {
-  float lr, alpha_lr, beta, m_f;
+  float lr, alpha_lr, beta, m_f, alpha;
 };
+// gamma_t of one tensor: lr * lr_scale, and (alpha * gamma_t), each rounded once.
+__device__ __forceinline__ OuterP for_tensor(OuterP p, float lr_scale) {
+  p.lr = p.lr * lr_scale;
+  p.alpha_lr = p.alpha * p.lr;
+  return p;
+}
 // Algorithm 1 lines 6-8 for one element, given the ordered sum s of the
 // replicas.  Returns x_{t+1,0}.
 __device__ __forceinline__ float outer_elem(float s, float x0, float &u, const OuterP &p) {
@@ -163,6 +169,11 @@ __global__ __launch_bounds__(kLocalBlock) void k_local_step(
   if (tile >= ntiles) return;
   const TileRef t = tiles[tile];         // uniform: scalar loads
   const SlotInfo s = slots[t.owner];
+  // per-tensor hyper-parameters (uniform over the workgroup)
+  sp.lr = sp.lr * s.lr_scale;
+  sp.wd = s.wd;
+  ap.lr = ap.lr * s.lr_scale;
+  ap.wd = s.wd;
   constexpr int gsize = BF16 ? 2 : 4;
   const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;  // offset of the tile in its tensor
   const void *g = static_cast<const char *>(gtab[t.owner]) + go * gsize;
@@ -266,11 +277,12 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
     float *__restrict__ hbase, float *__restrict__ vbase, int64_t d_pad, int ntiles, int chunk,
-    int remap, int m, OuterP p) {
+    int remap, int m, OuterP p0) {
   const int tile = tile_of(blockIdx.x, chunk, remap);
   if (tile >= ntiles) return;
   const TileRef t = tiles[tile];         // uniform: scalar loads
   const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
   const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;  // offset of the tile in its tensor
   const int64_t left = ti.numel - eo;
   const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
@@ -324,11 +336,12 @@ template <bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
     const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
     float *__restrict__ x0base, float *__restrict__ ubase, int ntiles, int chunk, int remap,
-    OuterP p) {
+    OuterP p0) {
   const int tile = tile_of(blockIdx.x, chunk, remap);
   if (tile >= ntiles) return;
   const TileRef t = tiles[tile];
   const SlotInfo s = slots[t.owner];
+  const OuterP p = for_tensor(p0, s.lr_scale);
   const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;
   float *x = s.x + go;
   float *x0 = x0base + s.so + go;
@@ -491,7 +504,7 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
 template <bool NT, int AVG>
 hipError_t launch_outer_t(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(a.ntiles, t.xcd_remap);
-  const OuterP p{a.lr, a.alpha_lr, a.beta, a.m_f};
+  const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
   hipLaunchKernelGGL((k_outer_step<NT, AVG>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s,
                      a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad, a.ntiles,
                      g.chunk, t.xcd_remap, a.m, p);
@@ -525,7 +538,7 @@ hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t 
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
   const Grid g = make_grid(a.ntiles, t.xcd_remap);
-  const OuterP p{a.lr, a.alpha_lr, a.beta, 1.0f};
+  const OuterP p{a.lr, 0.f, a.beta, 1.0f, a.alpha};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_outer_noavg<true>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles,
                        a.slots, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, p);

@@ -45,7 +45,8 @@ struct SlotInfo {
   float *x;        // device: the worker's replica of the tensor
   int64_t so;      // element offset of the tensor in the h / v arena (includes worker * d_pad)
   int64_t numel;   // elements in the tensor
-  int64_t pad_;
+  float wd;        // weight decay of this tensor
+  float lr_scale;  // the tensor's fast learning rate is lr * lr_scale
 };
 static_assert(sizeof(SlotInfo) == 32, "SlotInfo layout");
 
@@ -54,7 +55,8 @@ struct TensorInfo {
   int64_t fo;         // element offset of the tensor in the x0 / u arena
   int64_t numel;
   int64_t unaligned;  // non-zero: some replica of this tensor is not 16-byte aligned
-  int64_t pad_;
+  float lr_scale;     // the tensor's fast learning rate is lr * lr_scale
+  float pad_;
 };
 static_assert(sizeof(TensorInfo) == 32, "TensorInfo layout");
 

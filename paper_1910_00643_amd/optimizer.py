@@ -80,6 +80,23 @@ class SlowMo:
     def outer_step(self, lr: float) -> None:
         B.slowmo_outer_step(self.ctx, lr, torch.cuda.current_stream(self.device).cuda_stream)
 
+    def set_tensor_hparams(self, weight_decay=None, lr_scale=None) -> None:
+        B.slowmo_set_tensor_hparams(self.ctx, weight_decay, lr_scale,
+                                    torch.cuda.current_stream(self.device).cuda_stream)
+
+    def export_state(self) -> torch.Tensor:
+        """The optimizer state (x0, u, h, v, counters) as one uint8 CUDA tensor."""
+        n = B.slowmo_export_bytes(self.ctx)
+        blob = torch.empty(n, dtype=torch.uint8, device=self.device)
+        B.slowmo_export_state(self.ctx, blob.data_ptr(), n,
+                              torch.cuda.current_stream(self.device).cuda_stream)
+        return blob
+
+    def import_state(self, blob: torch.Tensor) -> None:
+        assert blob.dtype == torch.uint8 and blob.is_contiguous() and blob.device == self.device
+        B.slowmo_import_state(self.ctx, blob.data_ptr(), blob.numel(),
+                              torch.cuda.current_stream(self.device).cuda_stream)
+
     def counters(self):
         return B.slowmo_get_counters(self.ctx)
 

@@ -40,6 +40,8 @@ class Workload:
     rounds: int = 3
     exact_average: bool = True     # False: the variant without line 6 of Algorithm 1 (Section 6)
     mix: str = "none"              # "expgraph": a gossip step (Appendix C.1) after every local step
+    tensor_wd: tuple | None = None        # per-tensor weight decay (else weight_decay for all)
+    tensor_lr_scale: tuple | None = None  # per-tensor factor on the fast learning rate
 
     @property
     def seed(self) -> int:

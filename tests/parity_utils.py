@@ -52,7 +52,21 @@ def make_oracle(w, index, prec="f64"):
                           policy=w.policy, momentum=w.f32("momentum"),
                           weight_decay=w.f32("weight_decay"), beta1=w.f32("beta1"),
                           beta2=w.f32("beta2"), eps=w.f32("eps"), prec=prec,
-                          exact_average=w.exact_average)
+                          exact_average=w.exact_average, **_oracle_groups(w, index))
+
+
+def _oracle_groups(w, index):
+    """Per-tensor hyper-parameters for an oracle that runs on the element
+    subset `index`: group sizes are the number of sampled elements per tensor;
+    values are the fp32 numbers the library receives."""
+    if w.tensor_wd is None and w.tensor_lr_scale is None:
+        return {}
+    ends = w.tensor_starts + np.asarray(w.numel, dtype=np.int64)
+    tensor = np.searchsorted(ends, np.asarray(index, dtype=np.int64), side="right")
+    sizes = np.bincount(tensor, minlength=len(w.numel))
+    f32 = lambda vals: None if vals is None else [float(np.float32(v)) for v in vals]  # noqa: E731
+    return dict(tensor_sizes=sizes.tolist(), tensor_weight_decay=f32(w.tensor_wd),
+                tensor_lr_scale=f32(w.tensor_lr_scale))
 
 
 def oracle_grads(w, index, step):
@@ -95,7 +109,10 @@ def make_gpu(w, prob):
                       policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
                       weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                       no_average=not w.exact_average)
-    return SlowMo(prob.params, cfg)
+    opt = SlowMo(prob.params, cfg)
+    if w.tensor_wd is not None or w.tensor_lr_scale is not None:
+        opt.set_tensor_hparams(w.tensor_wd, w.tensor_lr_scale)
+    return opt
 
 
 def run_gpu(w, prob, opt, rounds, index):

@@ -159,6 +159,84 @@ def test_mixing_accepts_any_permutation_and_rejects_other_maps():
     opt.close()
 
 
+@pytest.mark.parametrize("base,exact_average", [("sgd_nesterov", True), ("adam", True),
+                                                ("sgd_nesterov", False)])
+def test_per_tensor_hyperparameters_every_element(base, exact_average):
+    """Parameter groups: every tensor its own weight decay and learning-rate
+    scale (e.g. no decay on the small vectors, smaller steps on some)."""
+    w0 = W.ragged_mini(base=base)
+    nt = len(w0.numel)
+    wd = tuple(0.0 if n < 300 else 1e-4 * (1 + j % 3) for j, n in enumerate(w0.numel))
+    sc = tuple((1.0, 0.5, 0.1, 2.0, 0.3)[j % 5] for j in range(nt))
+    w = dataclasses.replace(w0, tensor_wd=wd, tensor_lr_scale=sc, exact_average=exact_average)
+    prob = _problem(w, ring=2, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"))
+    import paper_1910_00643_amd as P
+    for bad in (dict(weight_decay=[-1.0] * nt), dict(lr_scale=[0.0] * nt),
+                dict(lr_scale=[float("nan")] * nt)):
+        with pytest.raises(P.SlowMoError):
+            opt.set_tensor_hparams(**bad)
+    opt.close()
+
+
+@pytest.mark.parametrize("base,policy,exact_average", [("sgd_nesterov", "reset", True),
+                                                       ("adam", "maintain", True),
+                                                       ("sgd_nesterov", "maintain", False)])
+def test_export_import_resumes_bit_for_bit(base, policy, exact_average):
+    """Stop inside an outer iteration, export the state, rebuild everything
+    from the saved bytes in a new context, continue: same bits as the
+    uninterrupted run (and within tolerance of the oracle)."""
+    import torch
+    import paper_1910_00643_amd as P
+    w = dataclasses.replace(W.ragged_mini(base=base, policy=policy), exact_average=exact_average)
+    idx = np.arange(w.d, dtype=np.int64)
+    stop = 2 * w.tau + 2                    # two rounds and two local steps
+    total = w.rounds * w.tau
+
+    def advance(prob, opt, first, last):
+        for step in range(first, last):
+            prob.fill_grads(0, step)
+            opt.local_step(prob.grads[0], w.lr)
+            if (step + 1) % w.tau == 0:
+                opt.outer_step(w.lr)
+
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    advance(prob, opt, 0, stop)
+    blob = opt.export_state().cpu()         # as a checkpoint file would hold it
+    saved = [[t.clone() for t in p] for p in prob.params]
+    assert opt.counters()[:2] == (2, 2)
+    advance(prob, opt, stop, total)
+    want = PU.gpu_state(w, prob, opt, idx)
+    opt.close()
+
+    prob2 = _problem(w, grad_layout="separate")
+    opt2 = PU.make_gpu(w, prob2)
+    for p, q in zip(prob2.params, saved):   # replicas are restored after create
+        for a, b in zip(p, q):
+            a.copy_(b)
+    opt2.import_state(blob.cuda())
+    assert opt2.counters() == (2, 2, 2 * w.tau + 2 if base == "adam" else opt2.counters()[2])
+    advance(prob2, opt2, stop, total)
+    got = PU.gpu_state(w, prob2, opt2, idx)
+    for key in ("x", "x0", "u", "h"):
+        assert np.array_equal(got[key], want[key]), key
+    o64, _ = PU.run_oracle(w, idx, w.rounds)
+    PU.assert_params_close(got["x0"], o64.x0, "x0 after resume")
+    # a blob from another configuration is refused
+    w3 = dataclasses.replace(w, m=w.m + 1)
+    prob3 = _problem(w3, grad_layout="separate")
+    opt3 = PU.make_gpu(w3, prob3)
+    with pytest.raises(P.SlowMoError):
+        opt3.import_state(torch.zeros(P.slowmo_export_bytes(opt3.ctx), dtype=torch.uint8, device="cuda:0"))
+    with pytest.raises(P.SlowMoError):
+        opt3.import_state(blob.cuda())
+    opt2.close()
+    opt3.close()
+
+
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
