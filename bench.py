@@ -53,13 +53,32 @@ def outer_bytes_per_element(w) -> int:
     return b
 
 
-def round_bytes(w) -> int:
+def fused_bytes_per_element(w) -> int:
+    """Last local step + outer step in one kernel: per worker x, h (and v), g
+    read and x written; x0, u read and written; the buffers written once per
+    worker unless the policy discards them."""
+    g = 2 if w.grad_dtype == "bf16" else 4
+    nbuf = 2 if w.base == "adam" else 1
+    first = w.policy == "reset" and w.tau == 1
+    reads = w.m * (4 + (0 if first else 4 * nbuf) + g) + 8
+    writes = 4 * w.m + 8 + (0 if w.policy == "reset" else 4 * nbuf * w.m)
+    return reads + writes
+
+
+def fusable(w) -> bool:
+    return w.exact_average and w.mix == "none"
+
+
+def round_bytes(w, fused: bool = False) -> int:
+    """Algorithmic HBM bytes of one outer iteration as it is executed."""
     reset = w.policy == "reset"
+    steps = range(w.tau - 1) if fused else range(w.tau)
     per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0, reset and k == w.tau - 1)
-                          for k in range(w.tau))
+                          for k in steps)
     if w.mix == "expgraph":     # every replica read and written once per gossip step
         per_worker_elem += 8 * w.tau
-    return w.d * (w.m * per_worker_elem + outer_bytes_per_element(w))
+    tail = fused_bytes_per_element(w) if fused else outer_bytes_per_element(w)
+    return w.d * (w.m * per_worker_elem + tail)
 
 
 def build_problem(w, ring):
@@ -81,7 +100,7 @@ def build_problem(w, ring):
     return prob, opt
 
 
-def run_rounds(w, opt, arrays, rounds, events=None):
+def run_rounds(w, opt, arrays, rounds, events=None, fused=False):
     """`rounds` outer iterations.  With `events`, brackets every call with HIP
     events on the stream the kernels are launched on (torch's current one)."""
     import torch
@@ -90,6 +109,15 @@ def run_rounds(w, opt, arrays, rounds, events=None):
     peers = [P.slowmo_expgraph_in_peers(w.m, s) for s in range(16)] if w.mix == "expgraph" else None
     for _ in range(rounds):
         for k in range(w.tau):
+            if fused and k == w.tau - 1:        # last local step + outer step, one call
+                if events is not None:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                opt.local_outer_step(arrays[k % ring], w.lr)
+                if events is not None:
+                    b.record()
+                    events["fused_last_outer"].append((a, b))
+                break
             if events is not None:
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
@@ -108,29 +136,31 @@ def run_rounds(w, opt, arrays, rounds, events=None):
                 if events is not None:
                     b.record()
                     events["mix"].append((a, b))
-        if events is not None:
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-        opt.outer_step(w.lr)
-        if events is not None:
-            b.record()
-            events["outer"].append((a, b))
+        else:
+            if events is not None:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            opt.outer_step(w.lr)
+            if events is not None:
+                b.record()
+                events["outer"].append((a, b))
 
 
-def time_workload(w, steps, warmup, ring=None):
+def time_workload(w, steps, warmup, ring=None, fused=False):
     import torch
     ring = ring or w.tau
     prob, opt = build_problem(w, ring)
     arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(ring)]
-    run_rounds(w, opt, arrays, warmup)
+    run_rounds(w, opt, arrays, warmup, fused=fused)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_rounds(w, opt, arrays, steps)
+    run_rounds(w, opt, arrays, steps, fused=fused)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     # second pass: per-kernel durations from HIP events around every launch
-    events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": []}
-    run_rounds(w, opt, arrays, steps, events)
+    events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": [],
+              "fused_last_outer": []}
+    run_rounds(w, opt, arrays, steps, events, fused=fused)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
                for k, v in events.items()}
@@ -198,6 +228,9 @@ def main():
                          "exponential graph after every local step")
     ap.add_argument("--no-average", action="store_true",
                     help="the variant without the exact average (Section 6 of the paper)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="end every outer iteration with slowmo_local_step + slowmo_outer_step "
+                         "instead of the single call slowmo_local_outer_step (same results)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (a kernel of known "
@@ -229,7 +262,8 @@ def main():
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
-    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring)
+    fused = fusable(w) and not args.unfused
+    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring, fused=fused)
     ms_per_step = 1e3 * wall / args.steps
     value = w.updates_per_round * args.steps / wall
     local_bytes = local_bytes_per_update(w, False) * w.m * w.d
@@ -244,10 +278,13 @@ def main():
                                f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}"
                                + ("" if w.exact_average else ", no exact average")
                                + ("" if w.mix == "none" else f", gossip={w.mix}"),
-                   "step": "one outer iteration: tau local steps on all m workers + outer step",
+                   "step": "one outer iteration: tau local steps on all m workers + outer step"
+                           + (" (the last local step and the outer step as one fused call)"
+                              if fused else ""),
                    "gradient_sets_resident": ring},
-        "hbm_gbps_whole_round": round_bytes(w) / wall * args.steps / 1e9,
-        "hbm_frac_whole_round": round_bytes(w) / wall * args.steps / 1e9 / HBM_PEAK_GBPS,
+        "hbm_gbps_whole_round": round_bytes(w, fused) / wall * args.steps / 1e9,
+        "hbm_frac_whole_round": round_bytes(w, fused) / wall * args.steps / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_round": round_bytes(w, fused),
         "kernel_ms": kern_ms,
         "roofline": {"bound": "hbm", "kernel": "k_local_step (steady state)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -255,11 +292,17 @@ def main():
                      "algorithmic_bytes_per_launch": local_bytes,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
-    if kern_ms["outer"]:
+    if kern_ms.get("outer"):
         ob = outer_bytes_per_element(w) * w.d
         out["outer_kernel"] = {"achieved": ob / (kern_ms["outer"] * 1e-3) / 1e9, "unit": "GB/s",
                                "frac": ob / (kern_ms["outer"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                "algorithmic_bytes_per_launch": ob}
+    if kern_ms.get("fused_last_outer"):
+        fb = fused_bytes_per_element(w) * w.d
+        ms = kern_ms["fused_last_outer"]
+        out["fused_last_outer_kernel"] = {"achieved": fb / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                                          "frac": fb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                          "algorithmic_bytes_per_launch": fb}
     if kern_ms.get("mix"):
         mb = 8 * w.m * w.d
         out["mix_kernel"] = {"achieved": mb / (kern_ms["mix"] * 1e-3) / 1e9, "unit": "GB/s",

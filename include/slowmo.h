@@ -146,6 +146,23 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
 slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream);
 
 /*
+ * The last local step of an outer iteration and the outer step as one call:
+ * the same results, bit for bit, as
+ *     slowmo_local_step(ctx, grads, lr, stream);
+ *     slowmo_outer_step(ctx, outer_lr, stream);
+ * but when cfg.no_average is 0 and every replica and gradient pointer is
+ * 16-byte aligned (8 bytes for bf16 gradients) both run in ONE kernel that
+ * keeps the stepped replicas in registers for the average: the replicas are
+ * read and written once instead of twice (8 m bytes less traffic per element),
+ * and the per-worker buffers of this step are not written under the RESET and
+ * AVERAGE policies.  Otherwise the two kernels are launched back to back.
+ * Errors: as for the two calls; STATE unless exactly tau-1 local steps were
+ * taken since the previous outer step.
+ */
+slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                      float outer_lr, void *stream);
+
+/*
  * One mixing (gossip) step of stochastic gradient push among the m logical
  * workers: Algorithm C.1, "send / receive / update model parameters", i.e.
  * X <- X P^T of Appendix C.1, for the case the paper runs: every worker sends

@@ -31,7 +31,7 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_destroy", "slowmo_last_error", "slowmo_get_buffer", "slowmo_get_counters",
            "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version", "slowmo_mix_step",
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
-           "slowmo_export_state", "slowmo_import_state"]
+           "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step"]
 
 
 class slowmo_config(C.Structure):
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
     L.slowmo_create.restype = C.c_int
     L.slowmo_local_step.argtypes = [vp, C.POINTER(vp), C.c_float, vp]
     L.slowmo_local_step.restype = C.c_int
+    L.slowmo_local_outer_step.argtypes = [vp, C.POINTER(vp), C.c_float, C.c_float, vp]
+    L.slowmo_local_outer_step.restype = C.c_int
     L.slowmo_outer_step.argtypes = [vp, C.c_float, vp]
     L.slowmo_outer_step.restype = C.c_int
     L.slowmo_destroy.argtypes = [vp]
@@ -155,6 +157,13 @@ def slowmo_local_step(ctx, grads, lr: float, stream: int = 0) -> None:
     """grads: m * n_tensors device addresses, or a prepared ctypes array."""
     arr = grads if (grads is None or isinstance(grads, C.Array)) else _ptr_array(grads)
     _check(lib().slowmo_local_step(ctx, arr, lr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_local_outer_step(ctx, grads, lr: float, outer_lr: float, stream: int = 0) -> None:
+    """The last local step of an outer iteration and the outer step in one call."""
+    arr = grads if (grads is None or isinstance(grads, C.Array)) else _ptr_array(grads)
+    _check(lib().slowmo_local_outer_step(ctx, arr, lr, outer_lr,
+                                         C.c_void_p(stream) if stream else None), ctx)
 
 
 def slowmo_outer_step(ctx, lr: float, stream: int = 0) -> None:

@@ -181,6 +181,7 @@ struct slowmo_ctx {
   int32_t k = 0;  // local steps in the current outer iteration
   int64_t l = 0;  // Adam steps counted by the bias correction
   bool buffers_zero = true;  // h (and v) are to be read as zero by the next local step
+  bool params_aligned = true;  // every replica pointer is 16-byte aligned
 
   LaunchTuning tune{};
   std::string err;
@@ -297,6 +298,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->layout = make_layout(n_tensors, numel);
   ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
   ctx->tune.nontemporal = env_flag("SLOWMO_NT", 1) ? 1 : 0;
+  ctx->tune.fuse_last = env_flag("SLOWMO_FUSE_LAST", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
@@ -356,14 +358,17 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   slots.resize(n_ptr);
   tinfo.resize(n_tensors);
   std::vector<float *> xtab_t(n_ptr);
-  for (int32_t j = 0; j < n_tensors; ++j) tinfo[j] = {L.arena_off[j], numel[j], 0, 1.0f, 0.f};
+  for (int32_t j = 0; j < n_tensors; ++j) tinfo[j] = {L.arena_off[j], numel[j], 0, 1.0f, cfg->weight_decay};
   for (int32_t w = 0; w < m; ++w) {
     for (int32_t j = 0; j < n_tensors; ++j) {
       const size_t slot = static_cast<size_t>(w) * n_tensors + j;
       slots[slot] = {params[slot], static_cast<int64_t>(w) * L.d_pad + L.arena_off[j], numel[j],
                      cfg->weight_decay, 1.0f};
       xtab_t[static_cast<size_t>(j) * m + w] = params[slot];
-      if (reinterpret_cast<uintptr_t>(params[slot]) & 15) tinfo[j].unaligned = 1;
+      if (numel[j] && (reinterpret_cast<uintptr_t>(params[slot]) & 15)) {
+        tinfo[j].unaligned = 1;
+        ctx->params_aligned = false;
+      }
     }
   }
   // tiles in launch order: worker-major, tensors in list order, pieces ascending
@@ -424,9 +429,13 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   return SLOWMO_OK;
 }
 
-slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float lr,
-                                void *stream_) {
-  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+namespace {
+
+// Checks the arguments of a local step, uploads the gradient-pointer table if
+// it changed and fills the kernel arguments.  *all_aligned tells whether every
+// gradient pointer allows 16-byte vector loads.
+slowmo_status prepare_local(slowmo_ctx *ctx, const void *const *grads, float lr,
+                            hipStream_t stream, LocalArgs *out, bool *all_aligned) {
   if (!grads) return fail(ctx, SLOWMO_ERR_ARG, "grads is NULL");
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k >= ctx->cfg.tau)
@@ -434,13 +443,15 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   const slowmo_config &c = ctx->cfg;
   const size_t n_ptr = static_cast<size_t>(c.m) * ctx->n_tensors;
   const size_t gsize = c.grad_dtype == SLOWMO_BF16 ? 2 : 4;
+  uintptr_t low_bits = 0;
   for (size_t i = 0; i < n_ptr; ++i) {
     if (ctx->numel[i % ctx->n_tensors] == 0) continue;
     if (!grads[i]) return fail(ctx, SLOWMO_ERR_ARG, "a gradient pointer is NULL");
     if (reinterpret_cast<uintptr_t>(grads[i]) % gsize)
       return fail(ctx, SLOWMO_ERR_ALIGN, "a gradient pointer is not aligned to its element size");
+    low_bits |= reinterpret_cast<uintptr_t>(grads[i]);
   }
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  *all_aligned = (low_bits & (4 * gsize - 1)) == 0;
 
   // gradient-pointer table: reuse the uploaded one if the pointers did not change
   int slot = ctx->gtab.cur;
@@ -463,55 +474,61 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   a.lr = lr;
   a.wd = c.weight_decay;
   a.mu = c.momentum;
-  const int64_t l_next = ctx->l + 1;
   if (c.base == SLOWMO_ADAM) {
+    const double l_next = static_cast<double>(ctx->l + 1);
     a.b1 = c.beta1;
     a.b2 = c.beta2;
     a.omb1 = 1.0f - c.beta1;
     a.omb2 = 1.0f - c.beta2;
     a.eps = c.eps;
     // 1 / (1 - beta^l), l counting this step, in fp64, rounded once
-    a.rc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta1), static_cast<double>(l_next))));
-    a.rc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta2), static_cast<double>(l_next))));
+    a.rc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta1), l_next)));
+    a.rc2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.beta2), l_next)));
   }
+  *out = a;
+  return SLOWMO_OK;
+}
+
+void finish_local(slowmo_ctx *ctx) {
+  ctx->k += 1;
+  ctx->l += 1;
+  ctx->buffers_zero = false;
+}
+
+void finish_outer(slowmo_ctx *ctx) {
+  ctx->k = 0;
+  ctx->t += 1;
+  if (ctx->cfg.policy == SLOWMO_BUF_RESET) {  // Algorithm 1 line 2 of the next outer iteration
+    ctx->buffers_zero = true;
+    ctx->l = 0;
+  }
+}
+
+}  // namespace
+
+slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  LocalArgs a{};
+  bool aligned = false;
+  slowmo_status st = prepare_local(ctx, grads, lr, stream, &a, &aligned);
+  if (st != SLOWMO_OK) return st;
+  const slowmo_config &c = ctx->cfg;
   // Under the reset policy the buffers written by the last step of an outer
   // iteration are discarded before they are read again: skip those stores.
   const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
   hipError_t e = launch_local_step(a, c.base, c.grad_dtype == SLOWMO_BF16, ctx->buffers_zero,
                                    dead_after, ctx->tune, stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-  ctx->k += 1;
-  ctx->l = l_next;
-  ctx->buffers_zero = false;
+  finish_local(ctx);
   return SLOWMO_OK;
 }
 
-slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
-  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
-  if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
-  if (ctx->k != ctx->cfg.tau)
-    return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
+namespace {
+
+OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
   const slowmo_config &c = ctx->cfg;
-  if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
-    OuterNoAvgArgs na{};
-    na.tiles = ctx->d_ltiles;
-    na.slots = ctx->d_slots;
-    na.ntiles = ctx->n_ltiles;
-    na.x0 = ctx->x0;
-    na.u = ctx->u;
-    na.lr = lr;
-    na.alpha = c.alpha;
-    na.beta = c.beta;
-    hipError_t e = launch_outer_noavg_step(na, ctx->tune, static_cast<hipStream_t>(stream_));
-    if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
-    ctx->k = 0;
-    ctx->t += 1;
-    if (c.policy == SLOWMO_BUF_RESET) {
-      ctx->buffers_zero = true;
-      ctx->l = 0;
-    }
-    return SLOWMO_OK;
-  }
   OuterArgs a{};
   a.tiles = ctx->d_otiles;
   a.tensors = ctx->d_tensors;
@@ -524,19 +541,72 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   a.alpha = c.alpha;
   a.beta = c.beta;
   a.m_f = static_cast<float>(c.m);
+  a.d_pad = ctx->layout.d_pad;
   if (c.policy == SLOWMO_BUF_AVERAGE) {  // Algorithm 1 line 2 of the next outer iteration
     a.avg_h = ctx->h;
     a.avg_v = ctx->v;  // nullptr unless Adam
-    a.d_pad = ctx->layout.d_pad;
   }
-  hipError_t e = launch_outer_step(a, ctx->tune, static_cast<hipStream_t>(stream_));
+  return a;
+}
+
+hipError_t launch_outer_any(const slowmo_ctx *ctx, float lr, hipStream_t stream) {
+  const slowmo_config &c = ctx->cfg;
+  if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
+    OuterNoAvgArgs na{};
+    na.tiles = ctx->d_ltiles;
+    na.slots = ctx->d_slots;
+    na.ntiles = ctx->n_ltiles;
+    na.x0 = ctx->x0;
+    na.u = ctx->u;
+    na.lr = lr;
+    na.alpha = c.alpha;
+    na.beta = c.beta;
+    return launch_outer_noavg_step(na, ctx->tune, stream);
+  }
+  return launch_outer_step(outer_args(ctx, lr), ctx->tune, stream);
+}
+
+}  // namespace
+
+slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
+  if (ctx->k != ctx->cfg.tau)
+    return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
+  hipError_t e = launch_outer_any(ctx, lr, static_cast<hipStream_t>(stream_));
   if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
-  ctx->k = 0;
-  ctx->t += 1;
-  if (c.policy == SLOWMO_BUF_RESET) {  // Algorithm 1 line 2 of the next outer iteration
-    ctx->buffers_zero = true;
-    ctx->l = 0;
+  finish_outer(ctx);
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                      float outer_lr, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!finite_pos(outer_lr)) return fail(ctx, SLOWMO_ERR_ARG, "outer_lr must be finite and > 0");
+  if (ctx->k != ctx->cfg.tau - 1)
+    return fail(ctx, SLOWMO_ERR_STATE,
+                "the fused step is the LAST local step of an outer iteration: tau-1 local steps "
+                "must have been taken");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  LocalArgs a{};
+  bool aligned = false;
+  slowmo_status st = prepare_local(ctx, grads, lr, stream, &a, &aligned);
+  if (st != SLOWMO_OK) return st;
+  const slowmo_config &c = ctx->cfg;
+  const bool bf16 = c.grad_dtype == SLOWMO_BF16;
+  hipError_t e;
+  if (c.no_average || !aligned || !ctx->params_aligned || !ctx->tune.fuse_last) {
+    // same two kernels as the separate calls
+    e = launch_local_step(a, c.base, bf16, ctx->buffers_zero, c.policy == SLOWMO_BUF_RESET,
+                          ctx->tune, stream);
+    if (e == hipSuccess) e = launch_outer_any(ctx, outer_lr, stream);
+  } else {
+    e = launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
+                                ctx->buffers_zero, c.policy, ctx->tune, stream);
   }
+  if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
+  finish_local(ctx);
+  finish_outer(ctx);
   return SLOWMO_OK;
 }
 
@@ -607,6 +677,7 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
   }
   for (int32_t j = 0; j < nt; ++j) {
     if (lr_scale) ctx->tinfo[j].lr_scale = lr_scale[j];
+    if (weight_decay) ctx->tinfo[j].wd = weight_decay[j];
     for (int32_t w = 0; w < m; ++w) {
       SlotInfo &s = ctx->slots[static_cast<size_t>(w) * nt + j];
       if (weight_decay) s.wd = weight_decay[j];

@@ -69,6 +69,7 @@ struct MixArgs {
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
+  int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
   int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
                         // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
@@ -79,6 +80,14 @@ struct LaunchTuning {
 hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+// The last local step of an outer iteration and the outer step in one pass
+// (one workgroup = 256 elements of one tensor, all workers).  Requires every
+// replica and gradient pointer to be 16-byte aligned (8 for bf16).  policy:
+// 0 reset (buffers not stored), 1 maintain (stored), 2 average (their mean
+// over the workers is stored).
+hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                   int base, bool bf16, bool first, int policy,
+                                   const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
                                    hipStream_t stream);

@@ -373,6 +373,140 @@ __global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
   }
 }
 
+// ---- last local step + outer step, fused ---------------------------------------
+// For one tile (256 elements of one tensor): for every worker in order, the
+// base-optimizer step on that worker's (x, h[, v], g) -- the same arithmetic
+// as k_local_step -- with the new x kept in registers and added to the ordered
+// sum; then lines 6-8 and the write of x_{t+1,0} into all replicas.  The
+// replicas are read once and written once (the unfused pair writes and
+// re-reads them), and under "reset" / "average" the per-worker buffers of this
+// step are never written.
+template <int BASE, bool BF16, bool FIRST, int POLICY, bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
+    float *__restrict__ x0base, float *__restrict__ ubase, float *__restrict__ hbase,
+    float *__restrict__ vbase, int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap,
+    int m, SgdP sp, AdamP ap, OuterP p0) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
+  sp.lr = sp.lr * ti.lr_scale;
+  sp.wd = ti.wd;
+  ap.lr = ap.lr * ti.lr_scale;
+  ap.wd = ti.wd;
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const void *const *__restrict__ gp = gtab + t.owner;       // worker i: gp[i * n_tensors]
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
+  float *h0 = hbase + ti.fo + eo;                              // worker i: h0 + i * d_pad
+  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
+  constexpr int gsize = BF16 ? 2 : 4;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (e0 + 4 <= n) {
+    V4 acc, acch, accv;
+#pragma unroll 4
+    for (int i = 0; i < m; ++i) {
+      float *xi = xp[i] + eo + e0;
+      float *hi = h0 + i * d_pad + e0;
+      float *vi = BASE == 1 ? v0 + i * d_pad + e0 : nullptr;
+      const void *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
+      V4 xv = ld4<NT>(xi), hv, vv;
+      if constexpr (!FIRST) hv = ld4<NT>(hi);
+      if constexpr (!FIRST && BASE == 1) vv = ld4<NT>(vi);
+      V4 gv = ldg4<BF16, NT>(gi, threadIdx.x);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float xe = xv[c], he = FIRST ? 0.f : hv[c];
+        if constexpr (BASE == 0) {
+          sgd_elem<FIRST>(xe, he, gv[c], sp);
+        } else {
+          float ve = FIRST ? 0.f : vv[c];
+          adam_elem<FIRST>(xe, he, ve, gv[c], ap);
+          vv[c] = ve;
+        }
+        xv[c] = xe;
+        hv[c] = he;
+      }
+      if constexpr (POLICY == 1) {
+        st4<NT>(hi, hv);
+        if constexpr (BASE == 1) st4<NT>(vi, vv);
+      }
+      if constexpr (POLICY == 2) {
+        acch = (i == 0) ? hv : acch + hv;
+        if constexpr (BASE == 1) accv = (i == 0) ? vv : accv + vv;
+      }
+      acc = (i == 0) ? xv : acc + xv;
+    }
+    V4 x0v = ld4<NT>(x0 + e0), uv = ld4<NT>(u + e0), xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<NT>(u + e0, uv);
+    st4<NT>(x0 + e0, xn);
+#pragma unroll 8
+    for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
+    if constexpr (POLICY == 2) {
+      V4 mh, mv;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        mh[c] = acch[c] / p.m_f;
+        if constexpr (BASE == 1) mv[c] = accv[c] / p.m_f;
+      }
+#pragma unroll 8
+      for (int i = 0; i < m; ++i) {
+        st4<NT>(h0 + i * d_pad + e0, mh);
+        if constexpr (BASE == 1) st4<NT>(v0 + i * d_pad + e0, mv);
+      }
+    }
+  } else {
+    for (int j = e0; j < n; ++j) {        // ragged tail of the tensor
+      float s = 0.f, sh = 0.f, sv = 0.f;
+      for (int i = 0; i < m; ++i) {
+        float *xi = xp[i] + eo + j;
+        float *hi = h0 + i * d_pad + j;
+        float *vi = BASE == 1 ? v0 + i * d_pad + j : nullptr;
+        const void *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
+        float xe = ld1(xi), he = FIRST ? 0.f : ld1(hi), ve = 0.f;
+        float ge = ldg1<BF16>(gi, j);
+        if constexpr (BASE == 0) {
+          sgd_elem<FIRST>(xe, he, ge, sp);
+        } else {
+          ve = FIRST ? 0.f : ld1(vi);
+          adam_elem<FIRST>(xe, he, ve, ge, ap);
+        }
+        if constexpr (POLICY == 1) {
+          st1(hi, he);
+          if constexpr (BASE == 1) st1(vi, ve);
+        }
+        sh = (i == 0) ? he : sh + he;
+        sv = (i == 0) ? ve : sv + ve;
+        s = (i == 0) ? xe : s + xe;
+      }
+      float ue = ld1(u + j);
+      float xn = outer_elem(s, ld1(x0 + j), ue, p);
+      st1(u + j, ue);
+      st1(x0 + j, xn);
+      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
+      if constexpr (POLICY == 2) {
+        for (int i = 0; i < m; ++i) {
+          st1(h0 + i * d_pad + j, sh / p.m_f);
+          if constexpr (BASE == 1) st1(v0 + i * d_pad + j, sv / p.m_f);
+        }
+      }
+    }
+  }
+}
+
 // ---- mixing step of stochastic gradient push (Algorithm C.1) ---------------------
 // x^{(i)} <- (x^{(i)} + x^{(in_peer(i))}) / 2 for a permutation in_peer, in
 // place.  The workers are visited cycle by cycle in the order "receiver, then
@@ -520,6 +654,58 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   }
   return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
                   : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
+}
+
+namespace {
+
+template <int BASE, bool BF16, bool FIRST, int POLICY>
+hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
+                          const LaunchTuning &t, hipStream_t s) {
+  const Grid g = make_grid(o.ntiles, t.xcd_remap);
+  const SgdP sp{l.lr, l.mu, l.wd};
+  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
+  const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, t.xcd_remap, o.m, sp, ap, p);
+  } else {
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, t.xcd_remap, o.m, sp, ap, p);
+  }
+  return hipGetLastError();
+}
+
+template <int BASE, bool BF16, bool FIRST>
+hipError_t launch_fused_p(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
+                          const LaunchTuning &t, hipStream_t s) {
+  switch (policy) {
+    case 0: return launch_fused_t<BASE, BF16, FIRST, 0>(l, o, n_tensors, t, s);
+    case 1: return launch_fused_t<BASE, BF16, FIRST, 1>(l, o, n_tensors, t, s);
+    default: return launch_fused_t<BASE, BF16, FIRST, 2>(l, o, n_tensors, t, s);
+  }
+}
+
+template <int BASE, bool BF16>
+hipError_t launch_fused_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
+                          int policy, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_fused_p<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
+               : launch_fused_p<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
+}
+
+}  // namespace
+
+hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                   int base, bool bf16, bool first, int policy,
+                                   const LaunchTuning &t, hipStream_t s) {
+  if (o.ntiles <= 0) return hipSuccess;
+  if (base == 0) {
+    return bf16 ? launch_fused_f<0, true>(l, o, n_tensors, first, policy, t, s)
+                : launch_fused_f<0, false>(l, o, n_tensors, first, policy, t, s);
+  }
+  return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, t, s)
+              : launch_fused_f<1, false>(l, o, n_tensors, first, policy, t, s);
 }
 
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {

@@ -56,7 +56,7 @@ struct TensorInfo {
   int64_t numel;
   int64_t unaligned;  // non-zero: some replica of this tensor is not 16-byte aligned
   float lr_scale;     // the tensor's fast learning rate is lr * lr_scale
-  float pad_;
+  float wd;           // weight decay of this tensor
 };
 static_assert(sizeof(TensorInfo) == 32, "TensorInfo layout");
 

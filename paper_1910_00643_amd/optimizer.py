@@ -74,6 +74,12 @@ class SlowMo:
         arr = grads if isinstance(grads, C.Array) else self.grad_pointer_array(grads)
         B.slowmo_local_step(self.ctx, arr, lr, torch.cuda.current_stream(self.device).cuda_stream)
 
+    def local_outer_step(self, grads, lr: float, outer_lr: Optional[float] = None) -> None:
+        """Last local step of the outer iteration + outer step (fused when possible)."""
+        arr = grads if isinstance(grads, C.Array) else self.grad_pointer_array(grads)
+        B.slowmo_local_outer_step(self.ctx, arr, lr, lr if outer_lr is None else outer_lr,
+                                  torch.cuda.current_stream(self.device).cuda_stream)
+
     def mix_step(self, in_peer: Sequence[int]) -> None:
         B.slowmo_mix_step(self.ctx, in_peer, torch.cuda.current_stream(self.device).cuda_stream)
 

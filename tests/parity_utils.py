@@ -115,7 +115,7 @@ def make_gpu(w, prob):
     return opt
 
 
-def run_gpu(w, prob, opt, rounds, index):
+def run_gpu(w, prob, opt, rounds, index, fused_last=False):
     """Runs `rounds` outer iterations; gradients are regenerated before every
     local step (ring slots in turn).  Returns the snapshot (x, h, v at the
     sampled indices) taken after the local steps of the last round."""
@@ -128,6 +128,10 @@ def run_gpu(w, prob, opt, rounds, index):
         for k in range(w.tau):
             s = step % prob.ring
             prob.fill_grads(s, step)
+            if fused_last and k == w.tau - 1 and not (t == rounds - 1):
+                opt.local_outer_step(arrays[s], lr)     # last local step + outer step
+                step += 1
+                continue
             opt.local_step(arrays[s], lr)
             if w.mix == "expgraph":
                 import paper_1910_00643_amd as P
@@ -138,7 +142,9 @@ def run_gpu(w, prob, opt, rounds, index):
                 snap.update(h=st["h"], v=st["v"])
         if t == rounds - 1:
             snap.update(x=gpu_state(w, prob, opt, index, with_outer=False)["x"])
-        opt.outer_step(lr)
+            opt.outer_step(lr)
+        elif not fused_last:
+            opt.outer_step(lr)
     return snap
 
 
@@ -162,10 +168,12 @@ def gpu_state(w, prob, opt, index, with_outer=True):
     return out
 
 
-def compare_run(w, prob, opt, index, rounds, bitwise_f32=False):
-    """Full comparison of a finished GPU run against the oracle on `index`."""
+def compare_run(w, prob, opt, index, rounds, bitwise_f32=False, fused_last=False):
+    """Full comparison of a finished GPU run against the oracle on `index`.
+    With fused_last, every outer iteration but the final one (whose replicas
+    are inspected before the outer step) ends with slowmo_local_outer_step."""
     lr = w.f32("lr")
-    snap = run_gpu(w, prob, opt, rounds, index)
+    snap = run_gpu(w, prob, opt, rounds, index, fused_last=fused_last)
     final = gpu_state(w, prob, opt, index)
     res = run_oracles(w, index, rounds, ("f64", "f32") if bitwise_f32 else ("f64",))
     o64, s64 = res["f64"]

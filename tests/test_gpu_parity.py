@@ -237,6 +237,46 @@ def test_export_import_resumes_bit_for_bit(base, policy, exact_average):
     opt3.close()
 
 
+@pytest.mark.parametrize("base,grad_dtype,policy,tau,layouts", [
+    ("sgd_nesterov", "f32", "reset", 5, ("separate", "padded")),
+    ("sgd_nesterov", "bf16", "maintain", 5, ("separate", "separate")),
+    ("sgd_nesterov", "f32", "average", 5, ("separate", "padded")),
+    ("sgd_nesterov", "f32", "reset", 1, ("separate", "separate")),     # first step is also the last
+    ("adam", "bf16", "maintain", 5, ("separate", "padded")),
+    ("adam", "f32", "reset", 3, ("separate", "separate")),
+    ("adam", "bf16", "average", 4, ("separate", "padded")),
+    ("sgd_nesterov", "f32", "reset", 5, ("flat", "flat")),             # unaligned: two kernels
+])
+def test_fused_last_local_and_outer_step(base, grad_dtype, policy, tau, layouts):
+    """slowmo_local_outer_step == slowmo_local_step + slowmo_outer_step, bit
+    for bit, and within tolerance of the oracle."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy=policy), tau=tau,
+                            tensor_wd=tuple(1e-4 * (j % 3) for j in range(26)),
+                            tensor_lr_scale=tuple((1.0, 0.5, 2.0)[j % 3] for j in range(26)))
+    idx = np.arange(w.d, dtype=np.int64)
+    res = []
+    for fused in (False, True):
+        prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
+        opt = PU.make_gpu(w, prob)
+        PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
+                       fused_last=fused)
+        res.append(PU.gpu_state(w, prob, opt, idx))
+        if fused:
+            import paper_1910_00643_amd as P
+            prob.fill_grads(0, 0)
+            if tau > 1:
+                with pytest.raises(P.SlowMoError) as e:     # not the last local step
+                    opt.local_outer_step(prob.grads[0], w.lr)
+                assert e.value.status == P.binding.SLOWMO_ERR_STATE
+        opt.close()
+    for key in ("x", "x0", "u"):
+        assert np.array_equal(res[0][key], res[1][key]), key
+    if policy != "reset":
+        assert np.array_equal(res[0]["h"], res[1]["h"])
+        if base == "adam":
+            assert np.array_equal(res[0]["v"], res[1]["v"])
+
+
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
