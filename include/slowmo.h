@@ -25,6 +25,15 @@
  *    the default stream) and the call returns without synchronizing.  All
  *    calls on one context must be issued on one stream or be ordered by the
  *    caller.  A context is not thread-safe.
+ *  - Graph capture: while the gradient pointers are the same as in the previous
+ *    call, slowmo_local_step, slowmo_outer_step and slowmo_local_outer_step only
+ *    launch kernels (no copies, no synchronization, no memset) and may be recorded
+ *    into a HIP graph.  Kernel arguments are fixed at capture time: the learning
+ *    rates, the first/last-step handling of the RESET policy and Adam's bias
+ *    corrections.  A captured outer iteration of the SGD base therefore replays
+ *    correctly any number of times; one of the Adam base does not (its bias
+ *    correction changes every step).  The context's counters advance when the
+ *    calls are recorded, not when the graph is replayed.
  *  - Errors: every entry point returns a slowmo_status; nothing aborts or
  *    throws.  A call that fails leaves the context's state unchanged.
  *    slowmo_last_error() gives a message for the most recent failure.

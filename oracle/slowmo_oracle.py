@@ -9,8 +9,8 @@ C in slowmo_oracle.c, built in fp64 (the reference) and fp32 (noise floor).
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import
 this module.  It shares no code with the HIP path and does not import it.
 
-Readings of the paper where it is silent or inconsistent (also listed in the
-design document): coupled L2 weight decay; Adam's bias-correction exponent
+Readings of the paper where it is silent or inconsistent: coupled L2 weight
+decay; Adam's bias-correction exponent
 counts the current update (starts at 1); eps is added after the square root of
 the bias-corrected second moment; the learning rate is a per-call scalar (the
 one given to the outer step is gamma_t of Eq. (2)-(3)); the mean is a

@@ -325,6 +325,110 @@ def test_gradient_pointer_table_follows_changing_pointers():
     opt.close()
 
 
+def test_learning_rate_schedule_and_side_stream():
+    """gamma is a per-call scalar (it may follow a schedule inside and across
+    outer iterations, Section 2), and all work goes to the stream handed in:
+    here a non-default stream of default priority."""
+    import torch
+    w = W.ragged_mini()
+    idx = np.arange(w.d, dtype=np.int64)
+    lr_local = lambda step: float(np.float32(0.02 * (1 + step % 4)))        # noqa: E731
+    lr_outer = lambda t: float(np.float32(0.05 / (1 + t)))                  # noqa: E731
+    o = PU.make_oracle(w, idx)
+    o32 = PU.make_oracle(w, idx, "f32")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        prob = _problem(w, grad_layout="separate")
+        opt = PU.make_gpu(w, prob)
+        step = 0
+        for t in range(w.rounds):
+            for k in range(w.tau):
+                prob.fill_grads(0, step)
+                opt.local_step(prob.grads[0], lr_local(step))
+                g = PU.oracle_grads(w, idx, step)
+                o.local_step(g, lr_local(step))
+                o32.local_step(g, lr_local(step))
+                step += 1
+            opt.outer_step(lr_outer(t))
+            o.outer_step(lr_outer(t))
+            o32.outer_step(lr_outer(t))
+        side.synchronize()
+        final = PU.gpu_state(w, prob, opt, idx)
+    PU.assert_params_close(final["x0"], o.x0, "x0 under a schedule")
+    assert np.array_equal(final["x0"], o32.x0) and np.array_equal(final["u"], o32.u)
+    opt.close()
+
+
+def test_two_contexts_side_by_side():
+    """Contexts share nothing: two optimizers over different tensor lists,
+    stepped alternately, give the results each gives alone."""
+    wa = W.ragged_mini()
+    wb = dataclasses.replace(W.ragged_mini(base="adam", grad_dtype="bf16"), m=2)
+    probs = [_problem(wa, grad_layout="separate"), _problem(wb, grad_layout="separate")]
+    opts = [PU.make_gpu(wa, probs[0]), PU.make_gpu(wb, probs[1])]
+    for t in range(2):
+        for k in range(wa.tau):
+            for w, prob, opt in zip((wa, wb), probs, opts):
+                prob.fill_grads(0, t * w.tau + k)
+                opt.local_step(prob.grads[0], w.lr)
+        for w, opt in zip((wa, wb), opts):
+            opt.outer_step(w.lr)
+    for w, prob, opt in zip((wa, wb), probs, opts):
+        idx = np.arange(w.d, dtype=np.int64)
+        o64, _ = PU.run_oracle(w, idx, 2)
+        PU.assert_params_close(PU.gpu_state(w, prob, opt, idx)["x0"], o64.x0, w.name)
+        opt.close()
+
+
+def test_outer_iteration_replayed_from_a_hip_graph():
+    """One whole outer iteration (tau-1 local steps and the fused last step)
+    captured into a HIP graph and replayed.  With unchanged gradient pointers
+    the library only launches kernels (the pointer table is already on the
+    device), and for the SGD base with the reset policy every outer iteration
+    is the same sequence of launches with the same arguments, so each replay
+    must equal one more eager outer iteration, bit for bit.  Replays are
+    separated by eager work and synchronizations."""
+    import torch
+    w = W.ragged_mini()
+    idx = np.arange(w.d, dtype=np.int64)
+
+    def build():
+        prob = _problem(w, ring=1, grad_layout="separate")
+        opt = PU.make_gpu(w, prob)
+        prob.fill_grads(0, 0)                   # one gradient set, used by every step
+        return prob, opt, opt.grad_pointer_array(prob.grads[0])
+
+    def one_round(opt, arr):
+        for k in range(w.tau - 1):
+            opt.local_step(arr, w.lr)
+        opt.local_outer_step(arr, w.lr)
+
+    ref_prob, ref_opt, ref_arr = build()
+    prob, opt, arr = build()
+    one_round(ref_opt, ref_arr)
+    one_round(opt, arr)                         # eager: uploads the pointer table
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=cap):
+        one_round(opt, arr)                     # recorded, not executed
+    torch.cuda.synchronize()
+    assert np.array_equal(PU.gpu_state(w, prob, opt, idx)["x0"],
+                          PU.gpu_state(w, ref_prob, ref_opt, idx)["x0"])
+    for rep in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        one_round(ref_opt, ref_arr)
+        assert np.isfinite(torch.randn(1 << 16, device="cuda:0").sum().item())   # eager work
+        got = PU.gpu_state(w, prob, opt, idx)
+        ref = PU.gpu_state(w, ref_prob, ref_opt, idx)
+        for key in ("x", "x0", "u"):
+            assert np.array_equal(got[key], ref[key]), (rep, key)
+    opt.close()
+    ref_opt.close()
+
+
 def test_call_sequence_errors_leave_state_unchanged():
     import paper_1910_00643_amd as P
     w = dataclasses.replace(W.ragged_mini(), tau=2, rounds=1)
