@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    "resnet50": 16407842445,            # profiles/resnet50_local_step_outer_step.md
-    "transformer_big": 43766508265,     # profiles/transformer_big_local_step_outer_step.md
+    "resnet50": 16407839435,            # profiles/resnet50_local_step_outer_step.md
+    "transformer_big": 43766547581,     # profiles/transformer_big_local_step_outer_step.md
 }
 
 
