@@ -83,7 +83,6 @@ def round_bytes(w, fused: bool = False) -> int:
 
 def build_problem(w, ring):
     import torch
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
     from slowmo_inputs.gpu_problem import GpuProblem
     from paper_1910_00643_amd.optimizer import SlowMo, make_config
     # parameters: one allocation per tensor and worker; gradients: every tensor

@@ -675,23 +675,28 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
     if (lr_scale && !finite_pos(lr_scale[j]))
       return fail(ctx, SLOWMO_ERR_ARG, "lr_scale entries must be finite and > 0");
   }
+  // build the new tables aside; they replace the context's only if the upload succeeds
+  std::vector<SlotInfo> slots = ctx->slots;
+  std::vector<TensorInfo> tinfo = ctx->tinfo;
   for (int32_t j = 0; j < nt; ++j) {
-    if (lr_scale) ctx->tinfo[j].lr_scale = lr_scale[j];
-    if (weight_decay) ctx->tinfo[j].wd = weight_decay[j];
+    if (lr_scale) tinfo[j].lr_scale = lr_scale[j];
+    if (weight_decay) tinfo[j].wd = weight_decay[j];
     for (int32_t w = 0; w < m; ++w) {
-      SlotInfo &s = ctx->slots[static_cast<size_t>(w) * nt + j];
+      SlotInfo &s = slots[static_cast<size_t>(w) * nt + j];
       if (weight_decay) s.wd = weight_decay[j];
       if (lr_scale) s.lr_scale = lr_scale[j];
     }
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  hipError_t e = hipMemcpyAsync(ctx->d_slots, ctx->slots.data(), ctx->slots.size() * sizeof(SlotInfo),
+  hipError_t e = hipMemcpyAsync(ctx->d_slots, slots.data(), slots.size() * sizeof(SlotInfo),
                                 hipMemcpyHostToDevice, stream);
   if (e == hipSuccess)
-    e = hipMemcpyAsync(ctx->d_tensors, ctx->tinfo.data(), ctx->tinfo.size() * sizeof(TensorInfo),
+    e = hipMemcpyAsync(ctx->d_tensors, tinfo.data(), tinfo.size() * sizeof(TensorInfo),
                        hipMemcpyHostToDevice, stream);
-  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the host tables may change again
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the tables above go out of scope
   if (e != hipSuccess) return fail_hip(ctx, e, "upload of the per-tensor hyper-parameters");
+  ctx->slots.swap(slots);
+  ctx->tinfo.swap(tinfo);
   return SLOWMO_OK;
 }
 
