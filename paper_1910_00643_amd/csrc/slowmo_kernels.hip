@@ -1,6 +1,12 @@
 // gfx950 kernels of the Slow Momentum hot path.
 //
-// Both kernels are pure streams: every byte is read once and written once, no
+// k_local_step         Algorithm 1 lines 3-5 for all workers (Table C.1 rows SGD, Adam)
+// k_outer_step         lines 6-8 + copy into every replica (+ "average" buffer strategy)
+// k_local_outer_step   the last local step of an outer iteration fused with the outer step
+// k_outer_noavg        lines 7-8 per worker, without line 6 (Section 6)
+// k_mix_step           mixing step of stochastic gradient push (Algorithm C.1)
+//
+// All of them are pure streams: every byte is read once and written once, no
 // element is reused, so there is no dense contraction and the matrix cores are
 // not involved.  The shape that measured fastest on MI355X for this read/write
 // mix:
@@ -36,8 +42,6 @@ typedef uint32_t U2 __attribute__((ext_vector_type(2)));
 #define SLOWMO_GLOBAL __attribute__((address_space(1)))
 typedef SLOWMO_GLOBAL V4 GV4;
 typedef SLOWMO_GLOBAL U2 GU2;
-typedef SLOWMO_GLOBAL float GF;
-typedef SLOWMO_GLOBAL uint16_t GH;
 
 template <typename T>
 __device__ __forceinline__ SLOWMO_GLOBAL T *as_global(const void *p) {
