@@ -464,7 +464,9 @@ def _sampled(w, rounds, n_random, ring=2, halo=4):
     prob = _problem(w, ring=ring, grad_layout="padded")     # the layout bench.py times
     opt = PU.make_gpu(w, prob)
     idx = prob.sample_indices(n_random, edges=_tile_edges(w), halo=halo, seed=w.seed)
-    worst = PU.compare_run(w, prob, opt, idx, rounds, bitwise_f32=(w.base == "sgd_nesterov"))
+    # as bench.py runs it: outer iterations end with the fused call where that applies
+    worst = PU.compare_run(w, prob, opt, idx, rounds, bitwise_f32=(w.base == "sgd_nesterov"),
+                           fused_last=(w.exact_average and w.mix == "none"))
     print(w.name, "sampled", idx.size, "worst errors", worst)
     opt.close()
 
