@@ -429,6 +429,49 @@ def test_outer_iteration_replayed_from_a_hip_graph():
     ref_opt.close()
 
 
+@pytest.mark.parametrize("seed", list(range(20)))
+def test_random_configurations(seed):
+    """Seeded random draws over everything the library accepts: tensor lists
+    with empty, tiny and multi-tile tensors, worker counts, tau, both base
+    optimizers, gradient dtypes, the three buffer strategies, the variant
+    without the exact average, gossip steps, parameter groups, aligned and
+    packed (unaligned) layouts, separate or fused end of the outer iteration."""
+    rng = np.random.default_rng(1000 + seed)
+    n_t = int(rng.integers(1, 10))
+    sizes = [int(rng.choice([0, 1, 3, 4, 7, 64, 255, 256, 257, 1000, 2049, 5000, 40_001]))
+             for _ in range(n_t)]
+    if sum(sizes) == 0:
+        sizes[0] = 17
+    base = str(rng.choice(["sgd_nesterov", "adam"]))
+    policy = str(rng.choice(["reset", "maintain", "average"]))
+    exact = seed % 4 != 3                   # every fourth draw: no exact average (Section 6)
+    if not exact and policy == "average":
+        policy = "maintain"
+    mix = "expgraph" if (exact and rng.integers(0, 4) == 0) else "none"
+    groups = bool(rng.integers(0, 2))
+    w = Workload = dataclasses.replace(
+        W.ragged_mini(base=base, grad_dtype=str(rng.choice(["f32", "bf16"])), policy=policy,
+                      m=int(rng.integers(1, 7))),
+        shapes=tuple((f"t{j}", (n,)) for j, n in enumerate(sizes)),
+        tau=int(rng.integers(1, 5)), rounds=3, exact_average=exact, mix=mix,
+        alpha=float(rng.choice([0.5, 1.0])), beta=float(rng.choice([0.0, 0.4, 0.8])),
+        tensor_wd=tuple(float(rng.choice([0.0, 1e-4, 1e-3])) for _ in sizes) if groups else None,
+        tensor_lr_scale=tuple(float(rng.choice([1.0, 0.5, 2.0])) for _ in sizes) if groups else None)
+    del Workload
+    layouts = (str(rng.choice(["separate", "flat", "arena"])),
+               str(rng.choice(["separate", "flat", "padded"])))
+    fused = bool(rng.integers(0, 2)) and exact and mix == "none"
+    print("config", seed, dict(sizes=sizes, m=w.m, tau=w.tau, base=base, grads=w.grad_dtype,
+                               policy=policy, exact=exact, mix=mix, groups=groups,
+                               layouts=layouts, fused=fused), flush=True)
+    prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
+                   fused_last=fused)
+    opt.close()
+
+
 def test_call_sequence_errors_leave_state_unchanged():
     import paper_1910_00643_amd as P
     w = dataclasses.replace(W.ragged_mini(), tau=2, rounds=1)
