@@ -415,7 +415,10 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
   if (e0 >= n) return;
   if (e0 + 4 <= n) {
     V4 acc, acch, accv;
-#pragma unroll 4
+#ifndef SLOWMO_FUSED_UNROLL
+#define SLOWMO_FUSED_UNROLL 8
+#endif
+    _Pragma(SLOWMO_STR(unroll SLOWMO_FUSED_UNROLL))
     for (int i = 0; i < m; ++i) {
       float *xi = xp[i] + eo + e0;
       float *hi = h0 + i * d_pad + e0;
