@@ -22,7 +22,8 @@
  *    caller.  The library keeps the parameter pointers and the workspace for
  *    the context's lifetime and never frees them; they must not overlap.
  *  - Streams: work is enqueued on the hipStream_t passed as `stream` (NULL =
- *    the default stream) and the call returns without synchronizing.  All
+ *    the default stream) and the step calls return without synchronizing
+ *    (create, set_tensor_hparams, export and import do wait; they say so).  All
  *    calls on one context must be issued on one stream or be ordered by the
  *    caller.  A context is not thread-safe.
  *  - Graph capture: while the gradient pointers are the same as in the previous
@@ -101,8 +102,8 @@ typedef enum { SLOWMO_BUF_X0 = 0, SLOWMO_BUF_U = 1, SLOWMO_BUF_H = 2, SLOWMO_BUF
 
 /*
  * Bytes of device workspace a context needs for this configuration and
- * tensor list: x0 and u (one copy each), h (and v for Adam) per worker, and
- * the tiling tables.  Returns 0 if the arguments are invalid.  Host-only.
+ * tensor list: x0 and u (one copy each; one per worker with cfg.no_average),
+ * h (and v for Adam) per worker, and the tiling and pointer tables.  Returns 0 if the arguments are invalid.  Host-only.
  */
 size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int64_t *numel);
 
@@ -114,8 +115,10 @@ size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int
  *            slowmo_state_bytes() long; owned by the caller.
  * Effects, enqueued on `stream`: x_{0,0} is taken from worker 0's replica and
  * copied into x0 and into the replicas of workers 1..m-1 (the paper assumes a
- * common starting point; this enforces it); u_0 = 0; h = v = 0.
- * Needs a HIP device.  Errors: ARG, ALIGN, NOMEM, HIP.
+ * common starting point; this enforces it); u_0 = 0; h = v = 0.  Unlike the
+ * step calls, create waits for `stream` before it returns (its tables are
+ * uploaded from temporary host memory).  All argument checks come before the
+ * first use of the device.  Needs a HIP device.  Errors: ARG, ALIGN, NOMEM, HIP.
  */
 slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t n_tensors,
                             const int64_t *numel, float *const *params, void *state,
