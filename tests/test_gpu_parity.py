@@ -472,6 +472,18 @@ def test_random_configurations(seed):
     opt.close()
 
 
+def test_c_abi_from_plain_c_matches_the_closed_form():
+    """tests/abi_c_check (plain C, built by __graft_entry__.build()) drives the
+    library through include/slowmo.h alone and checks Eq. (2)-(3)'s closed form
+    for constant gradients on the GPU."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_c_check")
+    assert os.path.exists(exe), "tests/abi_c_check is not built: run __graft_entry__.build()"
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and run.stdout.startswith("OK"), run.stdout + run.stderr
+
+
 def test_call_sequence_errors_leave_state_unchanged():
     import paper_1910_00643_amd as P
     w = dataclasses.replace(W.ragged_mini(), tau=2, rounds=1)
