@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    "resnet50": 16407839435,            # profiles/resnet50_local_step_outer_step.md
-    "transformer_big": 43766547581,     # profiles/transformer_big_local_step_outer_step.md
+    "resnet50": 16407839291,            # profiles/resnet50_local_step_outer_step.md
+    "transformer_big": 43766503735,     # profiles/transformer_big_local_step_outer_step.md
 }
 
 
@@ -233,6 +233,9 @@ def main():
                     help="end every outer iteration with slowmo_local_step + slowmo_outer_step "
                          "instead of the single call slowmo_local_outer_step (same results)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short extra run of the other target workload "
+                         "(Transformer-big-shaped, reported under 'other_workloads')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (a kernel of known "
                          "traffic for scaling rocprofv3 counters)")
@@ -309,6 +312,26 @@ def main():
         out["mix_kernel"] = {"achieved": mb / (kern_ms["mix"] * 1e-3) / 1e9, "unit": "GB/s",
                              "frac": mb / (kern_ms["mix"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                              "algorithmic_bytes_per_launch": mb}
+    if (not args.no_others and args.workload == "resnet50" and not args.policy
+            and not args.no_average and not args.mix):
+        # the second workload the bandwidth target is stated for, three timed iterations
+        w2 = W.transformer_big()
+        f2 = fusable(w2) and not args.unfused
+        wall2, k2 = time_workload(w2, 3, 1, 16, fused=f2)
+        lb2 = local_bytes_per_update(w2, False) * w2.m * w2.d
+        out["other_workloads"] = [{
+            "workload": f"{w2.name}-shaped tensor list ({len(w2.numel)} tensors, d={w2.d}), "
+                        f"m={w2.m}, tau={w2.tau}, base={w2.base}, grads={w2.grad_dtype}, "
+                        f"policy={w2.policy}",
+            "value": w2.updates_per_round * 3 / wall2, "unit": "updates/s", "steps": 3,
+            "ms_per_step": 1e3 * wall2 / 3,
+            "hbm_frac_whole_round": round_bytes(w2, f2) / wall2 * 3 / 1e9 / HBM_PEAK_GBPS,
+            "roofline": {"bound": "hbm", "kernel": "k_local_step (steady state)",
+                         "achieved": lb2 / (k2["local"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                         "unit": "GB/s", "frac": lb2 / (k2["local"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                         "algorithmic_bytes_per_launch": lb2,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(w2.name)},
+            "kernel_ms": k2}]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
