@@ -484,6 +484,24 @@ def test_c_abi_from_plain_c_matches_the_closed_form():
     assert run.returncode == 0 and run.stdout.startswith("OK"), run.stdout + run.stderr
 
 
+def test_denormal_values_are_not_flushed():
+    """fp32 subnormals take part in the arithmetic as IEEE values (no
+    flush-to-zero): gradients around 1e-38 give momentum buffers full of
+    subnormal numbers, which must equal the fp32 oracle's bit for bit."""
+    w = dataclasses.replace(W.ragged_mini(policy="maintain"), sigma=1e-38, weight_decay=0.0,
+                            rounds=2)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    snap = PU.run_gpu(w, prob, opt, w.rounds, idx)
+    _, s32 = PU.run_oracle(w, idx, w.rounds, "f32")
+    tiny = np.abs(s32["h"]) < np.finfo(np.float32).tiny
+    assert np.count_nonzero(tiny & (s32["h"] != 0)) > 1000        # the case is really exercised
+    assert np.array_equal(snap["h"], s32["h"])
+    assert np.array_equal(snap["x"], s32["x"])
+    opt.close()
+
+
 def test_call_sequence_errors_leave_state_unchanged():
     import paper_1910_00643_amd as P
     w = dataclasses.replace(W.ragged_mini(), tau=2, rounds=1)
