@@ -429,7 +429,7 @@ def test_outer_iteration_replayed_from_a_hip_graph():
     ref_opt.close()
 
 
-@pytest.mark.parametrize("seed", list(range(20)))
+@pytest.mark.parametrize("seed", list(range(24)))
 def test_random_configurations(seed):
     """Seeded random draws over everything the library accepts: tensor lists
     with empty, tiny and multi-tile tensors, worker counts, tau, both base
@@ -447,7 +447,8 @@ def test_random_configurations(seed):
     exact = seed % 4 != 3                   # every fourth draw: no exact average (Section 6)
     if not exact and policy == "average":
         policy = "maintain"
-    mix = "expgraph" if (exact and rng.integers(0, 4) == 0) else "none"
+    mix = "expgraph" if rng.integers(0, 3) == 0 else "none"     # also without the exact average:
+    # gossip as the only exchange is the SGP-SlowMo-noaverage variant of Section 6
     groups = bool(rng.integers(0, 2))
     w = Workload = dataclasses.replace(
         W.ragged_mini(base=base, grad_dtype=str(rng.choice(["f32", "bf16"])), policy=policy,
