@@ -75,7 +75,7 @@ def round_bytes(w, fused: bool = False) -> int:
     steps = range(w.tau - 1) if fused else range(w.tau)
     per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0, reset and k == w.tau - 1)
                           for k in steps)
-    if w.mix == "expgraph":     # every replica read and written once per gossip step
+    if w.mix != "none":         # every replica read and written once per gossip step
         per_worker_elem += 8 * w.tau
     tail = fused_bytes_per_element(w) if fused else outer_bytes_per_element(w)
     return w.d * (w.m * per_worker_elem + tail)
@@ -105,7 +105,12 @@ def run_rounds(w, opt, arrays, rounds, events=None, fused=False):
     import torch
     import paper_1910_00643_amd as P
     ring = len(arrays)
-    peers = [P.slowmo_expgraph_in_peers(w.m, s) for s in range(16)] if w.mix == "expgraph" else None
+    peers = None
+    if w.mix == "expgraph":
+        peers = [P.slowmo_expgraph_in_peers(w.m, s) for s in range(16)]
+    elif w.mix == "random":     # any in-neighbour map: the general (push-sum) kernel
+        from slowmo_inputs.workloads import in_peers
+        peers = [in_peers(w, s).tolist() for s in range(16)]
     for _ in range(rounds):
         for k in range(w.tau):
             if fused and k == w.tau - 1:        # last local step + outer step, one call
@@ -202,6 +207,9 @@ def cpu_baseline(w, budget_s=12.0):
             o.local_step(sets[step % 4], w.f32("lr"))
             if w.mix == "expgraph":
                 o.mix_step(O.exponential_graph_in_peers(w.m, step))
+            elif w.mix == "random":
+                from slowmo_inputs.workloads import in_peers
+                o.mix_step(in_peers(w, step))
             step += 1
         o.outer_step(w.f32("lr"))
         spent += time.perf_counter() - t0
@@ -224,7 +232,7 @@ def main():
     ap.add_argument("--ring", type=int, default=0, help="gradient sets kept in HBM (default tau)")
     ap.add_argument("--policy", default=None, choices=["reset", "maintain", "average"],
                     help="override the workload's buffer strategy")
-    ap.add_argument("--mix", default=None, choices=["expgraph"],
+    ap.add_argument("--mix", default=None, choices=["expgraph", "random"],
                     help="stochastic gradient push as base: a gossip step on the one-peer "
                          "exponential graph after every local step")
     ap.add_argument("--no-average", action="store_true",

@@ -177,20 +177,66 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
 /*
  * One mixing (gossip) step of stochastic gradient push among the m logical
  * workers: Algorithm C.1, "send / receive / update model parameters", i.e.
- * X <- X P^T of Appendix C.1, for the case the paper runs: every worker sends
- * one message and receives one per iteration.
- *   in_peer : host array of m worker indices, a permutation of 0..m-1; worker
- *             i receives from worker in_peer[i] (in_peer[i] == i: worker i
- *             neither sends nor receives in this step).
- * Every sender splits its mass evenly between itself and its receiver, so
- *   x^{(i)} <- x^{(i)} / 2 + x^{(in_peer[i])} / 2      (old values on the right)
- * for all i at once, in place.  This P is doubly stochastic: the push-sum
- * weights w_i of Algorithm C.1 stay 1 and the de-biased iterates z^{(i)} equal
- * x^{(i)}, so neither is stored.  May be called any number of times between
- * local steps; it changes the replicas only.
- * Errors: ARG (NULL, or in_peer is not a permutation), HIP.
+ * X <- X P^T of Appendix C.1, with a column-stochastic P in which every
+ * worker has at most one in-neighbour besides itself.
+ *   in_peer : host array of m worker indices in 0..m-1; worker i receives from
+ *             worker in_peer[i] (in_peer[i] == i: from nobody).  A worker may
+ *             send to any number of workers.
+ * A sender j splits its mass evenly between itself and its outdeg(j)
+ * receivers: p(i,j) = 1 / (1 + outdeg(j)) for j == i and j == in_peer[i], so
+ *   x^{(i)} <- p(i,i) x^{(i)} + p(i,in_peer[i]) x^{(in_peer[i])}   (old values on the right)
+ * for all i at once, in place, and the push-sum weights w_i, kept on the host,
+ * mix the same way.  When in_peer is a permutation (the case the paper runs:
+ * one message sent and one received per worker) every weight is 1/2 and P is
+ * doubly stochastic: equal w_i stay equal.  The w_i start at 1 and return
+ * to 1 at every outer step that averages exactly (cfg.no_average == 0).
+ * May be called any number of times between local steps; it changes the
+ * replicas and the w_i only.
+ * Errors: ARG (NULL, an entry outside 0..m-1), HIP.
  */
 slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream);
+
+/*
+ * Inspection: the order in which slowmo_mix_step updates the replicas in place
+ * for a map that is not a permutation (a permutation takes a shorter path with
+ * the same results).  Entry e sets, per element,
+ *   TREE        x[worker] <- keep * x[worker] + take * x[source]
+ *   ROOT        x[worker] <- keep * x[worker]
+ *   CYCLE_FIRST / CYCLE_NEXT: consecutive entries form a cycle; each worker's
+ *               source is the next entry's worker and the last one's source is
+ *               the first; all of them use the values from before the step.
+ * The order is valid if every worker comes before its source, except inside a
+ * cycle.  Idle workers (no sender, no receiver) have no entry.
+ * Writes at most m entries to `out` (host) and returns their number, or -1
+ * for bad arguments.  Host-only.
+ */
+enum { SLOWMO_MIX_TREE = 0, SLOWMO_MIX_ROOT = 1, SLOWMO_MIX_CYCLE_FIRST = 2, SLOWMO_MIX_CYCLE_NEXT = 3 };
+typedef struct slowmo_mix_entry {
+  int32_t worker;
+  int32_t source;
+  float keep;      /* p(worker, worker) */
+  float take;      /* p(worker, source) */
+  int32_t kind;    /* SLOWMO_MIX_* */
+  int32_t reserved;
+} slowmo_mix_entry;
+int32_t slowmo_plan_mix(int32_t m, const int32_t *in_peer, slowmo_mix_entry *out);
+
+/* Copies the m push-sum weights w_i (Algorithm C.1) into the HOST array w.
+ * Host-only, no device work.  Errors: ARG. */
+slowmo_status slowmo_get_pushsum_weights(const slowmo_ctx *ctx, float *w);
+
+/*
+ * The de-biased parameters of Algorithm C.1 (last line): z^{(i)} = x^{(i)} / w_i,
+ * the point at which worker i evaluates its next gradient.
+ *   z : host array of m * n_tensors DEVICE pointers, laid out like `params` of
+ *       slowmo_create; z[i * n_tensors + j] receives numel[j] floats.  4-byte
+ *       alignment is enough (16 enables vector stores).  The destinations
+ *       must not overlap the replicas, the workspace or each other.
+ * Reads the replicas and the current w_i; changes no state.  The pointer array
+ * is copied before the call returns.  Asynchronous on `stream`.
+ * Errors: ARG (NULL), ALIGN, HIP.
+ */
+slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream);
 
 /*
  * The communication pattern of Appendix C.1 (one-peer, time-varying directed
@@ -215,9 +261,9 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
                                         const float *lr_scale, void *stream);
 
 /*
- * Checkpointing.  The optimizer's state is x0, u, h (and v) plus the counters
- * t, k, l; slowmo_export_state packs it into one DEVICE buffer of
- * slowmo_export_bytes() bytes (a 256-byte header, then the arrays), which the
+ * Checkpointing.  The optimizer's state is x0, u, h (and v), the counters
+ * t, k, l and the push-sum weights; slowmo_export_state packs it into one DEVICE buffer of
+ * slowmo_export_bytes() bytes (a 256-byte header, the push-sum weights, then the arrays), which the
  * caller may copy anywhere; slowmo_import_state restores it into a context
  * created with the same configuration and tensor list (otherwise ARG).  The
  * replicas themselves belong to the caller and are not part of the blob; as

@@ -31,7 +31,16 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_destroy", "slowmo_last_error", "slowmo_get_buffer", "slowmo_get_counters",
            "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version", "slowmo_mix_step",
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
-           "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step"]
+           "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step",
+           "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix"]
+
+
+SLOWMO_MIX_TREE, SLOWMO_MIX_ROOT, SLOWMO_MIX_CYCLE_FIRST, SLOWMO_MIX_CYCLE_NEXT = 0, 1, 2, 3
+
+
+class slowmo_mix_entry(C.Structure):
+    _fields_ = [("worker", C.c_int32), ("source", C.c_int32), ("keep", C.c_float),
+                ("take", C.c_float), ("kind", C.c_int32), ("reserved", C.c_int32)]
 
 
 class slowmo_config(C.Structure):
@@ -93,6 +102,12 @@ def lib() -> C.CDLL:
     L.slowmo_plan_outer.restype = i64
     L.slowmo_mix_step.argtypes = [vp, C.POINTER(i32), vp]
     L.slowmo_mix_step.restype = C.c_int
+    L.slowmo_plan_mix.argtypes = [i32, C.POINTER(i32), C.POINTER(slowmo_mix_entry)]
+    L.slowmo_plan_mix.restype = C.c_int32
+    L.slowmo_get_pushsum_weights.argtypes = [vp, C.POINTER(C.c_float)]
+    L.slowmo_get_pushsum_weights.restype = C.c_int
+    L.slowmo_debias.argtypes = [vp, C.POINTER(vp), vp]
+    L.slowmo_debias.restype = C.c_int
     L.slowmo_expgraph_in_peers.argtypes = [i32, i64, C.POINTER(i32)]
     L.slowmo_expgraph_in_peers.restype = C.c_int
     L.slowmo_set_tensor_hparams.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
@@ -171,9 +186,35 @@ def slowmo_outer_step(ctx, lr: float, stream: int = 0) -> None:
 
 
 def slowmo_mix_step(ctx, in_peer: Sequence[int], stream: int = 0) -> None:
-    """in_peer: m worker indices (a permutation); worker i receives from in_peer[i]."""
+    """in_peer: m worker indices; worker i receives from in_peer[i]."""
     arr = (C.c_int32 * len(in_peer))(*[int(v) for v in in_peer]) if in_peer is not None else None
     _check(lib().slowmo_mix_step(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_plan_mix(in_peer: Sequence[int]):
+    """The in-place update order of a mixing step: a list of
+    (worker, source, keep, take, kind); None for bad arguments."""
+    m = len(in_peer)
+    arr = (C.c_int32 * max(m, 1))(*[int(v) for v in in_peer])
+    out = (slowmo_mix_entry * max(m, 1))()
+    n = lib().slowmo_plan_mix(m, arr, out)
+    if n < 0:
+        return None
+    return [(out[i].worker, out[i].source, out[i].keep, out[i].take, out[i].kind)
+            for i in range(n)]
+
+
+def slowmo_get_pushsum_weights(ctx, m: int):
+    """The m push-sum weights as a list of floats (fp32 values)."""
+    arr = (C.c_float * max(m, 1))()
+    _check(lib().slowmo_get_pushsum_weights(ctx, arr), ctx)
+    return [arr[i] for i in range(m)]
+
+
+def slowmo_debias(ctx, z, stream: int = 0) -> None:
+    """z: m * n_tensors device addresses that receive x^{(i)} / w_i."""
+    arr = z if (z is None or isinstance(z, C.Array)) else _ptr_array(z)
+    _check(lib().slowmo_debias(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
 
 
 def slowmo_expgraph_in_peers(m: int, step: int):

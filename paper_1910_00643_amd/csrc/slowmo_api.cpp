@@ -27,9 +27,17 @@ thread_local std::string g_err = "";
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// One slot of the mixing-table ring holds either the worker sequence of a
+// permutation (m int32) or the entries of a general map (m MixEntry).
+size_t mixtab_bytes(int32_t m) { return static_cast<size_t>(m) * sizeof(MixEntry); }
+// One slot of the de-bias ring: m * n_tensors destination pointers, then the m weights.
+size_t ztab_bytes(int32_t m, int32_t n_tensors) {
+  return static_cast<size_t>(m) * n_tensors * sizeof(void *) + static_cast<size_t>(m) * sizeof(float);
+}
+
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kSlots], mixtab[kSlots], slots, tensors, ltiles, otiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
@@ -50,7 +58,8 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
   s.xtab_t = take(n_ptr * sizeof(void *));
   for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
-  for (int i = 0; i < kSlots; ++i) s.mixtab[i] = take(static_cast<size_t>(c.m) * sizeof(int32_t));
+  for (int i = 0; i < kSlots; ++i) s.mixtab[i] = take(mixtab_bytes(c.m));
+  for (int i = 0; i < kSlots; ++i) s.ztab[i] = take(ztab_bytes(c.m, n_tensors));
   s.slots = take(n_ptr * sizeof(SlotInfo));
   s.tensors = take(static_cast<size_t>(n_tensors) * sizeof(TensorInfo));
   s.ltiles = take(n_ltiles * sizeof(TileRef));
@@ -174,6 +183,8 @@ struct slowmo_ctx {
   TableRing gtab;    // gradient pointers of the current call (m * n_tensors)
   std::vector<const void *> last_grads;  // contents of gtab's current slot
   TableRing mixtab;  // worker sequence of the current mixing step (m entries)
+  TableRing ztab;    // destination pointers and weights of the current de-bias call
+  std::vector<float> w;  // push-sum weights (Algorithm C.1), 1 after every exact average
   std::vector<SlotInfo> slots;      // host copies of the per-slot / per-tensor tables
   std::vector<TensorInfo> tinfo;
 
@@ -206,6 +217,7 @@ slowmo_status fail_hip(slowmo_ctx *ctx, hipError_t e, const char *what) {
 void release(slowmo_ctx *ctx) {
   ctx->gtab.destroy();
   ctx->mixtab.destroy();
+  ctx->ztab.destroy();
   delete ctx;
 }
 
@@ -348,8 +360,9 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   } while (0)
 
   CREATE_HIP(ctx->gtab.init(base, sec.gtab, n_ptr * sizeof(void *)), "gradient-pointer ring");
-  CREATE_HIP(ctx->mixtab.init(base, sec.mixtab, static_cast<size_t>(m) * sizeof(int32_t)),
-             "mixing-table ring");
+  CREATE_HIP(ctx->mixtab.init(base, sec.mixtab, mixtab_bytes(m)), "mixing-table ring");
+  CREATE_HIP(ctx->ztab.init(base, sec.ztab, ztab_bytes(m, n_tensors)), "de-bias table ring");
+  ctx->w.assign(m, 1.0f);
 
   // device tables
   const Layout &L = ctx->layout;
@@ -498,6 +511,8 @@ void finish_local(slowmo_ctx *ctx) {
 void finish_outer(slowmo_ctx *ctx) {
   ctx->k = 0;
   ctx->t += 1;
+  // after the exact average every worker holds the same, unbiased point again
+  if (!ctx->cfg.no_average) std::fill(ctx->w.begin(), ctx->w.end(), 1.0f);
   if (ctx->cfg.policy == SLOWMO_BUF_RESET) {  // Algorithm 1 line 2 of the next outer iteration
     ctx->buffers_zero = true;
     ctx->l = 0;
@@ -623,17 +638,12 @@ slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer
   return SLOWMO_OK;
 }
 
-slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
-  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
-  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+namespace {
+
+// Mixing step for a map in which every worker sends to exactly one other
+// worker or to nobody and receives likewise: all weights are 1/2.
+slowmo_status mix_permutation(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
   const int32_t m = ctx->cfg.m;
-  std::vector<char> hit(m, 0);
-  for (int32_t i = 0; i < m; ++i) {
-    if (in_peer[i] < 0 || in_peer[i] >= m || hit[in_peer[i]])
-      return fail(ctx, SLOWMO_ERR_ARG,
-                  "in_peer must be a permutation of 0..m-1 (one sender and one receiver per worker)");
-    hit[in_peer[i]] = 1;
-  }
   // Workers listed cycle by cycle, each followed by the worker it receives
   // from; bit 30 marks the first worker of a cycle.  Fixed points are idle.
   std::vector<int32_t> seq;
@@ -648,7 +658,6 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
     }
   }
   if (seq.empty() || ctx->n_otiles == 0) return SLOWMO_OK;
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
   hipError_t e = hipSuccess;
   const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(int32_t), stream, &e);
   if (slot < 0) return fail_hip(ctx, e, "upload of the mixing sequence");
@@ -662,6 +671,164 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
   a.len = static_cast<int32_t>(seq.size());
   e = launch_mix_step(a, ctx->tune, stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
+  return SLOWMO_OK;
+}
+
+// Mixing step for any map with at most one in-neighbour per worker.  A sender
+// j splits its mass evenly over itself and its outdeg(j) receivers, so
+// p(i,j) = 1 / (1 + outdeg(j)) and P is column-stochastic (Algorithm C.1).
+// The replicas are mixed in place: a worker is overwritten only after every
+// worker that receives from it has been served.  Seen as "i points to
+// in_peer[i]", the map is a forest of trees hanging off cycles and fixed
+// points; the trees go first, deepest workers first, then each cycle.
+void build_mix_entries(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
+                       std::vector<float> &share) {
+  std::vector<int32_t> outdeg(m, 0);
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] != i) ++outdeg[in_peer[i]];
+  share.resize(m);
+  for (int32_t j = 0; j < m; ++j) share[j] = 1.0f / static_cast<float>(1 + outdeg[j]);
+
+  // Peel workers nobody receives from, layer by layer: the peeling order is an
+  // order in which each worker precedes its source.  What is left are cycles.
+  std::vector<int32_t> pending = outdeg, order;
+  std::vector<char> peeled(m, 0);
+  order.reserve(m);
+  for (int32_t i = 0; i < m; ++i)
+    if (pending[i] == 0) order.push_back(i);
+  for (size_t q = 0; q < order.size(); ++q) {
+    const int32_t i = order[q];
+    peeled[i] = 1;
+    const int32_t j = in_peer[i];
+    if (j != i && --pending[j] == 0) order.push_back(j);
+  }
+  seq.clear();
+  seq.reserve(m);
+  for (int32_t i : order) {
+    const int32_t j = in_peer[i];
+    if (j != i) {
+      seq.push_back({i, j, share[i], share[j], kMixTree, 0});
+    } else if (outdeg[i] > 0) {
+      seq.push_back({i, i, share[i], 0.f, kMixRoot, 0});
+    }  // else: an idle worker keeps its value
+  }
+  for (int32_t i = 0; i < m; ++i) {
+    if (peeled[i]) continue;
+    bool first = true;
+    for (int32_t j = i; !peeled[j]; j = in_peer[j]) {
+      peeled[j] = 1;
+      seq.push_back({j, in_peer[j], share[j], share[in_peer[j]],
+                     first ? kMixCycleFirst : kMixCycleNext, 0});
+      first = false;
+    }
+  }
+}
+
+slowmo_status mix_general(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
+  const int32_t m = ctx->cfg.m;
+  std::vector<MixEntry> seq;
+  std::vector<float> share;
+  build_mix_entries(m, in_peer, seq, share);
+  if (!seq.empty() && ctx->n_otiles > 0) {
+    hipError_t e = hipSuccess;
+    const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
+    if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
+    MixGeneralArgs a{};
+    a.tiles = ctx->d_otiles;
+    a.tensors = ctx->d_tensors;
+    a.xtab_t = ctx->d_xtab_t;
+    a.ntiles = ctx->n_otiles;
+    a.m = m;
+    a.seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
+    a.len = static_cast<int32_t>(seq.size());
+    e = launch_mix_general(a, ctx->tune, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
+  }
+  return SLOWMO_OK;
+}
+
+}  // namespace
+
+slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+  const int32_t m = ctx->cfg.m;
+  std::vector<char> hit(m, 0);
+  bool permutation = true;
+  for (int32_t i = 0; i < m; ++i) {
+    if (in_peer[i] < 0 || in_peer[i] >= m)
+      return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
+    if (hit[in_peer[i]]) permutation = false;
+    hit[in_peer[i]] = 1;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const slowmo_status st =
+      permutation ? mix_permutation(ctx, in_peer, stream) : mix_general(ctx, in_peer, stream);
+  if (st != SLOWMO_OK) return st;
+  // the push-sum weights mix with the same P, in the same arithmetic as the replicas
+  std::vector<int32_t> outdeg(m, 0);
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] != i) ++outdeg[in_peer[i]];
+  std::vector<float> w_new(m);
+  for (int32_t i = 0; i < m; ++i) {
+    const int32_t j = in_peer[i];
+    float v = (1.0f / static_cast<float>(1 + outdeg[i])) * ctx->w[i];
+    if (j != i) v = v + (1.0f / static_cast<float>(1 + outdeg[j])) * ctx->w[j];
+    w_new[i] = v;
+  }
+  ctx->w.swap(w_new);
+  return SLOWMO_OK;
+}
+
+int32_t slowmo_plan_mix(int32_t m, const int32_t *in_peer, slowmo_mix_entry *out) {
+  static_assert(sizeof(slowmo_mix_entry) == sizeof(MixEntry), "public and internal entry differ");
+  if (m < 1 || m > SLOWMO_MAX_WORKERS || !in_peer || !out) return -1;
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] < 0 || in_peer[i] >= m) return -1;
+  std::vector<MixEntry> seq;
+  std::vector<float> share;
+  build_mix_entries(m, in_peer, seq, share);
+  for (size_t i = 0; i < seq.size(); ++i)
+    out[i] = {seq[i].node, seq[i].src, seq[i].a, seq[i].b, seq[i].kind, 0};
+  return static_cast<int32_t>(seq.size());
+}
+
+slowmo_status slowmo_get_pushsum_weights(const slowmo_ctx *ctx, float *w) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!w) return fail(const_cast<slowmo_ctx *>(ctx), SLOWMO_ERR_ARG, "w is NULL");
+  std::memcpy(w, ctx->w.data(), ctx->w.size() * sizeof(float));
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!z) return fail(ctx, SLOWMO_ERR_ARG, "z is NULL");
+  const int32_t m = ctx->cfg.m, nt = ctx->n_tensors;
+  const size_t n_ptr = static_cast<size_t>(m) * nt;
+  for (size_t i = 0; i < n_ptr; ++i) {
+    if (ctx->numel[i % nt] == 0) continue;
+    if (!z[i]) return fail(ctx, SLOWMO_ERR_ARG, "a destination pointer is NULL");
+    if (reinterpret_cast<uintptr_t>(z[i]) % sizeof(float))
+      return fail(ctx, SLOWMO_ERR_ALIGN, "a destination pointer is not 4-byte aligned");
+  }
+  if (ctx->n_ltiles == 0) return SLOWMO_OK;
+  std::vector<char> table(ztab_bytes(m, nt));
+  std::memcpy(table.data(), z, n_ptr * sizeof(void *));
+  std::memcpy(table.data() + n_ptr * sizeof(void *), ctx->w.data(), m * sizeof(float));
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipError_t e = hipSuccess;
+  const int slot = ctx->ztab.upload(table.data(), table.size(), stream, &e);
+  if (slot < 0) return fail_hip(ctx, e, "upload of the de-bias table");
+  DebiasArgs a{};
+  a.tiles = ctx->d_ltiles;
+  a.slots = ctx->d_slots;
+  a.ztab = static_cast<float *const *>(ctx->ztab.d[slot]);
+  a.w = reinterpret_cast<const float *>(static_cast<const char *>(ctx->ztab.d[slot]) +
+                                        n_ptr * sizeof(void *));
+  a.ntiles = ctx->n_ltiles;
+  a.n_tensors = nt;
+  e = launch_debias(a, ctx->tune, stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "de-bias kernel launch");
   return SLOWMO_OK;
 }
 
@@ -702,8 +869,9 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
 
 namespace {
 
-// Header of an exported state blob (256 bytes), followed by the x0, u, h, v
-// arenas exactly as they lie in the workspace.
+// Header of an exported state blob (256 bytes), followed by the m push-sum
+// weights (padded to a multiple of 256 bytes) and the x0, u, h, v arenas
+// exactly as they lie in the workspace.
 struct BlobHeader {
   char magic[8];
   uint32_t version;
@@ -712,17 +880,19 @@ struct BlobHeader {
   char pad_[256 - 8 - 4 * 8 - 8 * 4];
 };
 static_assert(sizeof(BlobHeader) == 256, "BlobHeader layout");
+constexpr uint32_t kBlobVersion = 2;
 constexpr char kBlobMagic[8] = {'S', 'L', 'O', 'W', 'M', 'O', 'S', 'T'};
 
 struct BlobParts {
-  size_t arena, outer_copies, n_v, total;
+  size_t arena, outer_copies, n_v, weights, total;
 };
 BlobParts blob_parts(const slowmo_ctx *ctx) {
   BlobParts p;
   p.arena = static_cast<size_t>(ctx->layout.d_pad) * sizeof(float);
   p.outer_copies = ctx->cfg.no_average ? ctx->cfg.m : 1;
   p.n_v = ctx->v ? ctx->cfg.m : 0;
-  p.total = sizeof(BlobHeader) + p.arena * (2 * p.outer_copies + ctx->cfg.m + p.n_v);
+  p.weights = round_up(static_cast<size_t>(ctx->cfg.m) * sizeof(float), 256);
+  p.total = sizeof(BlobHeader) + p.weights + p.arena * (2 * p.outer_copies + ctx->cfg.m + p.n_v);
   return p;
 }
 
@@ -737,7 +907,7 @@ slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst, size_t bytes, void
   if (bytes < p.total) return fail(ctx, SLOWMO_ERR_NOMEM, "destination smaller than slowmo_export_bytes()");
   BlobHeader hd{};
   std::memcpy(hd.magic, kBlobMagic, 8);
-  hd.version = 1;
+  hd.version = kBlobVersion;
   hd.m = ctx->cfg.m;
   hd.n_tensors = ctx->n_tensors;
   hd.base = ctx->cfg.base;
@@ -752,6 +922,10 @@ slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst, size_t bytes, void
   char *out = static_cast<char *>(dst);
   hipError_t e = hipMemcpyAsync(out, &hd, sizeof(hd), hipMemcpyHostToDevice, stream);
   size_t off = sizeof(hd);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(out + off, ctx->w.data(), ctx->w.size() * sizeof(float),
+                       hipMemcpyHostToDevice, stream);
+  off += p.weights;
   auto put = [&](const float *src, size_t n) {
     if (e == hipSuccess && n)
       e = hipMemcpyAsync(out + off, src, n, hipMemcpyDeviceToDevice, stream);
@@ -776,7 +950,7 @@ slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes
   hipError_t e = hipMemcpyAsync(&hd, src, sizeof(hd), hipMemcpyDeviceToHost, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "reading the blob header");
-  if (std::memcmp(hd.magic, kBlobMagic, 8) != 0 || hd.version != 1)
+  if (std::memcmp(hd.magic, kBlobMagic, 8) != 0 || hd.version != kBlobVersion)
     return fail(ctx, SLOWMO_ERR_ARG, "not a state blob of this library version");
   if (hd.m != ctx->cfg.m || hd.n_tensors != ctx->n_tensors || hd.base != ctx->cfg.base ||
       hd.no_average != ctx->cfg.no_average || hd.d != ctx->layout.d || hd.d_pad != ctx->layout.d_pad)
@@ -785,6 +959,13 @@ slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes
     return fail(ctx, SLOWMO_ERR_ARG, "the blob's counters do not fit this configuration");
   const char *in = static_cast<const char *>(src);
   size_t off = sizeof(hd);
+  std::vector<float> w(ctx->cfg.m);
+  e = hipMemcpyAsync(w.data(), in + off, w.size() * sizeof(float), hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "reading the blob's push-sum weights");
+  for (float wi : w)
+    if (!finite_pos(wi)) return fail(ctx, SLOWMO_ERR_ARG, "the blob's push-sum weights are not positive");
+  off += p.weights;
   auto get = [&](float *dst, size_t n) {
     if (e == hipSuccess && n)
       e = hipMemcpyAsync(dst, in + off, n, hipMemcpyDeviceToDevice, stream);
@@ -799,6 +980,7 @@ slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes
   ctx->k = hd.k;
   ctx->l = hd.l;
   ctx->buffers_zero = hd.buffers_zero != 0;
+  ctx->w.swap(w);
   return SLOWMO_OK;
 }
 

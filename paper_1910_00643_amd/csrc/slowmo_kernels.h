@@ -66,6 +66,40 @@ struct MixArgs {
   int32_t len;
 };
 
+// General mixing step (any in-neighbour map, column-stochastic weights): the
+// workers in an order in which every worker comes before the worker it
+// receives from, so that old values are still in memory when they are needed;
+// cycles are closed with the first member's old value, kept in registers.
+enum MixKind : int32_t { kMixTree = 0, kMixRoot = 1, kMixCycleFirst = 2, kMixCycleNext = 3 };
+struct MixEntry {
+  int32_t node;    // worker updated by this entry
+  int32_t src;     // worker it receives from (unused for kMixRoot)
+  float a;         // p(node, node) = 1 / (1 + outdeg(node))
+  float b;         // p(node, src)  = 1 / (1 + outdeg(src))
+  int32_t kind;    // MixKind
+  int32_t pad_;
+};
+static_assert(sizeof(MixEntry) == 24, "MixEntry layout");
+struct MixGeneralArgs {
+  const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
+  const TensorInfo *tensors;   // device
+  float *const *xtab_t;        // device: replica pointers, tensor-major
+  int32_t ntiles;
+  int32_t m;
+  const MixEntry *seq;         // device: len entries
+  int32_t len;
+};
+
+// De-biased parameters of push-sum: z^{(i)} = x^{(i)} / w_i, over the local tiles.
+struct DebiasArgs {
+  const TileRef *tiles;        // device (owner = slot)
+  const SlotInfo *slots;       // device
+  float *const *ztab;          // device: m * n_tensors destination pointers (worker-major)
+  const float *w;              // device: m push-sum weights
+  int32_t ntiles;
+  int32_t n_tensors;
+};
+
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
@@ -89,6 +123,9 @@ hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32
                                    int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_mix_general(const MixGeneralArgs &a, const LaunchTuning &tune,
+                              hipStream_t stream);
+hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
                                    hipStream_t stream);
 

@@ -590,6 +590,111 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
   }
 }
 
+// General in-neighbour map: see MixEntry.  One entry at a time (a worker's
+// source is read a second time when its own entry comes; that read normally
+// hits in L2, so plain loads are used for it).
+template <bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_mix_general(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const MixEntry *__restrict__ seq, int len, int ntiles,
+    int chunk, int remap, int m) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (ti.unaligned == 0 && e0 + 4 <= n) {
+    V4 first = {0.f, 0.f, 0.f, 0.f}, cur = first;
+    float a_prev = 0.f, b_prev = 0.f;
+    float *prev = nullptr;
+    for (int i = 0; i < len; ++i) {
+      const MixEntry en = seq[i];
+      float *ptr = xp[en.node] + eo + e0;
+      if (en.kind == kMixTree) {
+        V4 xi = ld4<NT>(ptr), xs = ld4<false>(xp[en.src] + eo + e0);
+        st4<NT>(ptr, en.a * xi + en.b * xs);
+      } else if (en.kind == kMixRoot) {
+        st4<NT>(ptr, en.a * ld4<NT>(ptr));
+      } else {
+        V4 v = ld4<NT>(ptr);
+        if (en.kind == kMixCycleFirst) {
+          if (prev) st4<NT>(prev, a_prev * cur + b_prev * first);
+          first = v;
+        } else {
+          st4<NT>(prev, a_prev * cur + b_prev * v);
+        }
+        cur = v;
+        prev = ptr;
+        a_prev = en.a;
+        b_prev = en.b;
+      }
+    }
+    if (prev) st4<NT>(prev, a_prev * cur + b_prev * first);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      float first = 0.f, cur = 0.f, a_prev = 0.f, b_prev = 0.f;
+      float *prev = nullptr;
+      for (int i = 0; i < len; ++i) {
+        const MixEntry en = seq[i];
+        float *ptr = xp[en.node] + eo + j;
+        if (en.kind == kMixTree) {
+          st1(ptr, en.a * ld1(ptr) + en.b * ld1(xp[en.src] + eo + j));
+        } else if (en.kind == kMixRoot) {
+          st1(ptr, en.a * ld1(ptr));
+        } else {
+          const float v = ld1(ptr);
+          if (en.kind == kMixCycleFirst) {
+            if (prev) st1(prev, a_prev * cur + b_prev * first);
+            first = v;
+          } else {
+            st1(prev, a_prev * cur + b_prev * v);
+          }
+          cur = v;
+          prev = ptr;
+          a_prev = en.a;
+          b_prev = en.b;
+        }
+      }
+      if (prev) st1(prev, a_prev * cur + b_prev * first);
+    }
+  }
+}
+
+// z^{(i)} = x^{(i)} / w_i (Algorithm C.1, last line), one workgroup per local tile.
+template <bool NT>
+__global__ __launch_bounds__(kLocalBlock) void k_debias(
+    const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
+    float *const *__restrict__ ztab, const float *__restrict__ w, int n_tensors, int ntiles,
+    int chunk, int remap) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const SlotInfo s = slots[t.owner];
+  const float wi = w[t.owner / n_tensors];
+  const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;
+  const float *x = s.x + go;
+  float *z = ztab[t.owner] + go;
+  const int64_t left = s.numel - go;
+  const int n = left < kLocalTile ? static_cast<int>(left) : kLocalTile;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(z)) & 15) == 0 && e0 + 4 <= n) {
+    V4 xv = ld4<NT>(x + e0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) xv[c] = xv[c] / wi;
+    st4<NT>(z + e0, xv);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) st1(z + j, ld1(x + j) / wi);
+  }
+}
+
 struct Grid {
   int chunk;
   unsigned blocks;
@@ -724,6 +829,32 @@ hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t 
   } else {
     hipLaunchKernelGGL((k_mix_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
                        a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_mix_general(const MixGeneralArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_mix_general<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+  } else {
+    hipLaunchKernelGGL((k_mix_general<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_debias<true>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles, a.slots,
+                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, t.xcd_remap);
+  } else {
+    hipLaunchKernelGGL((k_debias<false>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles, a.slots,
+                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, t.xcd_remap);
   }
   return hipGetLastError();
 }

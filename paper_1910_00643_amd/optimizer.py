@@ -83,6 +83,20 @@ class SlowMo:
     def mix_step(self, in_peer: Sequence[int]) -> None:
         B.slowmo_mix_step(self.ctx, in_peer, torch.cuda.current_stream(self.device).cuda_stream)
 
+    def pushsum_weights(self):
+        return B.slowmo_get_pushsum_weights(self.ctx, self.m)
+
+    def debias(self, z: Sequence[Sequence[torch.Tensor]]) -> None:
+        """z[i][j] <- x^{(i)}_j / w_i (fp32 CUDA tensors shaped like the replicas)."""
+        ptrs = []
+        for i in range(self.m):
+            assert len(z[i]) == len(self.numel)
+            for j, t in enumerate(z[i]):
+                assert t.dtype == torch.float32 and t.is_contiguous() and t.device == self.device
+                assert t.numel() == self.numel[j]
+                ptrs.append(t.data_ptr())
+        B.slowmo_debias(self.ctx, ptrs, torch.cuda.current_stream(self.device).cuda_stream)
+
     def outer_step(self, lr: float) -> None:
         B.slowmo_outer_step(self.ctx, lr, torch.cuda.current_stream(self.device).cuda_stream)
 

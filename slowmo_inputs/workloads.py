@@ -39,7 +39,9 @@ class Workload:
     sigma: float = 1.0             # gradient standard deviation
     rounds: int = 3
     exact_average: bool = True     # False: the variant without line 6 of Algorithm 1 (Section 6)
-    mix: str = "none"              # "expgraph": a gossip step (Appendix C.1) after every local step
+    mix: str = "none"              # a gossip step (Appendix C.1) after every local step:
+                                   # "expgraph" (one-peer exponential graph) or "random"
+                                   # (in_peers below: any map, so push-sum weights move)
     tensor_wd: tuple | None = None        # per-tensor weight decay (else weight_decay for all)
     tensor_lr_scale: tuple | None = None  # per-tensor factor on the fast learning rate
 
@@ -114,6 +116,14 @@ def ragged_mini(base: str = "sgd_nesterov", grad_dtype: str = "f32", m: int = 3,
                     alpha=0.75, beta=0.6, base="sgd_nesterov", policy=policy or "reset",
                     lr=0.1, momentum=0.9, weight_decay=1e-4, grad_dtype=grad_dtype,
                     sigma=0.1, rounds=4)
+
+
+def in_peers(w: Workload, step: int) -> np.ndarray:
+    """Seeded in-neighbour map for mix == "random": worker i receives from
+    in_peers[i] (itself: from nobody).  Any map may come out: several receivers
+    per sender, chains, cycles, idle workers."""
+    rng = np.random.default_rng([w.seed, 0x6d6978, step])
+    return rng.integers(0, w.m, size=w.m).astype(np.int32)
 
 
 BY_NAME = {"tiny": tiny, "resnet18": resnet18, "resnet50": resnet50,

@@ -164,3 +164,81 @@ def test_plan_of_transformer_big_and_1e9():
     tile = max(r[3] for r in P.slowmo_plan_local(1, [100_000]))
     assert n_local == 8 * -(-10 ** 9 // tile) and n_outer >= 10 ** 9 // (1 << 20)
     assert lib.slowmo_plan_local(0, 1, arr, None, 0) == -1
+
+
+def _random_in_peer(rng, m, kind):
+    if kind == "any":                       # arbitrary map: trees, cycles, fixed points
+        return rng.integers(0, m, size=m)
+    if kind == "star":                      # one worker sends to everybody
+        return np.zeros(m, dtype=np.int64)
+    if kind == "chain":                     # i receives from i+1, the last from nobody
+        return np.minimum(np.arange(m) + 1, m - 1)
+    perm = rng.permutation(m)               # a permutation, some workers idle
+    idle = rng.random(m) < 0.3
+    p = np.arange(m)
+    act = np.flatnonzero(~idle)
+    p[act] = act[rng.permutation(len(act))]
+    return p
+
+
+@pytest.mark.parametrize("kind", ["any", "star", "chain", "perm"])
+def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
+    """The update order slowmo_plan_mix reports, applied entry by entry to ONE
+    array (as the kernel does, fp32, product and sum rounded separately), must
+    give what the oracle computes from a saved copy of the old values --
+    bit for bit -- for any in-neighbour map (Algorithm C.1, X <- X P^T)."""
+    from oracle import slowmo_oracle as O
+    lib = O.load("f32")
+    rng = np.random.default_rng(7)
+    f32 = np.float32
+    for m in (1, 2, 3, 5, 8, 17, 64):
+        for _ in range(6):
+            peers = np.asarray(_random_in_peer(rng, m, kind), dtype=np.int32)
+            plan = P.slowmo_plan_mix(peers.tolist())
+            assert plan is not None and len(plan) <= m
+            d = 5
+            x = rng.standard_normal((m, d)).astype(f32)
+            want = x.copy()
+            w = np.ones(m, f32)
+            lib.oracle_mix_step(want.ctypes.data_as(C.c_void_p), w.ctypes.data_as(C.c_void_p),
+                                m, d, peers.ctypes.data_as(C.c_void_p))
+            got = x.copy()
+            seen = set()
+            i = 0
+            while i < len(plan):
+                worker, source, keep, take, kind_e = plan[i]
+                keep, take = f32(keep), f32(take)
+                assert worker not in seen
+                if kind_e == B.SLOWMO_MIX_TREE:
+                    assert source == peers[worker] != worker and source not in seen
+                    got[worker] = keep * got[worker] + take * got[source]
+                    seen.add(worker)
+                    i += 1
+                elif kind_e == B.SLOWMO_MIX_ROOT:
+                    assert peers[worker] == worker
+                    got[worker] = keep * got[worker]
+                    seen.add(worker)
+                    i += 1
+                else:
+                    assert kind_e == B.SLOWMO_MIX_CYCLE_FIRST
+                    j = i + 1
+                    while j < len(plan) and plan[j][4] == B.SLOWMO_MIX_CYCLE_NEXT:
+                        j += 1
+                    cyc = plan[i:j]
+                    old = [got[e[0]].copy() for e in cyc]
+                    for q, e in enumerate(cyc):
+                        nxt = (q + 1) % len(cyc)
+                        assert e[1] == peers[e[0]] == cyc[nxt][0] and e[0] not in seen
+                        got[e[0]] = f32(e[2]) * old[q] + f32(e[3]) * old[nxt]
+                    seen.update(e[0] for e in cyc)
+                    i = j
+            np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+            # workers without an entry are idle: nobody sends to or receives from them
+            for i in set(range(m)) - seen:
+                assert peers[i] == i and not np.any(np.delete(peers, i) == i)
+
+
+def test_mix_plan_rejects_bad_maps():
+    assert P.slowmo_plan_mix([0, 3]) is None
+    assert P.slowmo_plan_mix([-1, 0]) is None
+    assert P.slowmo_plan_mix([]) is None

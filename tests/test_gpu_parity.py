@@ -137,25 +137,106 @@ def test_gradient_push_mixing_every_element(m, base, param_layout):
     opt.close()
 
 
-def test_mixing_accepts_any_permutation_and_rejects_other_maps():
+def test_mixing_accepts_any_map_and_rejects_bad_indices():
     import paper_1910_00643_amd as P
     w = dataclasses.replace(W.ragged_mini(m=5), tau=1, rounds=1)
     prob = _problem(w, grad_layout="separate")
     opt = PU.make_gpu(w, prob)
     idx = np.arange(w.d, dtype=np.int64)
-    o = PU.make_oracle(w, idx)
+    o = PU.make_oracle(w, idx, "f32")
     prob.fill_grads(0, 0)
     opt.local_step(prob.grads[0], w.lr)
     o.local_step(PU.oracle_grads(w, idx, 0), w.f32("lr"))
-    for peers in ([1, 0, 2, 4, 3], [2, 3, 4, 0, 1], [0, 1, 2, 3, 4], [4, 0, 1, 2, 3]):
+    for peers in ([1, 0, 2, 4, 3], [2, 3, 4, 0, 1], [0, 1, 2, 3, 4], [4, 0, 1, 2, 3],
+                  [0, 0, 1, 2, 3], [0, 0, 0, 0, 0], [1, 0, 0, 4, 4], [1, 2, 0, 0, 3],
+                  [1, 0, 3, 4, 2]):      # the last: a permutation met with unequal weights
         opt.mix_step(peers)
         o.mix_step(peers)
-    got = np.stack([prob.gather(prob.params[i], idx) for i in range(w.m)])
-    PU.assert_params_close(got, o.x, "replicas after four mixing steps")
-    for bad in ([0, 0, 1, 2, 3], [1, 2, 3, 4, 5], [-1, 0, 1, 2, 3]):
+        got = np.stack([prob.gather(prob.params[i], idx) for i in range(w.m)])
+        assert np.array_equal(got, o.x), peers
+        assert np.array_equal(np.asarray(opt.pushsum_weights(), np.float32), o.w), peers
+    for bad in ([1, 2, 3, 4, 5], [-1, 0, 1, 2, 3]):
         with pytest.raises(P.SlowMoError) as e:
             opt.mix_step(bad)
         assert e.value.status == P.binding.SLOWMO_ERR_ARG
+    opt.close()
+
+
+@pytest.mark.parametrize("m,base,param_layout,exact", [
+    (5, "sgd_nesterov", "separate", True), (8, "sgd_nesterov", "flat", True),
+    (19, "adam", "separate", True), (33, "sgd_nesterov", "separate", True),
+    (6, "sgd_nesterov", "flat", False), (2, "sgd_nesterov", "separate", True)])
+def test_push_sum_with_any_in_neighbour_map_every_element(m, base, param_layout, exact):
+    """Stochastic gradient push with a column-stochastic P that is not doubly
+    stochastic (Algorithm C.1): a seeded random in-neighbour map after every
+    local step.  Replicas, push-sum weights and de-biased parameters against
+    the oracle; the weights return to 1 at an exact average and keep moving
+    without one (Section 6)."""
+    import torch
+    w = dataclasses.replace(W.ragged_mini(base=base, m=m, policy="maintain"), mix="random",
+                            tau=4, rounds=2, exact_average=exact)
+    prob = _problem(w, ring=2, param_layout=param_layout, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    precs = ("f64", "f32")
+    os_ = {p: PU.make_oracle(w, idx, p) for p in precs}
+    z = [[torch.full_like(t, float("nan")) for t in prob.params[i]] for i in range(m)]
+    step = 0
+    moved = False
+    for t in range(w.rounds):
+        for k in range(w.tau):
+            prob.fill_grads(step % 2, step)
+            opt.local_step(prob.grads[step % 2], w.lr)
+            peers = W.in_peers(w, step)
+            opt.mix_step(peers.tolist())
+            g = PU.oracle_grads(w, idx, step)
+            for o in os_.values():
+                o.local_step(g, w.f32("lr"))
+                o.mix_step(peers)
+            step += 1
+            wg = np.asarray(opt.pushsum_weights(), np.float32)
+            assert np.array_equal(wg, os_["f32"].w), (t, k)
+            np.testing.assert_allclose(wg.sum(), m, rtol=1e-6)      # P is column-stochastic
+            moved = moved or bool(np.any(wg != 1))
+            opt.debias(z)
+            got_x = np.stack([prob.gather(prob.params[i], idx) for i in range(m)])
+            got_z = np.stack([prob.gather(z[i], idx) for i in range(m)])
+            PU.assert_params_close(got_x, os_["f64"].x, f"replicas after gossip step {step}")
+            PU.assert_params_close(got_z, os_["f64"].debiased(), f"de-biased parameters, step {step}")
+            if base == "sgd_nesterov":
+                assert np.array_equal(got_x, os_["f32"].x), (t, k)
+                assert np.array_equal(got_z, os_["f32"].debiased()), (t, k)
+        opt.outer_step(w.lr)
+        for o in os_.values():
+            o.outer_step(w.f32("lr"))
+        wg = np.asarray(opt.pushsum_weights(), np.float32)
+        assert np.array_equal(wg, os_["f32"].w)
+        assert exact == bool(np.all(wg == 1)) or m == 1
+    assert moved or m == 1
+    final = PU.gpu_state(w, prob, opt, idx)
+    PU.assert_params_close(final["x"], os_["f64"].x, "replicas after the run")
+    PU.assert_u_close(final["u"], os_["f64"].u, w.f32("lr"), "u after the run")
+    if base == "sgd_nesterov":
+        assert np.array_equal(final["x"], os_["f32"].x)
+        assert np.array_equal(final["u"], os_["f32"].u)
+    opt.close()
+
+
+def test_push_sum_weights_survive_export_and_import():
+    w = dataclasses.replace(W.ragged_mini(m=7, policy="maintain"), mix="random", tau=3, rounds=1)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    prob.fill_grads(0, 0)
+    opt.local_step(prob.grads[0], w.lr)
+    opt.mix_step(W.in_peers(w, 0).tolist())
+    opt.mix_step(W.in_peers(w, 1).tolist())
+    want = opt.pushsum_weights()
+    assert any(v != 1 for v in want)
+    blob = opt.export_state()
+    opt.mix_step(W.in_peers(w, 2).tolist())
+    assert opt.pushsum_weights() != want
+    opt.import_state(blob)
+    assert opt.pushsum_weights() == want
     opt.close()
 
 
@@ -447,8 +528,9 @@ def test_random_configurations(seed):
     exact = seed % 4 != 3                   # every fourth draw: no exact average (Section 6)
     if not exact and policy == "average":
         policy = "maintain"
-    mix = "expgraph" if rng.integers(0, 3) == 0 else "none"     # also without the exact average:
-    # gossip as the only exchange is the SGP-SlowMo-noaverage variant of Section 6
+    # gossip (one-peer exponential graph, or any in-neighbour map) also without the exact
+    # average: as the only exchange it is the SGP-SlowMo-noaverage variant of Section 6
+    mix = ("expgraph", "random", "none", "none", "none", "none")[int(rng.integers(0, 6))]
     groups = bool(rng.integers(0, 2))
     w = Workload = dataclasses.replace(
         W.ragged_mini(base=base, grad_dtype=str(rng.choice(["f32", "bf16"])), policy=policy,
