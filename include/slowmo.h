@@ -197,26 +197,32 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
 slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream);
 
 /*
- * Inspection: the order in which slowmo_mix_step updates the replicas in place
- * for a map that is not a permutation (a permutation takes a shorter path with
- * the same results).  Entry e sets, per element,
- *   TREE        x[worker] <- keep * x[worker] + take * x[source]
- *   ROOT        x[worker] <- keep * x[worker]
- *   CYCLE_FIRST / CYCLE_NEXT: consecutive entries form a cycle; each worker's
- *               source is the next entry's worker and the last one's source is
- *               the first; all of them use the values from before the step.
- * The order is valid if every worker comes before its source, except inside a
- * cycle.  Idle workers (no sender, no receiver) have no entry.
+ * Inspection: the order in which slowmo_mix_step updates the replicas in
+ * place.  Entry e sets, per element,
+ *     x[worker] <- keep * own + take * src       (keep * own with NO_SOURCE)
+ * where own and src are the values x[worker] and x[source] had BEFORE the
+ * step.  They are read from memory unless a flag says that the kernel still
+ * holds them: OWN_HELD / SOURCE_HELD -- the operand is the source operand of
+ * the closest earlier entry that has one; SOURCE_IS_FIRST -- the operand is
+ * the own operand of the closest earlier entry flagged OPENS_CYCLE.  The order
+ * is valid if no entry reads from memory a worker that an earlier entry has
+ * written.  Idle workers (no sender, no receiver) have no entry.
  * Writes at most m entries to `out` (host) and returns their number, or -1
  * for bad arguments.  Host-only.
  */
-enum { SLOWMO_MIX_TREE = 0, SLOWMO_MIX_ROOT = 1, SLOWMO_MIX_CYCLE_FIRST = 2, SLOWMO_MIX_CYCLE_NEXT = 3 };
+enum {
+  SLOWMO_MIX_OWN_HELD = 1,
+  SLOWMO_MIX_SOURCE_HELD = 2,
+  SLOWMO_MIX_SOURCE_IS_FIRST = 4,
+  SLOWMO_MIX_OPENS_CYCLE = 8,
+  SLOWMO_MIX_NO_SOURCE = 16
+};
 typedef struct slowmo_mix_entry {
   int32_t worker;
   int32_t source;
   float keep;      /* p(worker, worker) */
   float take;      /* p(worker, source) */
-  int32_t kind;    /* SLOWMO_MIX_* */
+  int32_t flags;   /* SLOWMO_MIX_* bits */
   int32_t reserved;
 } slowmo_mix_entry;
 int32_t slowmo_plan_mix(int32_t m, const int32_t *in_peer, slowmo_mix_entry *out);

@@ -35,12 +35,13 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix"]
 
 
-SLOWMO_MIX_TREE, SLOWMO_MIX_ROOT, SLOWMO_MIX_CYCLE_FIRST, SLOWMO_MIX_CYCLE_NEXT = 0, 1, 2, 3
+(SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
+ SLOWMO_MIX_NO_SOURCE) = 1, 2, 4, 8, 16
 
 
 class slowmo_mix_entry(C.Structure):
     _fields_ = [("worker", C.c_int32), ("source", C.c_int32), ("keep", C.c_float),
-                ("take", C.c_float), ("kind", C.c_int32), ("reserved", C.c_int32)]
+                ("take", C.c_float), ("flags", C.c_int32), ("reserved", C.c_int32)]
 
 
 class slowmo_config(C.Structure):
@@ -193,14 +194,14 @@ def slowmo_mix_step(ctx, in_peer: Sequence[int], stream: int = 0) -> None:
 
 def slowmo_plan_mix(in_peer: Sequence[int]):
     """The in-place update order of a mixing step: a list of
-    (worker, source, keep, take, kind); None for bad arguments."""
+    (worker, source, keep, take, flags); None for bad arguments."""
     m = len(in_peer)
     arr = (C.c_int32 * max(m, 1))(*[int(v) for v in in_peer])
     out = (slowmo_mix_entry * max(m, 1))()
     n = lib().slowmo_plan_mix(m, arr, out)
     if n < 0:
         return None
-    return [(out[i].worker, out[i].source, out[i].keep, out[i].take, out[i].kind)
+    return [(out[i].worker, out[i].source, out[i].keep, out[i].take, out[i].flags)
             for i in range(n)]
 
 

@@ -27,8 +27,7 @@ thread_local std::string g_err = "";
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// One slot of the mixing-table ring holds either the worker sequence of a
-// permutation (m int32) or the entries of a general map (m MixEntry).
+// One slot of the mixing-table ring holds the entries of one mixing step.
 size_t mixtab_bytes(int32_t m) { return static_cast<size_t>(m) * sizeof(MixEntry); }
 // One slot of the de-bias ring: m * n_tensors destination pointers, then the m weights.
 size_t ztab_bytes(int32_t m, int32_t n_tensors) {
@@ -182,7 +181,7 @@ struct slowmo_ctx {
 
   TableRing gtab;    // gradient pointers of the current call (m * n_tensors)
   std::vector<const void *> last_grads;  // contents of gtab's current slot
-  TableRing mixtab;  // worker sequence of the current mixing step (m entries)
+  TableRing mixtab;  // update order of the current mixing step (at most m entries)
   TableRing ztab;    // destination pointers and weights of the current de-bias call
   std::vector<float> w;  // push-sum weights (Algorithm C.1), 1 after every exact average
   std::vector<SlotInfo> slots;      // host copies of the per-slot / per-tensor tables
@@ -640,47 +639,18 @@ slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer
 
 namespace {
 
-// Mixing step for a map in which every worker sends to exactly one other
-// worker or to nobody and receives likewise: all weights are 1/2.
-slowmo_status mix_permutation(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
-  const int32_t m = ctx->cfg.m;
-  // Workers listed cycle by cycle, each followed by the worker it receives
-  // from; bit 30 marks the first worker of a cycle.  Fixed points are idle.
-  std::vector<int32_t> seq;
-  std::vector<char> done(m, 0);
-  for (int32_t i = 0; i < m; ++i) {
-    if (done[i] || in_peer[i] == i) continue;
-    bool first = true;
-    for (int32_t j = i; !done[j]; j = in_peer[j]) {
-      done[j] = 1;
-      seq.push_back(first ? (j | kMixCycleStart) : j);
-      first = false;
-    }
-  }
-  if (seq.empty() || ctx->n_otiles == 0) return SLOWMO_OK;
-  hipError_t e = hipSuccess;
-  const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(int32_t), stream, &e);
-  if (slot < 0) return fail_hip(ctx, e, "upload of the mixing sequence");
-  MixArgs a{};
-  a.tiles = ctx->d_otiles;
-  a.tensors = ctx->d_tensors;
-  a.xtab_t = ctx->d_xtab_t;
-  a.ntiles = ctx->n_otiles;
-  a.m = m;
-  a.seq = static_cast<const int32_t *>(ctx->mixtab.d[slot]);
-  a.len = static_cast<int32_t>(seq.size());
-  e = launch_mix_step(a, ctx->tune, stream);
-  if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
-  return SLOWMO_OK;
-}
-
 // Mixing step for any map with at most one in-neighbour per worker.  A sender
 // j splits its mass evenly over itself and its outdeg(j) receivers, so
 // p(i,j) = 1 / (1 + outdeg(j)) and P is column-stochastic (Algorithm C.1).
 // The replicas are mixed in place: a worker is overwritten only after every
 // worker that receives from it has been served.  Seen as "i points to
 // in_peer[i]", the map is a forest of trees hanging off cycles and fixed
-// points; the trees go first, deepest workers first, then each cycle.
+// points.  Each tree is listed receivers-first (post-order), a sender's
+// receivers that have receivers of their own before those that have none:
+// then a worker is mostly followed by its source, whose old value the kernel
+// already holds in a register, and receivers of one sender that follow each
+// other share that register.  The cycles come last, each member before its
+// source.
 void build_mix_entries(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
                        std::vector<float> &share) {
   std::vector<int32_t> outdeg(m, 0);
@@ -689,42 +659,80 @@ void build_mix_entries(int32_t m, const int32_t *in_peer, std::vector<MixEntry> 
   share.resize(m);
   for (int32_t j = 0; j < m; ++j) share[j] = 1.0f / static_cast<float>(1 + outdeg[j]);
 
-  // Peel workers nobody receives from, layer by layer: the peeling order is an
-  // order in which each worker precedes its source.  What is left are cycles.
-  std::vector<int32_t> pending = outdeg, order;
-  std::vector<char> peeled(m, 0);
-  order.reserve(m);
+  // which workers lie on a cycle: peel those nobody (left) receives from
+  std::vector<int32_t> pending = outdeg, queue;
+  std::vector<char> in_tree(m, 0);
+  queue.reserve(m);
   for (int32_t i = 0; i < m; ++i)
-    if (pending[i] == 0) order.push_back(i);
-  for (size_t q = 0; q < order.size(); ++q) {
-    const int32_t i = order[q];
-    peeled[i] = 1;
+    if (pending[i] == 0) queue.push_back(i);
+  for (size_t q = 0; q < queue.size(); ++q) {
+    const int32_t i = queue[q];
+    in_tree[i] = 1;
     const int32_t j = in_peer[i];
-    if (j != i && --pending[j] == 0) order.push_back(j);
+    if (j != i && --pending[j] == 0) queue.push_back(j);
   }
+  // receivers of every worker that are tree workers: first those that have
+  // receivers themselves, then those that have none (CSR layout)
+  std::vector<int32_t> start(m + 1, 0), recv(m);
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] != i && in_tree[i]) ++start[in_peer[i] + 1];
+  for (int32_t j = 0; j < m; ++j) start[j + 1] += start[j];
+  {
+    std::vector<int32_t> fill(start.begin(), start.end() - 1);
+    for (int pass = 0; pass < 2; ++pass)
+      for (int32_t i = 0; i < m; ++i)
+        if (in_peer[i] != i && in_tree[i] && (outdeg[i] == 0) == (pass == 1))
+          recv[fill[in_peer[i]]++] = i;
+  }
+
   seq.clear();
   seq.reserve(m);
-  for (int32_t i : order) {
-    const int32_t j = in_peer[i];
-    if (j != i) {
-      seq.push_back({i, j, share[i], share[j], kMixTree, 0});
+  auto emit = [&](int32_t i) {
+    if (in_peer[i] != i) {
+      seq.push_back({i, in_peer[i], share[i], share[in_peer[i]], 0, 0});
     } else if (outdeg[i] > 0) {
-      seq.push_back({i, i, share[i], 0.f, kMixRoot, 0});
+      seq.push_back({i, i, share[i], 0.f, kMixNoSrc, 0});
     }  // else: an idle worker keeps its value
-  }
-  for (int32_t i = 0; i < m; ++i) {
-    if (peeled[i]) continue;
-    bool first = true;
-    for (int32_t j = i; !peeled[j]; j = in_peer[j]) {
-      peeled[j] = 1;
-      seq.push_back({j, in_peer[j], share[j], share[in_peer[j]],
-                     first ? kMixCycleFirst : kMixCycleNext, 0});
-      first = false;
+  };
+  // post-order walk of the trees below every fixed point and every cycle member
+  std::vector<std::pair<int32_t, int32_t>> stack;  // (worker, next receiver to visit)
+  for (int32_t r = 0; r < m; ++r) {
+    const bool root = in_tree[r] ? in_peer[r] == r : true;
+    if (!root) continue;
+    stack.push_back({r, start[r]});
+    while (!stack.empty()) {
+      auto &top = stack.back();
+      if (top.second < start[top.first + 1]) {
+        const int32_t c = recv[top.second++];
+        stack.push_back({c, start[c]});
+      } else {
+        if (in_tree[top.first]) emit(top.first);  // cycle members wait for their cycle
+        stack.pop_back();
+      }
     }
+  }
+  std::vector<char> seen(m, 0);
+  for (int32_t i = 0; i < m; ++i) {
+    if (in_tree[i] || seen[i]) continue;
+    const size_t first = seq.size();
+    for (int32_t j = i; !seen[j]; j = in_peer[j]) {
+      seen[j] = 1;
+      emit(j);
+    }
+    seq[first].flags |= kMixSaveFirst;
+    seq.back().flags |= kMixSrcFromFirst;
+  }
+  // operands that the kernel still holds from the previous entry
+  int32_t held = -1;  // worker whose old value is in the kernel's source register
+  for (MixEntry &e : seq) {
+    if (e.node == held) e.flags |= kMixOwnFromS;
+    if (e.flags & kMixNoSrc) continue;
+    if (e.src == held && !(e.flags & kMixSrcFromFirst)) e.flags |= kMixSrcFromS;
+    held = e.src;
   }
 }
 
-slowmo_status mix_general(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
+slowmo_status launch_mix(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
   const int32_t m = ctx->cfg.m;
   std::vector<MixEntry> seq;
   std::vector<float> share;
@@ -733,7 +741,7 @@ slowmo_status mix_general(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t s
     hipError_t e = hipSuccess;
     const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
     if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
-    MixGeneralArgs a{};
+    MixArgs a{};
     a.tiles = ctx->d_otiles;
     a.tensors = ctx->d_tensors;
     a.xtab_t = ctx->d_xtab_t;
@@ -741,7 +749,7 @@ slowmo_status mix_general(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t s
     a.m = m;
     a.seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
     a.len = static_cast<int32_t>(seq.size());
-    e = launch_mix_general(a, ctx->tune, stream);
+    e = launch_mix_step(a, ctx->tune, stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
   }
   return SLOWMO_OK;
@@ -753,17 +761,11 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
   if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
   const int32_t m = ctx->cfg.m;
-  std::vector<char> hit(m, 0);
-  bool permutation = true;
-  for (int32_t i = 0; i < m; ++i) {
+  for (int32_t i = 0; i < m; ++i)
     if (in_peer[i] < 0 || in_peer[i] >= m)
       return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
-    if (hit[in_peer[i]]) permutation = false;
-    hit[in_peer[i]] = 1;
-  }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const slowmo_status st =
-      permutation ? mix_permutation(ctx, in_peer, stream) : mix_general(ctx, in_peer, stream);
+  const slowmo_status st = launch_mix(ctx, in_peer, stream);
   if (st != SLOWMO_OK) return st;
   // the push-sum weights mix with the same P, in the same arithmetic as the replicas
   std::vector<int32_t> outdeg(m, 0);
@@ -789,7 +791,7 @@ int32_t slowmo_plan_mix(int32_t m, const int32_t *in_peer, slowmo_mix_entry *out
   std::vector<float> share;
   build_mix_entries(m, in_peer, seq, share);
   for (size_t i = 0; i < seq.size(); ++i)
-    out[i] = {seq[i].node, seq[i].src, seq[i].a, seq[i].b, seq[i].kind, 0};
+    out[i] = {seq[i].node, seq[i].src, seq[i].a, seq[i].b, seq[i].flags, 0};
   return static_cast<int32_t>(seq.size());
 }
 

@@ -53,34 +53,29 @@ struct OuterNoAvgArgs {
   float lr, alpha, beta;
 };
 
-// Mixing step of gradient push for a permutation: worker seq[t] receives from
-// worker seq[t+1] (cyclically inside a cycle); both get weight 1/2.
-constexpr int32_t kMixCycleStart = 1 << 30;
-struct MixArgs {
-  const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
-  const TensorInfo *tensors;   // device
-  float *const *xtab_t;        // device: replica pointers, tensor-major
-  int32_t ntiles;
-  int32_t m;
-  const int32_t *seq;          // device: len entries, bit 30 = first worker of a cycle
-  int32_t len;
+// Mixing step of gradient push (any in-neighbour map, column-stochastic weights).  The
+// workers are listed in an order in which every worker comes before the worker
+// it receives from, so that old values are still in memory when they are
+// needed; the members of a cycle follow each other, each before its source,
+// and the last one takes the first one's old value from a register.  Where an
+// operand is the previous entry's source it is taken from a register too.
+enum MixFlag : int32_t {
+  kMixOwnFromS = 1,      // the worker's old value is the previous entry's source value
+  kMixSrcFromS = 2,      // same source as the previous entry
+  kMixSrcFromFirst = 4,  // the source is the worker that opened the cycle
+  kMixSaveFirst = 8,     // this worker opens a cycle: keep its old value
+  kMixNoSrc = 16,        // receives from nobody: x <- a * x
 };
-
-// General mixing step (any in-neighbour map, column-stochastic weights): the
-// workers in an order in which every worker comes before the worker it
-// receives from, so that old values are still in memory when they are needed;
-// cycles are closed with the first member's old value, kept in registers.
-enum MixKind : int32_t { kMixTree = 0, kMixRoot = 1, kMixCycleFirst = 2, kMixCycleNext = 3 };
 struct MixEntry {
   int32_t node;    // worker updated by this entry
-  int32_t src;     // worker it receives from (unused for kMixRoot)
+  int32_t src;     // worker it receives from (the worker itself with kMixNoSrc)
   float a;         // p(node, node) = 1 / (1 + outdeg(node))
   float b;         // p(node, src)  = 1 / (1 + outdeg(src))
-  int32_t kind;    // MixKind
+  int32_t flags;   // MixFlag bits
   int32_t pad_;
 };
 static_assert(sizeof(MixEntry) == 24, "MixEntry layout");
-struct MixGeneralArgs {
+struct MixArgs {
   const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
   const TensorInfo *tensors;   // device
   float *const *xtab_t;        // device: replica pointers, tensor-major
@@ -122,8 +117,7 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipSt
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
                                    int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &tune, hipStream_t stream);
-hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
-hipError_t launch_mix_general(const MixGeneralArgs &a, const LaunchTuning &tune,
+hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune,
                               hipStream_t stream);
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,

@@ -4,7 +4,8 @@
 // k_outer_step         lines 6-8 + copy into every replica (+ "average" buffer strategy)
 // k_local_outer_step   the last local step of an outer iteration fused with the outer step
 // k_outer_noavg        lines 7-8 per worker, without line 6 (Section 6)
-// k_mix_step           mixing step of stochastic gradient push (Algorithm C.1)
+// k_mix_step        mixing step of stochastic gradient push (Algorithm C.1)
+// k_debias             de-biased parameters of stochastic gradient push (Algorithm C.1)
 //
 // All of them are pure streams: every byte is read once and written once, no
 // element is reused, so there is no dense contraction and the matrix cores are
@@ -515,86 +516,29 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
 }
 
 // ---- mixing step of stochastic gradient push (Algorithm C.1) ---------------------
-// x^{(i)} <- (x^{(i)} + x^{(in_peer(i))}) / 2 for a permutation in_peer, in
-// place.  The workers are visited cycle by cycle in the order "receiver, then
-// its sender": a worker's new value needs its own old value (held in a
-// register) and the next worker's (loaded next), so every replica is loaded
-// once and stored once; the cycle closes with the first worker's old value.
-// One workgroup = 256 elements of one tensor, all workers.
-constexpr int kMixBatch = 8;
+// x^{(i)} <- p(i,i) x^{(i)} + p(i,j) x^{(j)}, j = in_peer(i), in place; one
+// workgroup = 256 elements of one tensor, all workers.  See MixEntry.  Every entry overwrites one worker
+// with a * own + b * src, both operands being values from before the step.
+// An operand that the previous entry already loaded (it is the previous
+// entry's source) or that opened the current cycle is taken from a register
+// instead of memory, so a replica is read once unless a sender has several
+// receivers that are not neighbours in the order.  The loads of a batch of
+// entries are issued together; all of them read old values, which stay in
+// memory until their own entry comes, so issuing them early is safe.  Plain
+// (cached) loads for the source operand measured faster than non-temporal ones.
+#ifndef SLOWMO_MIX_BATCH
+#define SLOWMO_MIX_BATCH 4
+#endif
+#ifndef SLOWMO_MIX_OWN_NT
+#define SLOWMO_MIX_OWN_NT 1
+#endif
+#ifndef SLOWMO_MIX_SRC_NT
+#define SLOWMO_MIX_SRC_NT 0
+#endif
+constexpr int kMixBatch = SLOWMO_MIX_BATCH;
 
 template <bool NT>
 __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
-    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
-    float *const *__restrict__ xtab_t, const int32_t *__restrict__ seq, int len, int ntiles,
-    int chunk, int remap, int m) {
-  const int tile = tile_of(blockIdx.x, chunk, remap);
-  if (tile >= ntiles) return;
-  const TileRef t = tiles[tile];
-  const TensorInfo ti = tensors[t.owner];
-  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
-  const int64_t left = ti.numel - eo;
-  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
-  const int e0 = 4 * static_cast<int>(threadIdx.x);
-  if (e0 >= n) return;
-  if (ti.unaligned == 0 && e0 + 4 <= n) {
-    V4 first = {0.f, 0.f, 0.f, 0.f}, cur = first;
-    float *prev = nullptr;
-    for (int base = 0; base < len; base += kMixBatch) {
-      V4 v[kMixBatch];
-      float *ptr[kMixBatch];
-#pragma unroll
-      for (int q = 0; q < kMixBatch; ++q) {
-        if (base + q < len) {
-          ptr[q] = xp[seq[base + q] & ~kMixCycleStart] + eo + e0;
-          v[q] = ld4<NT>(ptr[q]);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < kMixBatch; ++q) {
-        if (base + q < len) {
-          const bool start = (seq[base + q] & kMixCycleStart) != 0;
-          if (start) {
-            if (prev) st4<NT>(prev, 0.5f * cur + 0.5f * first);
-            first = v[q];
-          } else {
-            st4<NT>(prev, 0.5f * cur + 0.5f * v[q]);
-          }
-          cur = v[q];
-          prev = ptr[q];
-        }
-      }
-    }
-    if (prev) st4<NT>(prev, 0.5f * cur + 0.5f * first);
-  } else {
-    const int e1 = e0 + 4 < n ? e0 + 4 : n;
-    for (int j = e0; j < e1; ++j) {
-      float first = 0.f, cur = 0.f;
-      float *prev = nullptr;
-      for (int i = 0; i < len; ++i) {
-        const int s = seq[i];
-        float *ptr = xp[s & ~kMixCycleStart] + eo + j;
-        const float v = ld1(ptr);
-        if (s & kMixCycleStart) {
-          if (prev) st1(prev, 0.5f * cur + 0.5f * first);
-          first = v;
-        } else {
-          st1(prev, 0.5f * cur + 0.5f * v);
-        }
-        cur = v;
-        prev = ptr;
-      }
-      if (prev) st1(prev, 0.5f * cur + 0.5f * first);
-    }
-  }
-}
-
-// General in-neighbour map: see MixEntry.  One entry at a time (a worker's
-// source is read a second time when its own entry comes; that read normally
-// hits in L2, so plain loads are used for it).
-template <bool NT>
-__global__ __launch_bounds__(kOuterBlock) void k_mix_general(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, const MixEntry *__restrict__ seq, int len, int ntiles,
     int chunk, int remap, int m) {
@@ -609,59 +553,59 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_general(
   const int e0 = 4 * static_cast<int>(threadIdx.x);
   if (e0 >= n) return;
   if (ti.unaligned == 0 && e0 + 4 <= n) {
-    V4 first = {0.f, 0.f, 0.f, 0.f}, cur = first;
-    float a_prev = 0.f, b_prev = 0.f;
-    float *prev = nullptr;
-    for (int i = 0; i < len; ++i) {
-      const MixEntry en = seq[i];
-      float *ptr = xp[en.node] + eo + e0;
-      if (en.kind == kMixTree) {
-        V4 xi = ld4<NT>(ptr), xs = ld4<false>(xp[en.src] + eo + e0);
-        st4<NT>(ptr, en.a * xi + en.b * xs);
-      } else if (en.kind == kMixRoot) {
-        st4<NT>(ptr, en.a * ld4<NT>(ptr));
-      } else {
-        V4 v = ld4<NT>(ptr);
-        if (en.kind == kMixCycleFirst) {
-          if (prev) st4<NT>(prev, a_prev * cur + b_prev * first);
-          first = v;
-        } else {
-          st4<NT>(prev, a_prev * cur + b_prev * v);
+    V4 S = {0.f, 0.f, 0.f, 0.f}, first = S;
+    for (int base = 0; base < len; base += kMixBatch) {
+      V4 own[kMixBatch], sv[kMixBatch];
+      float *ptr[kMixBatch];
+#pragma unroll
+      for (int q = 0; q < kMixBatch; ++q) {
+        if (base + q < len) {
+          const MixEntry en = seq[base + q];
+          ptr[q] = xp[en.node] + eo + e0;
+          if (!(en.flags & kMixOwnFromS)) own[q] = ld4<NT && SLOWMO_MIX_OWN_NT>(ptr[q]);
+          if (!(en.flags & (kMixSrcFromS | kMixSrcFromFirst | kMixNoSrc)))
+            sv[q] = ld4<NT && SLOWMO_MIX_SRC_NT>(xp[en.src] + eo + e0);
         }
-        cur = v;
-        prev = ptr;
-        a_prev = en.a;
-        b_prev = en.b;
+      }
+#pragma unroll
+      for (int q = 0; q < kMixBatch; ++q) {
+        if (base + q < len) {
+          const MixEntry en = seq[base + q];
+          const V4 o = (en.flags & kMixOwnFromS) ? S : own[q];
+          if (en.flags & kMixSaveFirst) first = o;
+          if (en.flags & kMixNoSrc) {
+            st4<NT>(ptr[q], en.a * o);
+          } else {
+            if (en.flags & kMixSrcFromFirst) {
+              S = first;
+            } else if (!(en.flags & kMixSrcFromS)) {
+              S = sv[q];
+            }
+            st4<NT>(ptr[q], en.a * o + en.b * S);
+          }
+        }
       }
     }
-    if (prev) st4<NT>(prev, a_prev * cur + b_prev * first);
   } else {
     const int e1 = e0 + 4 < n ? e0 + 4 : n;
     for (int j = e0; j < e1; ++j) {
-      float first = 0.f, cur = 0.f, a_prev = 0.f, b_prev = 0.f;
-      float *prev = nullptr;
+      float S = 0.f, first = 0.f;
       for (int i = 0; i < len; ++i) {
         const MixEntry en = seq[i];
         float *ptr = xp[en.node] + eo + j;
-        if (en.kind == kMixTree) {
-          st1(ptr, en.a * ld1(ptr) + en.b * ld1(xp[en.src] + eo + j));
-        } else if (en.kind == kMixRoot) {
-          st1(ptr, en.a * ld1(ptr));
+        const float o = (en.flags & kMixOwnFromS) ? S : ld1(ptr);
+        if (en.flags & kMixSaveFirst) first = o;
+        if (en.flags & kMixNoSrc) {
+          st1(ptr, en.a * o);
         } else {
-          const float v = ld1(ptr);
-          if (en.kind == kMixCycleFirst) {
-            if (prev) st1(prev, a_prev * cur + b_prev * first);
-            first = v;
-          } else {
-            st1(prev, a_prev * cur + b_prev * v);
+          if (en.flags & kMixSrcFromFirst) {
+            S = first;
+          } else if (!(en.flags & kMixSrcFromS)) {
+            S = ld1(xp[en.src] + eo + j);
           }
-          cur = v;
-          prev = ptr;
-          a_prev = en.a;
-          b_prev = en.b;
+          st1(ptr, en.a * o + en.b * S);
         }
       }
-      if (prev) st1(prev, a_prev * cur + b_prev * first);
     }
   }
 }
@@ -828,19 +772,6 @@ hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t 
                        a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
   } else {
     hipLaunchKernelGGL((k_mix_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
-  }
-  return hipGetLastError();
-}
-
-hipError_t launch_mix_general(const MixGeneralArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
-  if (t.nontemporal) {
-    hipLaunchKernelGGL((k_mix_general<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
-  } else {
-    hipLaunchKernelGGL((k_mix_general<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
                        a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
   }
   return hipGetLastError();

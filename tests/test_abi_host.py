@@ -204,34 +204,35 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
                                 m, d, peers.ctypes.data_as(C.c_void_p))
             got = x.copy()
             seen = set()
-            i = 0
-            while i < len(plan):
-                worker, source, keep, take, kind_e = plan[i]
+            held = first = None          # what the kernel keeps in registers
+            loads = 0
+            for worker, source, keep, take, flags in plan:
                 keep, take = f32(keep), f32(take)
                 assert worker not in seen
-                if kind_e == B.SLOWMO_MIX_TREE:
-                    assert source == peers[worker] != worker and source not in seen
-                    got[worker] = keep * got[worker] + take * got[source]
-                    seen.add(worker)
-                    i += 1
-                elif kind_e == B.SLOWMO_MIX_ROOT:
-                    assert peers[worker] == worker
-                    got[worker] = keep * got[worker]
-                    seen.add(worker)
-                    i += 1
+                if flags & B.SLOWMO_MIX_OWN_HELD:
+                    own = held
                 else:
-                    assert kind_e == B.SLOWMO_MIX_CYCLE_FIRST
-                    j = i + 1
-                    while j < len(plan) and plan[j][4] == B.SLOWMO_MIX_CYCLE_NEXT:
-                        j += 1
-                    cyc = plan[i:j]
-                    old = [got[e[0]].copy() for e in cyc]
-                    for q, e in enumerate(cyc):
-                        nxt = (q + 1) % len(cyc)
-                        assert e[1] == peers[e[0]] == cyc[nxt][0] and e[0] not in seen
-                        got[e[0]] = f32(e[2]) * old[q] + f32(e[3]) * old[nxt]
-                    seen.update(e[0] for e in cyc)
-                    i = j
+                    own = got[worker].copy()
+                    loads += 1
+                if flags & B.SLOWMO_MIX_OPENS_CYCLE:
+                    first = own
+                if flags & B.SLOWMO_MIX_NO_SOURCE:
+                    assert peers[worker] == worker
+                    got[worker] = keep * own
+                else:
+                    assert source == peers[worker] != worker
+                    if flags & B.SLOWMO_MIX_SOURCE_IS_FIRST:
+                        held = first
+                    elif not flags & B.SLOWMO_MIX_SOURCE_HELD:
+                        assert source not in seen       # memory still holds the old value
+                        held = got[source].copy()
+                        loads += 1
+                    got[worker] = keep * own + take * held
+                seen.add(worker)
+            if kind in ("perm", "chain"):   # nothing is read twice
+                assert loads == len(plan)
+            if kind == "star" and m > 1:    # the sender is read once for all its receivers
+                assert loads == m
             np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
             # workers without an entry are idle: nobody sends to or receives from them
             for i in set(range(m)) - seen:
