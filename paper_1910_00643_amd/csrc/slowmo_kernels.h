@@ -53,28 +53,6 @@ struct OuterNoAvgArgs {
   float lr, alpha, beta;
 };
 
-// Mixing step of gradient push (any in-neighbour map, column-stochastic weights).  The
-// workers are listed in an order in which every worker comes before the worker
-// it receives from, so that old values are still in memory when they are
-// needed; the members of a cycle follow each other, each before its source,
-// and the last one takes the first one's old value from a register.  Where an
-// operand is the previous entry's source it is taken from a register too.
-enum MixFlag : int32_t {
-  kMixOwnFromS = 1,      // the worker's old value is the previous entry's source value
-  kMixSrcFromS = 2,      // same source as the previous entry
-  kMixSrcFromFirst = 4,  // the source is the worker that opened the cycle
-  kMixSaveFirst = 8,     // this worker opens a cycle: keep its old value
-  kMixNoSrc = 16,        // receives from nobody: x <- a * x
-};
-struct MixEntry {
-  int32_t node;    // worker updated by this entry
-  int32_t src;     // worker it receives from (the worker itself with kMixNoSrc)
-  float a;         // p(node, node) = 1 / (1 + outdeg(node))
-  float b;         // p(node, src)  = 1 / (1 + outdeg(src))
-  int32_t flags;   // MixFlag bits
-  int32_t pad_;
-};
-static_assert(sizeof(MixEntry) == 24, "MixEntry layout");
 struct MixArgs {
   const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
   const TensorInfo *tensors;   // device

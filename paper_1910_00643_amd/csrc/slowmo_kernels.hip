@@ -416,6 +416,9 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
   if (e0 >= n) return;
   if (e0 + 4 <= n) {
     V4 acc, acch, accv;
+#ifndef SLOWMO_FUSED_NTL
+#define SLOWMO_FUSED_NTL 1
+#endif
 #ifndef SLOWMO_FUSED_UNROLL
 #define SLOWMO_FUSED_UNROLL 8
 #endif
@@ -425,10 +428,10 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
       float *hi = h0 + i * d_pad + e0;
       float *vi = BASE == 1 ? v0 + i * d_pad + e0 : nullptr;
       const void *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
-      V4 xv = ld4<NT>(xi), hv, vv;
-      if constexpr (!FIRST) hv = ld4<NT>(hi);
-      if constexpr (!FIRST && BASE == 1) vv = ld4<NT>(vi);
-      V4 gv = ldg4<BF16, NT>(gi, threadIdx.x);
+      V4 xv = ld4<NT && SLOWMO_FUSED_NTL>(xi), hv, vv;
+      if constexpr (!FIRST) hv = ld4<NT && SLOWMO_FUSED_NTL>(hi);
+      if constexpr (!FIRST && BASE == 1) vv = ld4<NT && SLOWMO_FUSED_NTL>(vi);
+      V4 gv = ldg4<BF16, NT && SLOWMO_FUSED_NTL>(gi, threadIdx.x);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         float xe = xv[c], he = FIRST ? 0.f : hv[c];

@@ -58,4 +58,97 @@ void plan_outer(int32_t n_tensors, const int64_t *numel, std::vector<PlanRun> &r
   cut(-1, n_tensors, numel, kOuterTile, runs);
 }
 
+// Mixing step for any map with at most one in-neighbour per worker.  A sender
+// j splits its mass evenly over itself and its outdeg(j) receivers, so
+// p(i,j) = 1 / (1 + outdeg(j)) and P is column-stochastic (Algorithm C.1).
+// The replicas are mixed in place: a worker is overwritten only after every
+// worker that receives from it has been served.  Seen as "i points to
+// in_peer[i]", the map is a forest of trees hanging off cycles and fixed
+// points.  Each tree is listed receivers-first (post-order), a sender's
+// receivers that have receivers of their own before those that have none:
+// then a worker is mostly followed by its source, whose old value the kernel
+// already holds in a register, and receivers of one sender that follow each
+// other share that register.  The cycles come last, each member before its
+// source.
+void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
+                       std::vector<float> &share) {
+  std::vector<int32_t> outdeg(m, 0);
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] != i) ++outdeg[in_peer[i]];
+  share.resize(m);
+  for (int32_t j = 0; j < m; ++j) share[j] = 1.0f / static_cast<float>(1 + outdeg[j]);
+
+  // which workers lie on a cycle: peel those nobody (left) receives from
+  std::vector<int32_t> pending = outdeg, queue;
+  std::vector<char> in_tree(m, 0);
+  queue.reserve(m);
+  for (int32_t i = 0; i < m; ++i)
+    if (pending[i] == 0) queue.push_back(i);
+  for (size_t q = 0; q < queue.size(); ++q) {
+    const int32_t i = queue[q];
+    in_tree[i] = 1;
+    const int32_t j = in_peer[i];
+    if (j != i && --pending[j] == 0) queue.push_back(j);
+  }
+  // receivers of every worker that are tree workers: first those that have
+  // receivers themselves, then those that have none (CSR layout)
+  std::vector<int32_t> start(m + 1, 0), recv(m);
+  for (int32_t i = 0; i < m; ++i)
+    if (in_peer[i] != i && in_tree[i]) ++start[in_peer[i] + 1];
+  for (int32_t j = 0; j < m; ++j) start[j + 1] += start[j];
+  {
+    std::vector<int32_t> fill(start.begin(), start.end() - 1);
+    for (int pass = 0; pass < 2; ++pass)
+      for (int32_t i = 0; i < m; ++i)
+        if (in_peer[i] != i && in_tree[i] && (outdeg[i] == 0) == (pass == 1))
+          recv[fill[in_peer[i]]++] = i;
+  }
+
+  seq.clear();
+  seq.reserve(m);
+  auto emit = [&](int32_t i) {
+    if (in_peer[i] != i) {
+      seq.push_back({i, in_peer[i], share[i], share[in_peer[i]], 0, 0});
+    } else if (outdeg[i] > 0) {
+      seq.push_back({i, i, share[i], 0.f, kMixNoSrc, 0});
+    }  // else: an idle worker keeps its value
+  };
+  // post-order walk of the trees below every fixed point and every cycle member
+  std::vector<std::pair<int32_t, int32_t>> stack;  // (worker, next receiver to visit)
+  for (int32_t r = 0; r < m; ++r) {
+    const bool root = in_tree[r] ? in_peer[r] == r : true;
+    if (!root) continue;
+    stack.push_back({r, start[r]});
+    while (!stack.empty()) {
+      auto &top = stack.back();
+      if (top.second < start[top.first + 1]) {
+        const int32_t c = recv[top.second++];
+        stack.push_back({c, start[c]});
+      } else {
+        if (in_tree[top.first]) emit(top.first);  // cycle members wait for their cycle
+        stack.pop_back();
+      }
+    }
+  }
+  std::vector<char> seen(m, 0);
+  for (int32_t i = 0; i < m; ++i) {
+    if (in_tree[i] || seen[i]) continue;
+    const size_t first = seq.size();
+    for (int32_t j = i; !seen[j]; j = in_peer[j]) {
+      seen[j] = 1;
+      emit(j);
+    }
+    seq[first].flags |= kMixSaveFirst;
+    seq.back().flags |= kMixSrcFromFirst;
+  }
+  // operands that the kernel still holds from the previous entry
+  int32_t held = -1;  // worker whose old value is in the kernel's source register
+  for (MixEntry &e : seq) {
+    if (e.node == held) e.flags |= kMixOwnFromS;
+    if (e.flags & kMixNoSrc) continue;
+    if (e.src == held && !(e.flags & kMixSrcFromFirst)) e.flags |= kMixSrcFromS;
+    held = e.src;
+  }
+}
+
 }  // namespace slowmo

@@ -71,6 +71,33 @@ struct PlanRun {  // host description of a tile (mirrors slowmo_plan_run)
   int64_t offset;
 };
 
+// Mixing step of gradient push (any in-neighbour map, column-stochastic weights).  The
+// workers are listed in an order in which every worker comes before the worker
+// it receives from, so that old values are still in memory when they are
+// needed; the members of a cycle follow each other, each before its source,
+// and the last one takes the first one's old value from a register.  Where an
+// operand is the previous entry's source it is taken from a register too.
+enum MixFlag : int32_t {
+  kMixOwnFromS = 1,      // the worker's old value is the previous entry's source value
+  kMixSrcFromS = 2,      // same source as the previous entry
+  kMixSrcFromFirst = 4,  // the source is the worker that opened the cycle
+  kMixSaveFirst = 8,     // this worker opens a cycle: keep its old value
+  kMixNoSrc = 16,        // receives from nobody: x <- a * x
+};
+struct MixEntry {
+  int32_t node;    // worker updated by this entry
+  int32_t src;     // worker it receives from (the worker itself with kMixNoSrc)
+  float a;         // p(node, node) = 1 / (1 + outdeg(node))
+  float b;         // p(node, src)  = 1 / (1 + outdeg(src))
+  int32_t flags;   // MixFlag bits
+  int32_t pad_;
+};
+static_assert(sizeof(MixEntry) == 24, "MixEntry layout");
+// The update order of one mixing step for the in-neighbour map in_peer (m
+// entries in 0..m-1); share[j] = 1 / (1 + outdeg(j)).
+void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
+              std::vector<float> &share);
+
 Layout make_layout(int32_t n_tensors, const int64_t *numel);
 
 // Number of tiles of each kind (no allocation).
