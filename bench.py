@@ -69,13 +69,15 @@ def fusable(w) -> bool:
     return w.exact_average and w.mix == "none"
 
 
-def round_bytes(w, fused: bool = False) -> int:
+def round_bytes(w, fused: bool = False, fused_mix: bool = False) -> int:
     """Algorithmic HBM bytes of one outer iteration as it is executed."""
     reset = w.policy == "reset"
     steps = range(w.tau - 1) if fused else range(w.tau)
-    per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0, reset and k == w.tau - 1)
+    # the fused local+gossip kernel always stores the buffers
+    per_worker_elem = sum(local_bytes_per_update(w, reset and k == 0,
+                                                 reset and k == w.tau - 1 and not fused_mix)
                           for k in steps)
-    if w.mix != "none":         # every replica read and written once per gossip step
+    if w.mix != "none" and not fused_mix:   # every replica read and written once per gossip step
         per_worker_elem += 8 * w.tau
     tail = fused_bytes_per_element(w) if fused else outer_bytes_per_element(w)
     return w.d * (w.m * per_worker_elem + tail)
@@ -99,7 +101,7 @@ def build_problem(w, ring):
     return prob, opt
 
 
-def run_rounds(w, opt, arrays, rounds, events=None, fused=False):
+def run_rounds(w, opt, arrays, rounds, events=None, fused=False, fused_mix=False):
     """`rounds` outer iterations.  With `events`, brackets every call with HIP
     events on the stream the kernels are launched on (torch's current one)."""
     import torch
@@ -122,6 +124,16 @@ def run_rounds(w, opt, arrays, rounds, events=None, fused=False):
                     b.record()
                     events["fused_last_outer"].append((a, b))
                 break
+            if peers is not None and fused_mix:     # local step + gossip step, one call
+                if events is not None:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                opt.local_mix_step(arrays[k % ring], w.lr, peers[k % len(peers)])
+                if events is not None:
+                    b.record()
+                    reset = w.policy == "reset"
+                    events["local_mix_first" if (reset and k == 0) else "local_mix"].append((a, b))
+                continue
             if events is not None:
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
@@ -150,21 +162,21 @@ def run_rounds(w, opt, arrays, rounds, events=None, fused=False):
                 events["outer"].append((a, b))
 
 
-def time_workload(w, steps, warmup, ring=None, fused=False):
+def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False):
     import torch
     ring = ring or w.tau
     prob, opt = build_problem(w, ring)
     arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(ring)]
-    run_rounds(w, opt, arrays, warmup, fused=fused)
+    run_rounds(w, opt, arrays, warmup, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_rounds(w, opt, arrays, steps, fused=fused)
+    run_rounds(w, opt, arrays, steps, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     # second pass: per-kernel durations from HIP events around every launch
     events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": [],
-              "fused_last_outer": []}
-    run_rounds(w, opt, arrays, steps, events, fused=fused)
+              "fused_last_outer": [], "local_mix": [], "local_mix_first": []}
+    run_rounds(w, opt, arrays, steps, events, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
                for k, v in events.items()}
@@ -275,11 +287,15 @@ def main():
         del a, b
         torch.cuda.empty_cache()
     fused = fusable(w) and not args.unfused
-    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring, fused=fused)
+    fused_mix = w.mix != "none" and not args.unfused
+    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring, fused=fused, fused_mix=fused_mix)
     ms_per_step = 1e3 * wall / args.steps
     value = w.updates_per_round * args.steps / wall
     local_bytes = local_bytes_per_update(w, False) * w.m * w.d
-    achieved = local_bytes / (kern_ms["local"] * 1e-3) / 1e9
+    # with gossip fused into the local step that kernel is the dominant one: same
+    # algorithmic bytes as a local step (the gossip adds no traffic)
+    dominant = "local_mix" if fused_mix and kern_ms.get("local_mix") else "local"
+    achieved = local_bytes / (kern_ms[dominant] * 1e-3) / 1e9
     out = {
         "metric": "param-element updates/s (m*d*tau per round)",
         "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
@@ -292,17 +308,21 @@ def main():
                                + ("" if w.mix == "none" else f", gossip={w.mix}"),
                    "step": "one outer iteration: tau local steps on all m workers + outer step"
                            + (" (the last local step and the outer step as one fused call)"
-                              if fused else ""),
+                              if fused else "")
+                           + (" (every local step and the gossip step after it as one fused call)"
+                              if fused_mix else ""),
                    "gradient_sets_resident": ring},
-        "hbm_gbps_whole_round": round_bytes(w, fused) / wall * args.steps / 1e9,
-        "hbm_frac_whole_round": round_bytes(w, fused) / wall * args.steps / 1e9 / HBM_PEAK_GBPS,
-        "algorithmic_bytes_per_round": round_bytes(w, fused),
+        "hbm_gbps_whole_round": round_bytes(w, fused, fused_mix) / wall * args.steps / 1e9,
+        "hbm_frac_whole_round": round_bytes(w, fused, fused_mix) / wall * args.steps / 1e9
+                                / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_round": round_bytes(w, fused, fused_mix),
         "kernel_ms": kern_ms,
-        "roofline": {"bound": "hbm", "kernel": "k_local_step (steady state)",
+        "roofline": {"bound": "hbm", "kernel": ("k_local_mix_step (steady state)" if dominant == "local_mix"
+                                                else "k_local_step (steady state)"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": local_bytes,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if dominant == "local" else None},
     }
     if kern_ms.get("outer"):
         ob = outer_bytes_per_element(w) * w.d

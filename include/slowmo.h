@@ -197,6 +197,22 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
 slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream);
 
 /*
+ * A local step and the mixing step that follows it as one call (stochastic
+ * gradient push as base optimizer, Algorithm C.1, runs this pair tau times per
+ * outer iteration): the same results, bit for bit, as
+ *     slowmo_local_step(ctx, grads, lr, stream);
+ *     slowmo_mix_step(ctx, in_peer, stream);
+ * but when every replica and gradient pointer is 16-byte aligned (8 bytes for
+ * bf16 gradients) both run in ONE kernel that keeps the stepped replicas in
+ * registers for the mix: the replicas are read and written once instead of
+ * twice (8 bytes less traffic per worker and element).  Otherwise the two
+ * kernels are launched back to back.
+ * Errors: as for the two calls.
+ */
+slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                    const int32_t *in_peer, void *stream);
+
+/*
  * Inspection: the order in which slowmo_mix_step updates the replicas in
  * place.  Entry e sets, per element,
  *     x[worker] <- keep * own + take * src       (keep * own with NO_SOURCE)

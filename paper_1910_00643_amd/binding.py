@@ -32,7 +32,8 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_plan_local", "slowmo_plan_outer", "slowmo_version", "slowmo_mix_step",
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
            "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step",
-           "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix"]
+           "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix",
+           "slowmo_local_mix_step"]
 
 
 (SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
@@ -103,6 +104,8 @@ def lib() -> C.CDLL:
     L.slowmo_plan_outer.restype = i64
     L.slowmo_mix_step.argtypes = [vp, C.POINTER(i32), vp]
     L.slowmo_mix_step.restype = C.c_int
+    L.slowmo_local_mix_step.argtypes = [vp, C.POINTER(vp), C.c_float, C.POINTER(i32), vp]
+    L.slowmo_local_mix_step.restype = C.c_int
     L.slowmo_plan_mix.argtypes = [i32, C.POINTER(i32), C.POINTER(slowmo_mix_entry)]
     L.slowmo_plan_mix.restype = C.c_int32
     L.slowmo_get_pushsum_weights.argtypes = [vp, C.POINTER(C.c_float)]
@@ -190,6 +193,14 @@ def slowmo_mix_step(ctx, in_peer: Sequence[int], stream: int = 0) -> None:
     """in_peer: m worker indices; worker i receives from in_peer[i]."""
     arr = (C.c_int32 * len(in_peer))(*[int(v) for v in in_peer]) if in_peer is not None else None
     _check(lib().slowmo_mix_step(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_local_mix_step(ctx, grads, lr: float, in_peer: Sequence[int], stream: int = 0) -> None:
+    """A local step and the mixing step after it in one call."""
+    arr = grads if (grads is None or isinstance(grads, C.Array)) else _ptr_array(grads)
+    peers = (C.c_int32 * len(in_peer))(*[int(v) for v in in_peer]) if in_peer is not None else None
+    _check(lib().slowmo_local_mix_step(ctx, arr, lr, peers,
+                                       C.c_void_p(stream) if stream else None), ctx)
 
 
 def slowmo_plan_mix(in_peer: Sequence[int]):

@@ -310,6 +310,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
   ctx->tune.nontemporal = env_flag("SLOWMO_NT", 1) ? 1 : 0;
   ctx->tune.fuse_last = env_flag("SLOWMO_FUSE_LAST", 1) ? 1 : 0;
+  ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
@@ -664,17 +665,17 @@ slowmo_status launch_mix(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t st
 
 }  // namespace
 
-slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
-  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
-  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+namespace {
+
+bool check_in_peer(const slowmo_ctx *ctx, const int32_t *in_peer) {
+  for (int32_t i = 0; i < ctx->cfg.m; ++i)
+    if (in_peer[i] < 0 || in_peer[i] >= ctx->cfg.m) return false;
+  return true;
+}
+
+// the push-sum weights mix with the same P, in the same arithmetic as the replicas
+void mix_weights(slowmo_ctx *ctx, const int32_t *in_peer) {
   const int32_t m = ctx->cfg.m;
-  for (int32_t i = 0; i < m; ++i)
-    if (in_peer[i] < 0 || in_peer[i] >= m)
-      return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const slowmo_status st = launch_mix(ctx, in_peer, stream);
-  if (st != SLOWMO_OK) return st;
-  // the push-sum weights mix with the same P, in the same arithmetic as the replicas
   std::vector<int32_t> outdeg(m, 0);
   for (int32_t i = 0; i < m; ++i)
     if (in_peer[i] != i) ++outdeg[in_peer[i]];
@@ -686,6 +687,63 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
     w_new[i] = v;
   }
   ctx->w.swap(w_new);
+}
+
+}  // namespace
+
+slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+  if (!check_in_peer(ctx, in_peer))
+    return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
+  const slowmo_status st = launch_mix(ctx, in_peer, static_cast<hipStream_t>(stream_));
+  if (st != SLOWMO_OK) return st;
+  mix_weights(ctx, in_peer);
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, float lr,
+                                    const int32_t *in_peer, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
+  if (!check_in_peer(ctx, in_peer))
+    return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  LocalArgs a{};
+  bool aligned = false;
+  slowmo_status st = prepare_local(ctx, grads, lr, stream, &a, &aligned);
+  if (st != SLOWMO_OK) return st;
+  const slowmo_config &c = ctx->cfg;
+  const bool bf16 = c.grad_dtype == SLOWMO_BF16;
+  if (!aligned || !ctx->params_aligned || !ctx->tune.fuse_mix || ctx->n_otiles == 0) {
+    // same two kernels as the separate calls
+    const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
+    hipError_t e = launch_local_step(a, c.base, bf16, ctx->buffers_zero, dead_after, ctx->tune, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
+    finish_local(ctx);
+    st = launch_mix(ctx, in_peer, stream);
+    if (st != SLOWMO_OK) return st;
+  } else {
+    std::vector<MixEntry> seq;
+    std::vector<float> share;
+    plan_mix(c.m, in_peer, seq, share, /*with_idle=*/true);
+    hipError_t e = hipSuccess;
+    const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
+    if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
+    MixArgs x{};
+    x.tiles = ctx->d_otiles;
+    x.tensors = ctx->d_tensors;
+    x.xtab_t = ctx->d_xtab_t;
+    x.ntiles = ctx->n_otiles;
+    x.m = c.m;
+    x.seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
+    x.len = static_cast<int32_t>(seq.size());
+    e = launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
+                              ctx->buffers_zero, ctx->tune, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "fused local+mixing kernel launch");
+    finish_local(ctx);
+  }
+  mix_weights(ctx, in_peer);
   return SLOWMO_OK;
 }
 

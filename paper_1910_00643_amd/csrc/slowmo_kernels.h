@@ -77,6 +77,7 @@ struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
   int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
+  int32_t fuse_mix;     // 1: slowmo_local_mix_step runs one fused kernel when it can
   int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
                         // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
@@ -97,6 +98,12 @@ hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32
                                    const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune,
                               hipStream_t stream);
+// The local step and the mixing step that follows it in one kernel; x.seq must
+// list EVERY worker (plan_mix with idle workers).  Needs 16-byte aligned
+// replicas and gradient pointers that allow vector loads.
+hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                 int32_t n_tensors, int base, bool bf16, bool first,
+                                 const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
                                    hipStream_t stream);

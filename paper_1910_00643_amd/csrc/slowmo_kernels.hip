@@ -5,6 +5,7 @@
 // k_local_outer_step   the last local step of an outer iteration fused with the outer step
 // k_outer_noavg        lines 7-8 per worker, without line 6 (Section 6)
 // k_mix_step        mixing step of stochastic gradient push (Algorithm C.1)
+// k_local_mix_step     a local step and the mixing step that follows it, fused
 // k_debias             de-biased parameters of stochastic gradient push (Algorithm C.1)
 //
 // All of them are pure streams: every byte is read once and written once, no
@@ -613,6 +614,156 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
   }
 }
 
+// ---- local step + mixing step, fused ---------------------------------------------
+// Stochastic gradient push as base optimizer runs a mixing step after every
+// local step (Algorithm C.1).  Done as two kernels, the replicas are written by
+// the first and read again by the second.  Here one workgroup takes a tile of
+// one tensor through all workers in the mixing order: a worker's base-optimizer
+// step (the arithmetic of k_local_step) is computed when its value is first
+// needed and the stepped x stays in registers for the mix, so x is read once
+// and written once per step (8 bytes per worker and element less).  A worker
+// whose stepped value is needed as a source before its own turn, and is not
+// the next in the order, is stepped again from memory at its own turn: its x,
+// h and v in memory stay untouched until then.
+template <int BASE, bool BF16, bool FIRST, bool NT>
+__device__ __forceinline__ void step_vec4(const float *xi, const float *hi, const float *vi,
+                                          const void *gi, int lane, const SgdP &sp,
+                                          const AdamP &ap, V4 &xv, V4 &hv, V4 &vv) {
+  xv = ld4<NT>(xi);
+  if constexpr (!FIRST) hv = ld4<NT>(hi);
+  if constexpr (!FIRST && BASE == 1) vv = ld4<NT>(vi);
+  const V4 gv = ldg4<BF16, NT>(gi, lane);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    float xe = xv[c], he = FIRST ? 0.f : hv[c];
+    if constexpr (BASE == 0) {
+      sgd_elem<FIRST>(xe, he, gv[c], sp);
+    } else {
+      float ve = FIRST ? 0.f : vv[c];
+      adam_elem<FIRST>(xe, he, ve, gv[c], ap);
+      vv[c] = ve;
+    }
+    xv[c] = xe;
+    hv[c] = he;
+  }
+}
+
+template <int BASE, bool BF16, bool FIRST>
+__device__ __forceinline__ void step_1(const float *xi, const float *hi, const float *vi,
+                                       const void *gi, int j, const SgdP &sp, const AdamP &ap,
+                                       float &xe, float &he, float &ve) {
+  xe = ld1(xi);
+  he = FIRST ? 0.f : ld1(hi);
+  ve = 0.f;
+  const float ge = ldg1<BF16>(gi, j);
+  if constexpr (BASE == 0) {
+    sgd_elem<FIRST>(xe, he, ge, sp);
+  } else {
+    ve = FIRST ? 0.f : ld1(vi);
+    adam_elem<FIRST>(xe, he, ve, ge, ap);
+  }
+}
+
+template <int BASE, bool BF16, bool FIRST, bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
+    float *__restrict__ hbase, float *__restrict__ vbase, const MixEntry *__restrict__ seq, int len,
+    int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap, int m, SgdP sp, AdamP ap) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  sp.lr = sp.lr * ti.lr_scale;
+  sp.wd = ti.wd;
+  ap.lr = ap.lr * ti.lr_scale;
+  ap.wd = ti.wd;
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const void *const *__restrict__ gp = gtab + t.owner;       // worker i: gp[i * n_tensors]
+  float *h0 = hbase + ti.fo + eo;                              // worker i: h0 + i * d_pad
+  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
+  constexpr int gsize = BF16 ? 2 : 4;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (e0 + 4 <= n) {
+    V4 Sx = {0.f, 0.f, 0.f, 0.f}, Sh = Sx, Sv = Sx, first = Sx;
+#pragma unroll 1
+    for (int i = 0; i < len; ++i) {
+      const MixEntry en = seq[i];
+      float *xi = xp[en.node] + eo + e0;
+      float *hi = h0 + en.node * d_pad + e0;
+      float *vi = BASE == 1 ? v0 + en.node * d_pad + e0 : nullptr;
+      V4 xo, ho, vo;
+      if (en.flags & kMixOwnFromS) {
+        xo = Sx;
+        ho = Sh;
+        vo = Sv;
+      } else {
+        const void *gi =
+            static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
+        step_vec4<BASE, BF16, FIRST, NT>(xi, hi, vi, gi, threadIdx.x, sp, ap, xo, ho, vo);
+      }
+      st4<NT>(hi, ho);
+      if constexpr (BASE == 1) st4<NT>(vi, vo);
+      if (en.flags & kMixSaveFirst) first = xo;
+      if (en.flags & kMixNoSrc) {
+        st4<NT>(xi, en.a * xo);
+      } else {
+        if (en.flags & kMixSrcFromFirst) {
+          Sx = first;
+        } else if (!(en.flags & kMixSrcFromS)) {
+          const void *gs =
+              static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;
+          step_vec4<BASE, BF16, FIRST, NT>(xp[en.src] + eo + e0, h0 + en.src * d_pad + e0,
+                                           BASE == 1 ? v0 + en.src * d_pad + e0 : nullptr, gs,
+                                           threadIdx.x, sp, ap, Sx, Sh, Sv);
+        }
+        st4<NT>(xi, en.a * xo + en.b * Sx);
+      }
+    }
+  } else {
+    for (int j = e0; j < n; ++j) {        // ragged tail of the tensor
+      float Sx = 0.f, Sh = 0.f, Sv = 0.f, first = 0.f;
+      for (int i = 0; i < len; ++i) {
+        const MixEntry en = seq[i];
+        float *xi = xp[en.node] + eo + j;
+        float *hi = h0 + en.node * d_pad + j;
+        float *vi = BASE == 1 ? v0 + en.node * d_pad + j : nullptr;
+        float xo, ho, vo;
+        if (en.flags & kMixOwnFromS) {
+          xo = Sx;
+          ho = Sh;
+          vo = Sv;
+        } else {
+          const void *gi =
+              static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
+          step_1<BASE, BF16, FIRST>(xi, hi, vi, gi, j, sp, ap, xo, ho, vo);
+        }
+        st1(hi, ho);
+        if constexpr (BASE == 1) st1(vi, vo);
+        if (en.flags & kMixSaveFirst) first = xo;
+        if (en.flags & kMixNoSrc) {
+          st1(xi, en.a * xo);
+        } else {
+          if (en.flags & kMixSrcFromFirst) {
+            Sx = first;
+          } else if (!(en.flags & kMixSrcFromS)) {
+            const void *gs =
+                static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;
+            step_1<BASE, BF16, FIRST>(xp[en.src] + eo + j, h0 + en.src * d_pad + j,
+                                      BASE == 1 ? v0 + en.src * d_pad + j : nullptr, gs, j, sp, ap,
+                                      Sx, Sh, Sv);
+          }
+          st1(xi, en.a * xo + en.b * Sx);
+        }
+      }
+    }
+  }
+}
+
 // z^{(i)} = x^{(i)} / w_i (Algorithm C.1, last line), one workgroup per local tile.
 template <bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_debias(
@@ -778,6 +929,47 @@ hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t 
                        a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
   }
   return hipGetLastError();
+}
+
+namespace {
+
+template <int BASE, bool BF16, bool FIRST>
+hipError_t launch_local_mix_t(const LocalArgs &l, const MixArgs &x, int64_t d_pad, int n_tensors,
+                              const LaunchTuning &t, hipStream_t s) {
+  const Grid g = make_grid(x.ntiles, t.xcd_remap);
+  const SgdP sp{l.lr, l.mu, l.wd};
+  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_local_mix_step<BASE, BF16, FIRST, true>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
+                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, t.xcd_remap, x.m, sp, ap);
+  } else {
+    hipLaunchKernelGGL((k_local_mix_step<BASE, BF16, FIRST, false>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
+                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, t.xcd_remap, x.m, sp, ap);
+  }
+  return hipGetLastError();
+}
+
+template <int BASE, bool BF16>
+hipError_t launch_local_mix_f(const LocalArgs &l, const MixArgs &x, int64_t d_pad, int n_tensors,
+                              bool first, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_local_mix_t<BASE, BF16, true>(l, x, d_pad, n_tensors, t, s)
+               : launch_local_mix_t<BASE, BF16, false>(l, x, d_pad, n_tensors, t, s);
+}
+
+}  // namespace
+
+hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                 int32_t n_tensors, int base, bool bf16, bool first,
+                                 const LaunchTuning &t, hipStream_t s) {
+  if (x.ntiles <= 0 || x.len <= 0) return hipSuccess;
+  if (base == 0) {
+    return bf16 ? launch_local_mix_f<0, true>(l, x, d_pad, n_tensors, first, t, s)
+                : launch_local_mix_f<0, false>(l, x, d_pad, n_tensors, first, t, s);
+  }
+  return bf16 ? launch_local_mix_f<1, true>(l, x, d_pad, n_tensors, first, t, s)
+              : launch_local_mix_f<1, false>(l, x, d_pad, n_tensors, first, t, s);
 }
 
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &t, hipStream_t s) {

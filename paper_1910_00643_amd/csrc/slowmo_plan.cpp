@@ -71,7 +71,7 @@ void plan_outer(int32_t n_tensors, const int64_t *numel, std::vector<PlanRun> &r
 // other share that register.  The cycles come last, each member before its
 // source.
 void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
-                       std::vector<float> &share) {
+              std::vector<float> &share, bool with_idle) {
   std::vector<int32_t> outdeg(m, 0);
   for (int32_t i = 0; i < m; ++i)
     if (in_peer[i] != i) ++outdeg[in_peer[i]];
@@ -109,7 +109,7 @@ void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
   auto emit = [&](int32_t i) {
     if (in_peer[i] != i) {
       seq.push_back({i, in_peer[i], share[i], share[in_peer[i]], 0, 0});
-    } else if (outdeg[i] > 0) {
+    } else if (outdeg[i] > 0 || with_idle) {
       seq.push_back({i, i, share[i], 0.f, kMixNoSrc, 0});
     }  // else: an idle worker keeps its value
   };

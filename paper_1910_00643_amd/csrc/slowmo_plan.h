@@ -94,9 +94,10 @@ struct MixEntry {
 };
 static_assert(sizeof(MixEntry) == 24, "MixEntry layout");
 // The update order of one mixing step for the in-neighbour map in_peer (m
-// entries in 0..m-1); share[j] = 1 / (1 + outdeg(j)).
+// entries in 0..m-1); share[j] = 1 / (1 + outdeg(j)).  Workers that neither
+// send nor receive get no entry unless with_idle is set (then: a = 1, kMixNoSrc).
 void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
-              std::vector<float> &share);
+              std::vector<float> &share, bool with_idle = false);
 
 Layout make_layout(int32_t n_tensors, const int64_t *numel);
 

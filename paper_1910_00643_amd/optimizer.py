@@ -80,6 +80,12 @@ class SlowMo:
         B.slowmo_local_outer_step(self.ctx, arr, lr, lr if outer_lr is None else outer_lr,
                                   torch.cuda.current_stream(self.device).cuda_stream)
 
+    def local_mix_step(self, grads, lr: float, in_peer: Sequence[int]) -> None:
+        """A local step and the gossip step after it (fused when possible)."""
+        arr = grads if isinstance(grads, C.Array) else self.grad_pointer_array(grads)
+        B.slowmo_local_mix_step(self.ctx, arr, lr, in_peer,
+                                torch.cuda.current_stream(self.device).cuda_stream)
+
     def mix_step(self, in_peer: Sequence[int]) -> None:
         B.slowmo_mix_step(self.ctx, in_peer, torch.cuda.current_stream(self.device).cuda_stream)
 

@@ -118,7 +118,14 @@ def make_gpu(w, prob):
     return opt
 
 
-def run_gpu(w, prob, opt, rounds, index, fused_last=False):
+def _gpu_in_peers(w, step):
+    import paper_1910_00643_amd as P
+    if w.mix == "expgraph":
+        return P.slowmo_expgraph_in_peers(w.m, step)
+    return W.in_peers(w, step).tolist()
+
+
+def run_gpu(w, prob, opt, rounds, index, fused_last=False, fused_mix=False):
     """Runs `rounds` outer iterations; gradients are regenerated before every
     local step (ring slots in turn).  Returns the snapshot (x, h, v at the
     sampled indices) taken after the local steps of the last round."""
@@ -135,12 +142,12 @@ def run_gpu(w, prob, opt, rounds, index, fused_last=False):
                 opt.local_outer_step(arrays[s], lr)     # last local step + outer step
                 step += 1
                 continue
-            opt.local_step(arrays[s], lr)
-            if w.mix == "expgraph":
-                import paper_1910_00643_amd as P
-                opt.mix_step(P.slowmo_expgraph_in_peers(w.m, step))
-            elif w.mix == "random":
-                opt.mix_step(W.in_peers(w, step).tolist())
+            if w.mix != "none" and fused_mix:       # local step + gossip step as one call
+                opt.local_mix_step(arrays[s], lr, _gpu_in_peers(w, step))
+            else:
+                opt.local_step(arrays[s], lr)
+                if w.mix != "none":
+                    opt.mix_step(_gpu_in_peers(w, step))
             step += 1
             if t == rounds - 1 and k == kb:
                 st = gpu_state(w, prob, opt, index, with_outer=False)
@@ -173,12 +180,13 @@ def gpu_state(w, prob, opt, index, with_outer=True):
     return out
 
 
-def compare_run(w, prob, opt, index, rounds, bitwise_f32=False, fused_last=False):
+def compare_run(w, prob, opt, index, rounds, bitwise_f32=False, fused_last=False,
+                fused_mix=False):
     """Full comparison of a finished GPU run against the oracle on `index`.
     With fused_last, every outer iteration but the final one (whose replicas
     are inspected before the outer step) ends with slowmo_local_outer_step."""
     lr = w.f32("lr")
-    snap = run_gpu(w, prob, opt, rounds, index, fused_last=fused_last)
+    snap = run_gpu(w, prob, opt, rounds, index, fused_last=fused_last, fused_mix=fused_mix)
     final = gpu_state(w, prob, opt, index)
     res = run_oracles(w, index, rounds, ("f64", "f32") if bitwise_f32 else ("f64",))
     o64, s64 = res["f64"]

@@ -120,21 +120,53 @@ def test_noaverage_variant_every_element(base, grad_dtype, policy, param_layout)
     opt.close()
 
 
+@pytest.mark.parametrize("fused_mix", [False, True])
 @pytest.mark.parametrize("m,base,param_layout", [(4, "sgd_nesterov", "separate"),
                                                  (8, "sgd_nesterov", "flat"),
                                                  (6, "sgd_nesterov", "separate"),
                                                  (19, "adam", "separate"), (1, "sgd_nesterov", "flat")])
-def test_gradient_push_mixing_every_element(m, base, param_layout):
+def test_gradient_push_mixing_every_element(m, base, param_layout, fused_mix):
     """SGP as base optimizer (Algorithm C.1): every local step is followed by
     a gossip step on the one-peer exponential graph; m = 6 and 19 give
-    permutations with several cycles, m = 1 an idle step."""
+    permutations with several cycles, m = 1 an idle step.  With fused_mix the
+    pair is one call (one kernel for the 16-byte aligned "separate" layout,
+    the two kernels for "flat")."""
     w = dataclasses.replace(W.ragged_mini(base=base, m=m, policy="maintain"), mix="expgraph",
                             tau=7, rounds=2)
     prob = _problem(w, ring=2, param_layout=param_layout, grad_layout="separate")
     opt = PU.make_gpu(w, prob)
     idx = np.arange(w.d, dtype=np.int64)
-    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"))
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
+                   fused_mix=fused_mix)
     opt.close()
+
+
+@pytest.mark.parametrize("base,grad_dtype,policy,mix", [
+    ("sgd_nesterov", "f32", "reset", "random"), ("adam", "bf16", "maintain", "random"),
+    ("adam", "f32", "reset", "expgraph"), ("sgd_nesterov", "bf16", "average", "random")])
+def test_fused_local_and_mixing_step_equals_the_two_calls_bitwise(base, grad_dtype, policy, mix):
+    """slowmo_local_mix_step against slowmo_local_step + slowmo_mix_step on
+    the same inputs: replicas, buffers, x0, u and push-sum weights bit for bit
+    (also for Adam, whose arithmetic is the same code in both kernels)."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, m=11, policy=policy),
+                            mix=mix, tau=3, rounds=2)
+    idx = np.arange(w.d, dtype=np.int64)
+    states = []
+    for fused in (False, True):
+        prob = _problem(w, ring=2, param_layout="separate", grad_layout="separate")
+        opt = PU.make_gpu(w, prob)
+        snap = PU.run_gpu(w, prob, opt, w.rounds, idx, fused_mix=fused)
+        final = PU.gpu_state(w, prob, opt, idx)
+        states.append((snap, final, opt.pushsum_weights()))
+        opt.close()
+    (s0, f0, w0), (s1, f1, w1) = states
+    assert w0 == w1
+    if policy == "reset":       # h, v after the last local step are dead and need not be stored
+        f0.pop("h"), f0.pop("v")
+    for a, b in ((s0, s1), (f0, f1)):
+        for key in a:
+            if a[key] is not None:
+                assert np.array_equal(a[key], b[key], equal_nan=False), key
 
 
 def test_mixing_accepts_any_map_and_rejects_bad_indices():
@@ -186,9 +218,12 @@ def test_push_sum_with_any_in_neighbour_map_every_element(m, base, param_layout,
     for t in range(w.rounds):
         for k in range(w.tau):
             prob.fill_grads(step % 2, step)
-            opt.local_step(prob.grads[step % 2], w.lr)
             peers = W.in_peers(w, step)
-            opt.mix_step(peers.tolist())
+            if step % 2:                     # the pair as one call on every other step
+                opt.local_mix_step(prob.grads[step % 2], w.lr, peers.tolist())
+            else:
+                opt.local_step(prob.grads[step % 2], w.lr)
+                opt.mix_step(peers.tolist())
             g = PU.oracle_grads(w, idx, step)
             for o in os_.values():
                 o.local_step(g, w.f32("lr"))
@@ -544,14 +579,15 @@ def test_random_configurations(seed):
     layouts = (str(rng.choice(["separate", "flat", "arena"])),
                str(rng.choice(["separate", "flat", "padded"])))
     fused = bool(rng.integers(0, 2)) and exact and mix == "none"
+    fused_mix = mix != "none" and seed % 2 == 0
     print("config", seed, dict(sizes=sizes, m=w.m, tau=w.tau, base=base, grads=w.grad_dtype,
                                policy=policy, exact=exact, mix=mix, groups=groups,
-                               layouts=layouts, fused=fused), flush=True)
+                               layouts=layouts, fused=fused, fused_mix=fused_mix), flush=True)
     prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
     opt = PU.make_gpu(w, prob)
     idx = np.arange(w.d, dtype=np.int64)
     PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
-                   fused_last=fused)
+                   fused_last=fused, fused_mix=fused_mix)
     opt.close()
 
 
