@@ -34,7 +34,10 @@
  *    corrections.  A captured outer iteration of the SGD base therefore replays
  *    correctly any number of times; one of the Adam base does not (its bias
  *    correction changes every step).  The context's counters advance when the
- *    calls are recorded, not when the graph is replayed.
+ *    calls are recorded, not when the graph is replayed.  slowmo_mix_step,
+ *    slowmo_local_mix_step and slowmo_debias upload a small table with every
+ *    call (from a staging buffer that later calls reuse) and keep the push-sum
+ *    weights on the host: do not record them into a graph.
  *  - Errors: every entry point returns a slowmo_status; nothing aborts or
  *    throws.  A call that fails leaves the context's state unchanged.
  *    slowmo_last_error() gives a message for the most recent failure.
