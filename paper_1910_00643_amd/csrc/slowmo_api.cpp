@@ -419,20 +419,18 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   CREATE_HIP(hipMemsetAsync(ctx->u, 0, arena * outer_copies, stream), "clearing u");
   CREATE_HIP(hipMemsetAsync(ctx->h, 0, arena * m, stream), "clearing h");
   if (ctx->v) CREATE_HIP(hipMemsetAsync(ctx->v, 0, arena * m, stream), "clearing v");
-  // common starting point x_{0,0}: worker 0's replica
-  for (int32_t j = 0; j < n_tensors; ++j) {
-    const size_t bytes = static_cast<size_t>(numel[j]) * sizeof(float);
-    if (!bytes) continue;
-    for (size_t w = 0; w < outer_copies; ++w) {
-      CREATE_HIP(hipMemcpyAsync(ctx->x0 + w * L.d_pad + L.arena_off[j], params[j], bytes,
-                                hipMemcpyDeviceToDevice, stream),
-                 "copy of x_{0,0} into x0");
-    }
-    for (int32_t w = 1; w < m; ++w) {
-      CREATE_HIP(hipMemcpyAsync(params[static_cast<size_t>(w) * n_tensors + j], params[j], bytes,
-                                hipMemcpyDeviceToDevice, stream),
-                 "copy of x_{0,0} into a replica");
-    }
+  // common starting point x_{0,0}: worker 0's replica, into x0 and every other replica
+  {
+    OuterArgs ia{};
+    ia.tiles = ctx->d_otiles;
+    ia.tensors = ctx->d_tensors;
+    ia.xtab_t = ctx->d_xtab_t;
+    ia.ntiles = ctx->n_otiles;
+    ia.m = m;
+    ia.x0 = ctx->x0;
+    ia.d_pad = L.d_pad;
+    CREATE_HIP(launch_init_broadcast(ia, static_cast<int32_t>(outer_copies), ctx->tune, stream),
+               "copy of x_{0,0} into x0 and the replicas");
   }
   // the host-side tables above go out of scope: wait for their uploads
   CREATE_HIP(hipStreamSynchronize(stream), "hipStreamSynchronize");

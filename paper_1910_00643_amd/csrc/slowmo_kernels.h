@@ -96,6 +96,10 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipSt
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
                                    int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &tune, hipStream_t stream);
+// Copies worker 0's replica into x0 (x0_copies copies, d_pad apart) and into the
+// replicas of workers 1..m-1; uses a.tiles, a.tensors, a.xtab_t, a.x0, a.d_pad, a.m.
+hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &tune,
+                                 hipStream_t stream);
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &tune,
                               hipStream_t stream);
 // The local step and the mixing step that follows it in one kernel; x.seq must

@@ -3,6 +3,7 @@
 // k_local_step         Algorithm 1 lines 3-5 for all workers (Table C.1 rows SGD, Adam)
 // k_outer_step         lines 6-8 + copy into every replica (+ "average" buffer strategy)
 // k_local_outer_step   the last local step of an outer iteration fused with the outer step
+// k_init_broadcast     Algorithm 1 "Input": x_{0,0} into x0 and every replica
 // k_outer_noavg        lines 7-8 per worker, without line 6 (Section 6)
 // k_mix_step        mixing step of stochastic gradient push (Algorithm C.1)
 // k_local_mix_step     a local step and the mixing step that follows it, fused
@@ -332,6 +333,40 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
   // line 2 of the next outer iteration, strategy "average"
   if constexpr (AVG >= 1) average_arena<NTL, NTS>(hbase + ti.fo + eo, d_pad, m, p.m_f, e0, n);
   if constexpr (AVG >= 2) average_arena<NTL, NTS>(vbase + ti.fo + eo, d_pad, m, p.m_f, e0, n);
+}
+
+// ---- common starting point (Algorithm 1, "Input") ------------------------------
+// x_{0,0} is worker 0's replica: copy it into x0 (one copy, or one per worker
+// when every worker keeps its own) and into the replicas of workers 1..m-1.
+template <bool NT>
+__global__ __launch_bounds__(kOuterBlock) void k_init_broadcast(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, float *__restrict__ x0base, int64_t d_pad, int x0_copies,
+    int ntiles, int chunk, int remap, int m) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const int64_t eo = static_cast<int64_t>(t.k) * kOuterTile;
+  const int64_t left = ti.numel - eo;
+  const int n = left < kOuterTile ? static_cast<int>(left) : kOuterTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  float *x0 = x0base + ti.fo + eo;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if (ti.unaligned == 0 && e0 + 4 <= n) {
+    const V4 v = ld4<NT>(xp[0] + eo + e0);
+    for (int c = 0; c < x0_copies; ++c) st4<NT>(x0 + c * d_pad + e0, v);
+#pragma unroll 8
+    for (int i = 1; i < m; ++i) st4<NT>(xp[i] + eo + e0, v);
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) {
+      const float v = ld1(xp[0] + eo + j);
+      for (int c = 0; c < x0_copies; ++c) st1(x0 + c * d_pad + j, v);
+      for (int i = 1; i < m; ++i) st1(xp[i] + eo + j, v);
+    }
+  }
 }
 
 // ---- outer step without the exact average (Section 6) ---------------------------
@@ -916,6 +951,22 @@ hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32
   }
   return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, t, s)
               : launch_fused_f<1, false>(l, o, n_tensors, first, policy, t, s);
+}
+
+hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &t,
+                                 hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  if (t.nontemporal) {
+    hipLaunchKernelGGL((k_init_broadcast<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.x0, a.d_pad, x0_copies, a.ntiles, g.chunk,
+                       t.xcd_remap, a.m);
+  } else {
+    hipLaunchKernelGGL((k_init_broadcast<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
+                       a.tensors, a.xtab_t, a.x0, a.d_pad, x0_copies, a.ntiles, g.chunk,
+                       t.xcd_remap, a.m);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {
