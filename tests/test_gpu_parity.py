@@ -658,7 +658,8 @@ def _sampled(w, rounds, n_random, ring=2, halo=4):
     idx = prob.sample_indices(n_random, edges=_tile_edges(w), halo=halo, seed=w.seed)
     # as bench.py runs it: outer iterations end with the fused call where that applies
     worst = PU.compare_run(w, prob, opt, idx, rounds, bitwise_f32=(w.base == "sgd_nesterov"),
-                           fused_last=(w.exact_average and w.mix == "none"))
+                           fused_last=(w.exact_average and w.mix == "none"),
+                           fused_mix=(w.mix != "none"))
     print(w.name, "sampled", idx.size, "worst errors", worst)
     opt.close()
 
@@ -688,6 +689,19 @@ def test_resnet50_shaped_average_policy_sampled():
     the m momentum buffers)."""
     w = dataclasses.replace(W.resnet50(), policy="average", rounds=4)
     _sampled(w, w.rounds, 1500)
+
+
+@pytest.mark.parametrize("mix", ["expgraph", "random"])
+def test_resnet50_shaped_gradient_push_sampled(mix):
+    """Stochastic gradient push as base optimizer at full size, as bench.py
+    --mix runs it: every local step and its gossip step as one fused call."""
+    w = dataclasses.replace(W.resnet50(), mix=mix, rounds=3)
+    _sampled(w, w.rounds, 1500)
+
+
+def test_transformer_big_shaped_gradient_push_sampled():
+    w = dataclasses.replace(W.transformer_big(), mix="expgraph", rounds=1, tau=12)
+    _sampled(w, w.rounds, 2000)
 
 
 def test_stress_1e9_sampled():
