@@ -4,7 +4,9 @@
  * against the closed form that Eq. (2)-(3) of the paper give for that case:
  *     u_t      = tau * cbar * (1 - beta^t) / (1 - beta)
  *     x_{T,0}  = x_{0,0} - alpha * gamma * tau * cbar * sum_{t=1..T} (1 - beta^t)/(1 - beta)
- * (cbar = mean of the c_i).  Prints "OK" and returns 0 on success.
+ * (cbar = mean of the c_i), followed by one push-sum mixing step on the consensus point
+ * (Algorithm C.1) whose de-biased parameters must give that point back.
+ * Prints "OK" and returns 0 on success.
  * Built by __graft_entry__.build() into tests/abi_c_check; run by the GPU tests.
  */
 #define __HIP_PLATFORM_AMD__ 1
@@ -102,6 +104,39 @@ int main(void) {
         for (int64_t e = 0; e < numel[j]; ++e) {
             double err = lr * fabs(host[e] - TAU * cbar * geo_last) / (1 + lr * TAU * cbar * geo_last);
             if (err > worst) worst = err;
+        }
+    }
+    /* Push-sum (Algorithm C.1) on the consensus point: worker 0 sends to everybody.  Its mass is
+     * split over M workers, so x^(0) = x/M, x^(i) = x + x/M, w = (1/M, 1 + 1/M, ...), and the
+     * de-biased parameters z^(i) = x^(i) / w_i are the consensus point again on every worker. */
+    {
+        const int32_t star[M] = {0};
+        float w[M], *z[M * NT];
+        SMCHECK(slowmo_mix_step(ctx, star, NULL), ctx);
+        SMCHECK(slowmo_get_pushsum_weights(ctx, w), ctx);
+        for (int i = 0; i < M; ++i) {
+            double want_w = i == 0 ? 1.0 / M : 1.0 + 1.0 / M;
+            if (fabs(w[i] - want_w) > 1e-6) { printf("push-sum weight %d is %g\n", i, w[i]); return 6; }
+            for (int j = 0; j < NT; ++j)
+                HIPCHECK(hipMalloc((void **)&z[i * NT + j], sizeof(float) * (size_t)numel[j]));
+        }
+        SMCHECK(slowmo_debias(ctx, z, NULL), ctx);
+        HIPCHECK(hipDeviceSynchronize());
+        for (int i = 0; i < M; ++i) {
+            for (int j = 0; j < NT; ++j) {
+                float *biased = malloc(sizeof(float) * (size_t)numel[j]);
+                HIPCHECK(hipMemcpy(host, z[i * NT + j], sizeof(float) * (size_t)numel[j], hipMemcpyDeviceToHost));
+                HIPCHECK(hipMemcpy(biased, params[i * NT + j], sizeof(float) * (size_t)numel[j], hipMemcpyDeviceToHost));
+                for (int64_t e = 0; e < numel[j]; ++e) {
+                    double want = (1.0 + 0.001 * (double)e) - (double)alpha * lr * TAU * cbar * geo_sum;
+                    double err = fabs(host[e] - want) / (1 + fabs(want));
+                    if (err > worst) worst = err;
+                    err = fabs(biased[e] - want * (i == 0 ? 1.0 / M : 1.0 + 1.0 / M)) / (1 + fabs(want));
+                    if (err > worst) worst = err;
+                }
+                free(biased);
+                HIPCHECK(hipFree(z[i * NT + j]));
+            }
         }
     }
     SMCHECK(slowmo_destroy(ctx), NULL);
