@@ -29,6 +29,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 MEASURED_TRAFFIC_BYTES = {
     "resnet50": 16407839291,            # profiles/resnet50_local_step_outer_step.md
     "transformer_big": 43766503735,     # profiles/transformer_big_local_step_outer_step.md
+    # k_local_mix_step, profiles/resnet50_average_noaverage_mixing.md
+    ("resnet50", "expgraph"): 16358148679,
+    ("resnet50", "random"): 18164425935,
 }
 
 
@@ -322,7 +325,8 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": local_bytes,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if dominant == "local" else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name if dominant == "local"
+                                                           else (w.name, w.mix))},
     }
     if kern_ms.get("outer"):
         ob = outer_bytes_per_element(w) * w.d
