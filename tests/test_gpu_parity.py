@@ -651,6 +651,51 @@ def test_call_sequence_errors_leave_state_unchanged():
     opt.close()
 
 
+def test_failed_mixing_calls_leave_replicas_weights_and_counters_unchanged():
+    import torch
+    import paper_1910_00643_amd as P
+    B = P.binding
+    w = dataclasses.replace(W.ragged_mini(m=4), tau=2, rounds=1)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    prob.fill_grads(0, 0)
+    opt.local_mix_step(prob.grads[0], w.lr, [0, 0, 1, 1])
+    before = (PU.gpu_state(w, prob, opt, idx, with_outer=False), opt.pushsum_weights(), opt.counters())
+    assert before[1] != [1.0] * 4 and before[2][:2] == (0, 1)
+    for bad_peers in ([0, 0, 1, 4], [0, -1, 1, 1]):
+        for call in (lambda p: opt.mix_step(p), lambda p: opt.local_mix_step(prob.grads[0], w.lr, p)):
+            with pytest.raises(P.SlowMoError) as e:
+                call(bad_peers)
+            assert e.value.status == B.SLOWMO_ERR_ARG
+    with pytest.raises(P.SlowMoError) as e:
+        opt.local_mix_step(prob.grads[0], -1.0, [0, 0, 1, 1])
+    assert e.value.status == B.SLOWMO_ERR_ARG
+    # de-bias: a missing destination and a misaligned one
+    z = [[torch.empty_like(t) for t in prob.params[i]] for i in range(w.m)]
+    ptrs = [t.data_ptr() for zi in z for t in zi]
+    big = next(k for k, n in enumerate(prob.numel) if n > 8)
+    with pytest.raises(P.SlowMoError) as e:
+        B.slowmo_debias(opt.ctx, ptrs[:big] + [0] + ptrs[big + 1:])
+    assert e.value.status == B.SLOWMO_ERR_ARG
+    with pytest.raises(P.SlowMoError) as e:
+        B.slowmo_debias(opt.ctx, ptrs[:big] + [ptrs[big] + 2] + ptrs[big + 1:])
+    assert e.value.status == B.SLOWMO_ERR_ALIGN
+    after = (PU.gpu_state(w, prob, opt, idx, with_outer=False), opt.pushsum_weights(), opt.counters())
+    assert after[1] == before[1] and after[2] == before[2]
+    for key in ("x", "h"):
+        assert np.array_equal(before[0][key], after[0][key]), key
+    # the context still works: finish the outer iteration
+    prob.fill_grads(0, 1)
+    opt.local_mix_step(prob.grads[0], w.lr, [1, 0, 3, 2])
+    with pytest.raises(P.SlowMoError) as e:
+        opt.local_mix_step(prob.grads[0], w.lr, [1, 0, 3, 2])      # tau steps already taken
+    assert e.value.status == B.SLOWMO_ERR_STATE
+    opt.outer_step(w.lr)
+    assert opt.pushsum_weights() == [1.0] * 4
+    opt.close()
+
+
 # ---- full sizes, sampled elements ------------------------------------------------
 def _sampled(w, rounds, n_random, ring=2, halo=4):
     prob = _problem(w, ring=ring, grad_layout="padded")     # the layout bench.py times
