@@ -302,6 +302,20 @@ slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst_device, size_t byte
 slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src_device, size_t bytes,
                                   void *stream);
 
+/*
+ * Host-side check that [ptr, ptr + bytes) is memory the current device can
+ * access: both ends known to the HIP runtime as device, managed or pinned host
+ * memory of the current device, and inside one allocation where the runtime
+ * can tell.  Launches nothing.  slowmo_create applies it to every parameter
+ * tensor and to the workspace, so that a host pointer passed by mistake is an
+ * ARG error instead of a GPU memory fault.  Environment variable
+ * SLOWMO_CHECK_POINTERS, read at slowmo_create: 0 = no such checks, 1
+ * (default) = at create, 2 = also the gradient tensors whenever their pointer
+ * table changes and the destinations of slowmo_debias (a few microseconds per
+ * tensor).  Errors: ARG (with the reason in slowmo_last_error(NULL)), HIP.
+ */
+slowmo_status slowmo_check_device_range(const void *ptr, size_t bytes);
+
 /* Frees the context's host memory and its small device-side bookkeeping.
  * Never touches parameters, gradients or the workspace.  NULL is accepted. */
 slowmo_status slowmo_destroy(slowmo_ctx *ctx);

@@ -33,7 +33,7 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
            "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step",
            "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix",
-           "slowmo_local_mix_step"]
+           "slowmo_local_mix_step", "slowmo_check_device_range"]
 
 
 (SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
@@ -106,6 +106,8 @@ def lib() -> C.CDLL:
     L.slowmo_mix_step.restype = C.c_int
     L.slowmo_local_mix_step.argtypes = [vp, C.POINTER(vp), C.c_float, C.POINTER(i32), vp]
     L.slowmo_local_mix_step.restype = C.c_int
+    L.slowmo_check_device_range.argtypes = [vp, C.c_size_t]
+    L.slowmo_check_device_range.restype = C.c_int
     L.slowmo_plan_mix.argtypes = [i32, C.POINTER(i32), C.POINTER(slowmo_mix_entry)]
     L.slowmo_plan_mix.restype = C.c_int32
     L.slowmo_get_pushsum_weights.argtypes = [vp, C.POINTER(C.c_float)]
@@ -201,6 +203,11 @@ def slowmo_local_mix_step(ctx, grads, lr: float, in_peer: Sequence[int], stream:
     peers = (C.c_int32 * len(in_peer))(*[int(v) for v in in_peer]) if in_peer is not None else None
     _check(lib().slowmo_local_mix_step(ctx, arr, lr, peers,
                                        C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_check_device_range(ptr: int, nbytes: int) -> None:
+    """Raises SlowMoError unless [ptr, ptr + nbytes) is device-accessible memory."""
+    _check(lib().slowmo_check_device_range(C.c_void_p(ptr) if ptr else None, nbytes), None)
 
 
 def slowmo_plan_mix(in_peer: Sequence[int]):

@@ -192,6 +192,7 @@ struct slowmo_ctx {
   int64_t l = 0;  // Adam steps counted by the bias correction
   bool buffers_zero = true;  // h (and v) are to be read as zero by the next local step
   bool params_aligned = true;  // every replica pointer is 16-byte aligned
+  int32_t check_pointers = 1;  // 1: caller's tensors are checked at create; 2: also per call
 
   LaunchTuning tune{};
   std::string err;
@@ -274,6 +275,37 @@ int64_t slowmo_plan_outer(int32_t m, int32_t n_tensors, const int64_t *numel, sl
   return plan_query(false, m, n_tensors, numel, out, cap);
 }
 
+slowmo_status slowmo_check_device_range(const void *ptr, size_t bytes) {
+  if (!ptr) return fail(nullptr, SLOWMO_ERR_ARG, "pointer is NULL");
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipGetDevice");
+  const char *lo = static_cast<const char *>(ptr);
+  const char *ends[2] = {lo, lo + (bytes ? bytes - 1 : 0)};
+  for (const char *q : ends) {
+    hipPointerAttribute_t at{};
+    e = hipPointerGetAttributes(&at, q);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();  // not sticky: the next call must not see it
+      return fail(nullptr, SLOWMO_ERR_ARG,
+                  "the range is not memory known to the HIP runtime (ordinary host memory?)");
+    }
+    if (at.type == hipMemoryTypeUnregistered)
+      return fail(nullptr, SLOWMO_ERR_ARG, "the range is ordinary host memory, not device-accessible");
+    if (at.type == hipMemoryTypeDevice && at.device != dev)
+      return fail(nullptr, SLOWMO_ERR_ARG, "the range is memory of another device");
+  }
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  e = hipMemGetAddressRange(&base, &size, const_cast<void *>(ptr));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();  // no range information for this kind of memory: both ends were known
+  } else if (lo + bytes > static_cast<const char *>(base) + size) {
+    return fail(nullptr, SLOWMO_ERR_ARG, "the range runs past the end of its allocation");
+  }
+  return SLOWMO_OK;
+}
+
 slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t n_tensors,
                             const int64_t *numel, float *const *params, void *state,
                             size_t state_bytes, void *stream_) {
@@ -336,6 +368,19 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   if (e != hipSuccess) {
     delete ctx;
     return fail_hip(nullptr, e, "hipGetDevice");
+  }
+  ctx->check_pointers = env_flag("SLOWMO_CHECK_POINTERS", 1);
+  if (ctx->check_pointers) {
+    slowmo_status bad_ptr = slowmo_check_device_range(state, sec.total);
+    for (size_t i = 0; i < n_ptr && bad_ptr == SLOWMO_OK; ++i) {
+      const int64_t n = numel[i % n_tensors];
+      if (n) bad_ptr = slowmo_check_device_range(params[i], static_cast<size_t>(n) * sizeof(float));
+    }
+    if (bad_ptr != SLOWMO_OK) {
+      delete ctx;
+      g_err = "parameter tensor or workspace: " + g_err;
+      return bad_ptr;
+    }
   }
   char *base = static_cast<char *>(state);
   ctx->x0 = reinterpret_cast<float *>(base + sec.x0);
@@ -470,6 +515,13 @@ slowmo_status prepare_local(slowmo_ctx *ctx, const void *const *grads, float lr,
                     std::memcmp(ctx->last_grads.data(), grads, n_ptr * sizeof(void *)) == 0;
   if (!same) {
     hipError_t e = hipSuccess;
+    if (ctx->check_pointers >= 2) {
+      for (size_t i = 0; i < n_ptr; ++i) {
+        const int64_t n = ctx->numel[i % ctx->n_tensors];
+        if (n && slowmo_check_device_range(grads[i], static_cast<size_t>(n) * gsize) != SLOWMO_OK)
+          return fail(ctx, SLOWMO_ERR_ARG, "gradient tensor: " + g_err);
+      }
+    }
     slot = ctx->gtab.upload(grads, n_ptr * sizeof(void *), stream, &e);
     if (slot < 0) return fail_hip(ctx, e, "upload of the gradient pointers");
     ctx->last_grads.assign(grads, grads + n_ptr);
@@ -775,6 +827,13 @@ slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
     if (!z[i]) return fail(ctx, SLOWMO_ERR_ARG, "a destination pointer is NULL");
     if (reinterpret_cast<uintptr_t>(z[i]) % sizeof(float))
       return fail(ctx, SLOWMO_ERR_ALIGN, "a destination pointer is not 4-byte aligned");
+  }
+  if (ctx->check_pointers >= 2) {
+    for (size_t i = 0; i < n_ptr; ++i) {
+      const int64_t n = ctx->numel[i % nt];
+      if (n && slowmo_check_device_range(z[i], static_cast<size_t>(n) * sizeof(float)) != SLOWMO_OK)
+        return fail(ctx, SLOWMO_ERR_ARG, "destination tensor: " + g_err);
+    }
   }
   if (ctx->n_ltiles == 0) return SLOWMO_OK;
   std::vector<char> table(ztab_bytes(m, nt));

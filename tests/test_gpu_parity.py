@@ -651,6 +651,41 @@ def test_call_sequence_errors_leave_state_unchanged():
     opt.close()
 
 
+def test_host_pointers_are_rejected_before_any_kernel_runs():
+    """A host array passed where a device tensor belongs must come back as an
+    argument error from the host-side range check, not reach a kernel."""
+    import torch
+    import paper_1910_00643_amd as P
+    from paper_1910_00643_amd.optimizer import make_config
+    B = P.binding
+    dev = torch.zeros(1000, dtype=torch.float32, device="cuda:0")
+    host = np.zeros(1000, dtype=np.float32)
+    pinned = torch.zeros(1000, dtype=torch.float32).pin_memory()
+    # the check itself, first: it launches nothing
+    P.slowmo_check_device_range(dev.data_ptr(), 4000)
+    P.slowmo_check_device_range(dev.data_ptr() + 400, 3600)
+    P.slowmo_check_device_range(pinned.data_ptr(), 4000)       # pinned host memory is device-accessible
+    for ptr, nbytes in ((host.ctypes.data, 4000), (0, 16)):
+        with pytest.raises(P.SlowMoError) as e:
+            P.slowmo_check_device_range(ptr, nbytes)
+        assert e.value.status == B.SLOWMO_ERR_ARG
+    whole = torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0")    # an allocation of its own
+    with pytest.raises(P.SlowMoError) as e:
+        P.slowmo_check_device_range(whole.data_ptr(), (1 << 30) + whole.numel())
+    assert e.value.status == B.SLOWMO_ERR_ARG
+    # only now through slowmo_create (the check has just been shown to reject this pointer)
+    cfg = make_config(m=2, tau=2, alpha=1.0, beta=0.5, base="sgd_nesterov", momentum=0.9)
+    x = [torch.zeros(1000, dtype=torch.float32, device="cuda:0") for _ in range(2)]
+    nbytes = P.slowmo_state_bytes(cfg, [1000])
+    state = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(P.SlowMoError) as e:
+        P.slowmo_create(cfg, [1000], [x[0].data_ptr(), host.ctypes.data], state.data_ptr(), nbytes)
+    assert e.value.status == B.SLOWMO_ERR_ARG and "parameter tensor" in e.value.message
+    ctx = P.slowmo_create(cfg, [1000], [t.data_ptr() for t in x], state.data_ptr(), nbytes)
+    P.slowmo_destroy(ctx)
+    torch.cuda.synchronize()
+
+
 def test_failed_mixing_calls_leave_replicas_weights_and_counters_unchanged():
     import torch
     import paper_1910_00643_amd as P
