@@ -26,10 +26,14 @@
  *    (create, set_tensor_hparams, export and import do wait; they say so).  All
  *    calls on one context must be issued on one stream or be ordered by the
  *    caller.  A context is not thread-safe.
- *  - Graph capture: while the gradient pointers are the same as in the previous
- *    call, slowmo_local_step, slowmo_outer_step and slowmo_local_outer_step only
- *    launch kernels (no copies, no synchronization, no memset) and may be recorded
- *    into a HIP graph.  Kernel arguments are fixed at capture time: the learning
+ *  - Gradient pointers: the library keeps the 16 most recently used distinct
+ *    pointer tables on the device; a call whose `grads` array equals one of them
+ *    uploads nothing.
+ *  - Graph capture: in that case slowmo_local_step, slowmo_outer_step and
+ *    slowmo_local_outer_step only launch kernels (no copies, no synchronization,
+ *    no memset) and may be recorded into a HIP graph (pass every gradient set
+ *    once before capturing, and no more than 16 distinct ones while the graph
+ *    is in use).  Kernel arguments are fixed at capture time: the learning
  *    rates, the first/last-step handling of the RESET policy and Adam's bias
  *    corrections.  A captured outer iteration of the SGD base therefore replays
  *    correctly any number of times; one of the Adam base does not (its bias

@@ -20,7 +20,8 @@ using namespace slowmo;
 
 namespace {
 
-constexpr int kSlots = 4;            // ring of gradient-pointer tables
+constexpr int kSlots = 4;            // ring of per-call tables (mixing order, de-bias table)
+constexpr int kGradSlots = 16;       // gradient-pointer tables kept on the device
 constexpr size_t kSectionAlign = 256;
 
 thread_local std::string g_err = "";
@@ -36,7 +37,7 @@ size_t ztab_bytes(int32_t m, int32_t n_tensors) {
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kGradSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
@@ -56,7 +57,7 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.h = take(arena * c.m);
   s.v = take(c.base == SLOWMO_ADAM ? arena * c.m : 0);
   s.xtab_t = take(n_ptr * sizeof(void *));
-  for (int i = 0; i < kSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
+  for (int i = 0; i < kGradSlots; ++i) s.gtab[i] = take(n_ptr * sizeof(void *));
   for (int i = 0; i < kSlots; ++i) s.mixtab[i] = take(mixtab_bytes(c.m));
   for (int i = 0; i < kSlots; ++i) s.ztab[i] = take(ztab_bytes(c.m, n_tensors));
   s.slots = take(n_ptr * sizeof(SlotInfo));
@@ -120,15 +121,17 @@ int32_t env_flag(const char *name, int32_t dflt) {
 // device slots (inside the caller's workspace) with pinned staging copies,
 // and one event per slot recorded after its upload, so that a staging copy is
 // not rewritten while an earlier upload may still be reading it.
+template <int N>
 struct TableRing {
-  void *d[kSlots] = {};
-  void *h[kSlots] = {};
-  hipEvent_t ev[kSlots] = {};
-  bool used[kSlots] = {};
-  int cur = -1;  // slot of the most recent upload, -1 = none
+  void *d[N] = {};
+  void *h[N] = {};
+  hipEvent_t ev[N] = {};
+  bool used[N] = {};
+  size_t len[N] = {};  // bytes of the table in each slot
+  int cur = -1;        // slot of the most recent upload, -1 = none
 
   hipError_t init(char *device_base, const size_t *offsets, size_t bytes) {
-    for (int i = 0; i < kSlots; ++i) {
+    for (int i = 0; i < N; ++i) {
       d[i] = device_base + offsets[i];
       hipError_t e = hipHostMalloc(&h[i], std::max<size_t>(bytes, 8), hipHostMallocDefault);
       if (e != hipSuccess) return e;
@@ -137,24 +140,36 @@ struct TableRing {
     }
     return hipSuccess;
   }
+  // Slot that already holds exactly this table (most recent first), or -1.
+  // The staging copy of a slot always equals what its device copy holds once
+  // the stream has reached the upload.
+  int find(const void *src, size_t bytes) const {
+    for (int k = 0; k < N && cur >= 0; ++k) {
+      const int slot = (cur - k + N) % N;
+      if (used[slot] && len[slot] == bytes && std::memcmp(h[slot], src, bytes) == 0) return slot;
+    }
+    return -1;
+  }
   // Uploads `bytes` from src into the next slot; returns the slot or -1.
   int upload(const void *src, size_t bytes, hipStream_t stream, hipError_t *err) {
-    const int slot = (cur + 1) % kSlots;
+    const int slot = (cur + 1) % N;
     if (used[slot]) {
       *err = hipEventSynchronize(ev[slot]);
       if (*err != hipSuccess) return -1;
     }
+    used[slot] = false;
     std::memcpy(h[slot], src, bytes);
     *err = hipMemcpyAsync(d[slot], h[slot], bytes, hipMemcpyHostToDevice, stream);
     if (*err != hipSuccess) return -1;
     *err = hipEventRecord(ev[slot], stream);
     if (*err != hipSuccess) return -1;
     used[slot] = true;
+    len[slot] = bytes;
     cur = slot;
     return slot;
   }
   void destroy() {
-    for (int i = 0; i < kSlots; ++i) {
+    for (int i = 0; i < N; ++i) {
       if (ev[i]) (void)hipEventDestroy(ev[i]);
       if (h[i]) (void)hipHostFree(h[i]);
     }
@@ -179,10 +194,9 @@ struct slowmo_ctx {
   TileRef *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
 
-  TableRing gtab;    // gradient pointers of the current call (m * n_tensors)
-  std::vector<const void *> last_grads;  // contents of gtab's current slot
-  TableRing mixtab;  // update order of the current mixing step (at most m entries)
-  TableRing ztab;    // destination pointers and weights of the current de-bias call
+  TableRing<kGradSlots> gtab;  // gradient-pointer tables of recent calls (m * n_tensors each)
+  TableRing<kSlots> mixtab;  // update order of the current mixing step (at most m entries)
+  TableRing<kSlots> ztab;  // destination pointers and weights of the current de-bias call
   std::vector<float> w;  // push-sum weights (Algorithm C.1), 1 after every exact average
   std::vector<SlotInfo> slots;      // host copies of the per-slot / per-tensor tables
   std::vector<TensorInfo> tinfo;
@@ -509,11 +523,9 @@ slowmo_status prepare_local(slowmo_ctx *ctx, const void *const *grads, float lr,
   }
   *all_aligned = (low_bits & (4 * gsize - 1)) == 0;
 
-  // gradient-pointer table: reuse the uploaded one if the pointers did not change
-  int slot = ctx->gtab.cur;
-  const bool same = slot >= 0 && ctx->last_grads.size() == n_ptr &&
-                    std::memcmp(ctx->last_grads.data(), grads, n_ptr * sizeof(void *)) == 0;
-  if (!same) {
+  // gradient-pointer table: reuse a device copy if one of the recent calls had these pointers
+  int slot = ctx->gtab.find(grads, n_ptr * sizeof(void *));
+  if (slot < 0) {
     hipError_t e = hipSuccess;
     if (ctx->check_pointers >= 2) {
       for (size_t i = 0; i < n_ptr; ++i) {
@@ -524,7 +536,6 @@ slowmo_status prepare_local(slowmo_ctx *ctx, const void *const *grads, float lr,
     }
     slot = ctx->gtab.upload(grads, n_ptr * sizeof(void *), stream, &e);
     if (slot < 0) return fail_hip(ctx, e, "upload of the gradient pointers");
-    ctx->last_grads.assign(grads, grads + n_ptr);
   }
 
   LocalArgs a{};

@@ -651,6 +651,20 @@ def test_call_sequence_errors_leave_state_unchanged():
     opt.close()
 
 
+@pytest.mark.parametrize("ring", [3, 20])
+def test_gradient_pointer_tables_are_cached_and_evicted_correctly(ring):
+    """The library keeps the most recent 16 distinct gradient-pointer tables
+    on the device.  3 gradient sets in turn: every table is found again; 20
+    sets in turn: every call evicts the oldest table and uploads anew.  The
+    results must not depend on it."""
+    w = dataclasses.replace(W.ragged_mini(), tau=7, rounds=6)
+    prob = _problem(w, ring=ring, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    idx = np.arange(w.d, dtype=np.int64)
+    PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=True)
+    opt.close()
+
+
 def test_host_pointers_are_rejected_before_any_kernel_runs():
     """A host array passed where a device tensor belongs must come back as an
     argument error from the host-side range check, not reach a kernel."""
