@@ -229,7 +229,10 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
  * the closest earlier entry that has one; SOURCE_IS_FIRST -- the operand is
  * the own operand of the closest earlier entry flagged OPENS_CYCLE.  The order
  * is valid if no entry reads from memory a worker that an earlier entry has
- * written.  Idle workers (no sender, no receiver) have no entry.
+ * written.  Idle workers (no sender, no receiver) have no entry.  Entries of
+ * one connected group of workers are consecutive and the first of them carries
+ * GROUP_START; no HELD / IS_FIRST flag refers across a group start, and the
+ * library runs the groups as separate kernel launches.
  * Writes at most m entries to `out` (host) and returns their number, or -1
  * for bad arguments.  Host-only.
  */
@@ -238,7 +241,8 @@ enum {
   SLOWMO_MIX_SOURCE_HELD = 2,
   SLOWMO_MIX_SOURCE_IS_FIRST = 4,
   SLOWMO_MIX_OPENS_CYCLE = 8,
-  SLOWMO_MIX_NO_SOURCE = 16
+  SLOWMO_MIX_NO_SOURCE = 16,
+  SLOWMO_MIX_GROUP_START = 32
 };
 typedef struct slowmo_mix_entry {
   int32_t worker;

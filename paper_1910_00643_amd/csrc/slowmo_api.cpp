@@ -701,6 +701,24 @@ slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer
 
 namespace {
 
+// Ranges [first, last) of the mixing entries to run as separate launches: one
+// per connected group of workers (a launch then walks only that group's
+// replicas per tile, and fewer memory regions visited side by side measure
+// faster), consecutive groups merged when there are more than kMaxMixLaunches.
+constexpr size_t kMaxMixLaunches = 32;
+std::vector<std::pair<int32_t, int32_t>> mix_launch_ranges(const std::vector<MixEntry> &seq) {
+  std::vector<int32_t> starts;
+  for (size_t i = 0; i < seq.size(); ++i)
+    if (seq[i].flags & kMixGroupStart) starts.push_back(static_cast<int32_t>(i));
+  std::vector<std::pair<int32_t, int32_t>> out;
+  const size_t per = (starts.size() + kMaxMixLaunches - 1) / kMaxMixLaunches;  // groups per launch
+  for (size_t g = 0; g < starts.size(); g += per) {
+    const size_t g_end = std::min(g + per, starts.size());
+    out.push_back({starts[g], g_end < starts.size() ? starts[g_end] : static_cast<int32_t>(seq.size())});
+  }
+  return out;
+}
+
 slowmo_status launch_mix(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
   const int32_t m = ctx->cfg.m;
   std::vector<MixEntry> seq;
@@ -716,10 +734,13 @@ slowmo_status launch_mix(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t st
     a.xtab_t = ctx->d_xtab_t;
     a.ntiles = ctx->n_otiles;
     a.m = m;
-    a.seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
-    a.len = static_cast<int32_t>(seq.size());
-    e = launch_mix_step(a, ctx->tune, stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
+    const MixEntry *d_seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
+    for (const auto &r : mix_launch_ranges(seq)) {
+      a.seq = d_seq + r.first;
+      a.len = r.second - r.first;
+      e = launch_mix_step(a, ctx->tune, stream);
+      if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
+    }
   }
   return SLOWMO_OK;
 }
@@ -797,11 +818,14 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
     x.xtab_t = ctx->d_xtab_t;
     x.ntiles = ctx->n_otiles;
     x.m = c.m;
-    x.seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
-    x.len = static_cast<int32_t>(seq.size());
-    e = launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
-                              ctx->buffers_zero, ctx->tune, stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "fused local+mixing kernel launch");
+    const MixEntry *d_seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
+    for (const auto &r : mix_launch_ranges(seq)) {
+      x.seq = d_seq + r.first;
+      x.len = r.second - r.first;
+      e = launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
+                                ctx->buffers_zero, ctx->tune, stream);
+      if (e != hipSuccess) return fail_hip(ctx, e, "fused local+mixing kernel launch");
+    }
     finish_local(ctx);
   }
   mix_weights(ctx, in_peer);

@@ -68,8 +68,8 @@ void plan_outer(int32_t n_tensors, const int64_t *numel, std::vector<PlanRun> &r
 // receivers that have receivers of their own before those that have none:
 // then a worker is mostly followed by its source, whose old value the kernel
 // already holds in a register, and receivers of one sender that follow each
-// other share that register.  The cycles come last, each member before its
-// source.
+// other share that register.  A cycle comes after the trees of its members,
+// each member before its source.
 void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
               std::vector<float> &share, bool with_idle) {
   std::vector<int32_t> outdeg(m, 0);
@@ -113,37 +113,53 @@ void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
       seq.push_back({i, i, share[i], 0.f, kMixNoSrc, 0});
     }  // else: an idle worker keeps its value
   };
-  // post-order walk of the trees below every fixed point and every cycle member
+  // post-order walk of the tree below `root`; the root itself is listed only
+  // if it is a tree worker (cycle members wait for their cycle)
   std::vector<std::pair<int32_t, int32_t>> stack;  // (worker, next receiver to visit)
-  for (int32_t r = 0; r < m; ++r) {
-    const bool root = in_tree[r] ? in_peer[r] == r : true;
-    if (!root) continue;
-    stack.push_back({r, start[r]});
+  auto walk = [&](int32_t root) {
+    stack.push_back({root, start[root]});
     while (!stack.empty()) {
       auto &top = stack.back();
       if (top.second < start[top.first + 1]) {
         const int32_t c = recv[top.second++];
         stack.push_back({c, start[c]});
       } else {
-        if (in_tree[top.first]) emit(top.first);  // cycle members wait for their cycle
+        if (in_tree[top.first]) emit(top.first);
         stack.pop_back();
       }
     }
+  };
+  // One group per connected set of workers: a fixed point with everything that
+  // hangs off it, or a cycle with the trees of its members.  Groups share no
+  // worker, so they may run as separate launches.
+  std::vector<size_t> group_start;
+  for (int32_t r = 0; r < m; ++r) {
+    if (!(in_tree[r] && in_peer[r] == r)) continue;
+    const size_t at = seq.size();
+    walk(r);
+    if (seq.size() > at) group_start.push_back(at);
   }
   std::vector<char> seen(m, 0);
   for (int32_t i = 0; i < m; ++i) {
     if (in_tree[i] || seen[i]) continue;
-    const size_t first = seq.size();
+    group_start.push_back(seq.size());
     for (int32_t j = i; !seen[j]; j = in_peer[j]) {
       seen[j] = 1;
+      walk(j);  // the trees of the cycle's members first
+    }
+    const size_t first = seq.size();
+    for (int32_t j = i; seen[j] == 1; j = in_peer[j]) {
+      seen[j] = 2;
       emit(j);
     }
     seq[first].flags |= kMixSaveFirst;
     seq.back().flags |= kMixSrcFromFirst;
   }
-  // operands that the kernel still holds from the previous entry
+  for (size_t at : group_start) seq[at].flags |= kMixGroupStart;
+  // operands that the kernel still holds from the previous entry of the group
   int32_t held = -1;  // worker whose old value is in the kernel's source register
   for (MixEntry &e : seq) {
+    if (e.flags & kMixGroupStart) held = -1;
     if (e.node == held) e.flags |= kMixOwnFromS;
     if (e.flags & kMixNoSrc) continue;
     if (e.src == held && !(e.flags & kMixSrcFromFirst)) e.flags |= kMixSrcFromS;

@@ -83,6 +83,7 @@ enum MixFlag : int32_t {
   kMixSrcFromFirst = 4,  // the source is the worker that opened the cycle
   kMixSaveFirst = 8,     // this worker opens a cycle: keep its old value
   kMixNoSrc = 16,        // receives from nobody: x <- a * x
+  kMixGroupStart = 32,   // first entry of a connected group of workers (for the launcher only)
 };
 struct MixEntry {
   int32_t node;    // worker updated by this entry

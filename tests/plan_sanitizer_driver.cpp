@@ -65,11 +65,13 @@ static void check_mix(int32_t m, const std::vector<int32_t> &peer) {
     if (peer[i] != i) v = v + share[peer[i]] * x[peer[i]];
     want[i] = v;
   }
+  REQUIRE(seq.empty() || (seq[0].flags & kMixGroupStart));
   std::vector<char> written(m, 0);
   float S = 0.f, first = 0.f;
   bool s_valid = false, first_valid = false;
   for (const MixEntry &e : seq) {
     REQUIRE(e.node >= 0 && e.node < m && e.src >= 0 && e.src < m && !written[e.node]);
+    if (e.flags & kMixGroupStart) s_valid = first_valid = false;  // a launch of its own
     float own;
     if (e.flags & kMixOwnFromS) {
       REQUIRE(s_valid);

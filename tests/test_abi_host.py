@@ -206,9 +206,16 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
             seen = set()
             held = first = None          # what the kernel keeps in registers
             loads = 0
+            group_of = {}
             for worker, source, keep, take, flags in plan:
                 keep, take = f32(keep), f32(take)
                 assert worker not in seen
+                if flags & B.SLOWMO_MIX_GROUP_START:    # another launch: registers start empty
+                    held = first = None
+                    group = len(set(group_of.values()))
+                    assert not flags & (B.SLOWMO_MIX_OWN_HELD | B.SLOWMO_MIX_SOURCE_HELD
+                                        | B.SLOWMO_MIX_SOURCE_IS_FIRST)
+                group_of[worker] = group
                 if flags & B.SLOWMO_MIX_OWN_HELD:
                     own = held
                 else:
@@ -229,6 +236,10 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
                         loads += 1
                     got[worker] = keep * own + take * held
                 seen.add(worker)
+            assert not plan or plan[0][4] & B.SLOWMO_MIX_GROUP_START
+            for worker, source, *_ in plan:     # a group is closed under "receives from"
+                assert group_of[worker] == group_of.get(source, group_of[worker])
+                assert source in group_of
             if kind in ("perm", "chain"):   # nothing is read twice
                 assert loads == len(plan)
             if kind == "star" and m > 1:    # the sender is read once for all its receivers
