@@ -354,6 +354,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->numel.assign(numel, numel + n_tensors);
   ctx->layout = make_layout(n_tensors, numel);
   ctx->tune.xcd_remap = env_flag("SLOWMO_XCD_REMAP", 1) ? 1 : 0;
+  ctx->tune.xcd_run = std::max(env_flag("SLOWMO_XCD_RUN", 0), 0);
   ctx->tune.nontemporal = env_flag("SLOWMO_NT", 1) ? 1 : 0;
   ctx->tune.fuse_last = env_flag("SLOWMO_FUSE_LAST", 1) ? 1 : 0;
   ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;

@@ -75,6 +75,8 @@ struct DebiasArgs {
 
 struct LaunchTuning {
   int32_t xcd_remap;    // 1: consecutive tiles go to the same XCD
+  int32_t xcd_run;      // tiles an XCD takes in a row before the next XCD's run; 0 = one
+                        // contiguous eighth of all tiles per XCD
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
   int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
   int32_t fuse_mix;     // 1: slowmo_local_mix_step runs one fused kernel when it can

@@ -99,8 +99,13 @@ __device__ __forceinline__ V4 ldg4(const void *g, int vec) {
 // Tile of workgroup b.  Workgroup b runs on XCD b mod 8; with the remap, XCD c
 // walks the contiguous tile range [c * chunk, (c + 1) * chunk), so each XCD's
 // L2 and TLB see one compact window of every stream instead of a 1-in-8 comb.
-__device__ __forceinline__ int tile_of(int b, int chunk, int remap) {
-  return remap ? (b % kXcd) * chunk + b / kXcd : b;
+__device__ __forceinline__ int tile_of(int b, int chunk, int run) {
+  // run == 0: workgroup b takes tile b.  Otherwise the workgroups of one XCD
+  // (b % 8) take runs of `run` consecutive tiles, the 8 XCDs side by side;
+  // run == chunk gives every XCD one contiguous eighth of the tiles.
+  if (run == 0) return b;
+  const int q = b / kXcd, x = b % kXcd;
+  return (q / run) * (kXcd * run) + x * run + q % run;
 }
 
 // ---- per-element arithmetic -------------------------------------------------
@@ -830,28 +835,39 @@ __global__ __launch_bounds__(kLocalBlock) void k_debias(
 
 struct Grid {
   int chunk;
+  int run;  // tiles per XCD turn; 0 = no remap
   unsigned blocks;
 };
-Grid make_grid(int ntiles, int remap) {
+Grid make_grid(int ntiles, const LaunchTuning &t) {
   Grid g;
   g.chunk = (ntiles + kXcd - 1) / kXcd;
-  g.blocks = static_cast<unsigned>(remap ? g.chunk * kXcd : ntiles);
+  g.run = !t.xcd_remap ? 0 : (t.xcd_run > 0 && t.xcd_run < g.chunk ? t.xcd_run : g.chunk);
+  if (g.run == 0) {
+    g.blocks = static_cast<unsigned>(ntiles);
+  } else {
+    int64_t span = static_cast<int64_t>(kXcd) * g.run;
+    if ((ntiles + span - 1) / span * span > INT32_MAX) {  // keep workgroup ids within int
+      g.run = g.chunk;
+      span = static_cast<int64_t>(kXcd) * g.run;
+    }
+    g.blocks = static_cast<unsigned>((ntiles + span - 1) / span * span);
+  }
   return g;
 }
 
 template <int BASE, bool BF16, bool FIRST, bool LAST>
 hipError_t launch_local_t(const LocalArgs &a, const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   const SgdP sp{a.lr, a.mu, a.wd};
   const AdamP ap{a.lr, a.wd, a.b1, a.b2, a.omb1, a.omb2, a.rc1, a.rc2, a.eps};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, LAST, true>), dim3(g.blocks),
                        dim3(kLocalBlock), 0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles,
-                       g.chunk, t.xcd_remap, sp, ap);
+                       g.chunk, g.run, sp, ap);
   } else {
     hipLaunchKernelGGL((k_local_step<BASE, BF16, FIRST, LAST, false>), dim3(g.blocks),
                        dim3(kLocalBlock), 0, s, a.tiles, a.slots, a.gtab, a.h, a.v, a.ntiles,
-                       g.chunk, t.xcd_remap, sp, ap);
+                       g.chunk, g.run, sp, ap);
   }
   return hipGetLastError();
 }
@@ -882,11 +898,11 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
 
 template <bool NT, int AVG>
 hipError_t launch_outer_t(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
   hipLaunchKernelGGL((k_outer_step<NT, AVG>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s,
                      a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad, a.ntiles,
-                     g.chunk, t.xcd_remap, a.m, p);
+                     g.chunk, g.run, a.m, p);
   return hipGetLastError();
 }
 
@@ -906,18 +922,18 @@ namespace {
 template <int BASE, bool BF16, bool FIRST, int POLICY>
 hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
                           const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(o.ntiles, t.xcd_remap);
+  const Grid g = make_grid(o.ntiles, t);
   const SgdP sp{l.lr, l.mu, l.wd};
   const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
   const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true>), dim3(g.blocks),
                        dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
-                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, t.xcd_remap, o.m, sp, ap, p);
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
   } else {
     hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false>), dim3(g.blocks),
                        dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
-                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, t.xcd_remap, o.m, sp, ap, p);
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
   }
   return hipGetLastError();
 }
@@ -956,28 +972,28 @@ hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32
 hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &t,
                                  hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_init_broadcast<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
                        a.tensors, a.xtab_t, a.x0, a.d_pad, x0_copies, a.ntiles, g.chunk,
-                       t.xcd_remap, a.m);
+                       g.run, a.m);
   } else {
     hipLaunchKernelGGL((k_init_broadcast<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
                        a.tensors, a.xtab_t, a.x0, a.d_pad, x0_copies, a.ntiles, g.chunk,
-                       t.xcd_remap, a.m);
+                       g.run, a.m);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_mix_step(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_mix_step<true>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, g.run, a.m);
   } else {
     hipLaunchKernelGGL((k_mix_step<false>), dim3(g.blocks), dim3(kOuterBlock), 0, s, a.tiles,
-                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, t.xcd_remap, a.m);
+                       a.tensors, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, g.run, a.m);
   }
   return hipGetLastError();
 }
@@ -987,17 +1003,17 @@ namespace {
 template <int BASE, bool BF16, bool FIRST>
 hipError_t launch_local_mix_t(const LocalArgs &l, const MixArgs &x, int64_t d_pad, int n_tensors,
                               const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(x.ntiles, t.xcd_remap);
+  const Grid g = make_grid(x.ntiles, t);
   const SgdP sp{l.lr, l.mu, l.wd};
   const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_local_mix_step<BASE, BF16, FIRST, true>), dim3(g.blocks),
                        dim3(kOuterBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
-                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, t.xcd_remap, x.m, sp, ap);
+                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, g.run, x.m, sp, ap);
   } else {
     hipLaunchKernelGGL((k_local_mix_step<BASE, BF16, FIRST, false>), dim3(g.blocks),
                        dim3(kOuterBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
-                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, t.xcd_remap, x.m, sp, ap);
+                       x.len, d_pad, n_tensors, x.ntiles, g.chunk, g.run, x.m, sp, ap);
   }
   return hipGetLastError();
 }
@@ -1025,27 +1041,27 @@ hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d
 
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_debias<true>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles, a.slots,
-                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, t.xcd_remap);
+                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, g.run);
   } else {
     hipLaunchKernelGGL((k_debias<false>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles, a.slots,
-                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, t.xcd_remap);
+                       a.ztab, a.w, a.n_tensors, a.ntiles, g.chunk, g.run);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t.xcd_remap);
+  const Grid g = make_grid(a.ntiles, t);
   const OuterP p{a.lr, 0.f, a.beta, 1.0f, a.alpha};
   if (t.nontemporal) {
     hipLaunchKernelGGL((k_outer_noavg<true>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles,
-                       a.slots, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, p);
+                       a.slots, a.x0, a.u, a.ntiles, g.chunk, g.run, p);
   } else {
     hipLaunchKernelGGL((k_outer_noavg<false>), dim3(g.blocks), dim3(kLocalBlock), 0, s, a.tiles,
-                       a.slots, a.x0, a.u, a.ntiles, g.chunk, t.xcd_remap, p);
+                       a.slots, a.x0, a.u, a.ntiles, g.chunk, g.run, p);
   }
   return hipGetLastError();
 }
