@@ -405,6 +405,19 @@ def test_worker_counts(m):
     opt.close()
 
 
+@pytest.mark.parametrize("mix,exact", [("random", True), ("expgraph", True), ("random", False)])
+def test_largest_worker_count_with_gossip(mix, exact):
+    """m = SLOWMO_MAX_WORKERS = 1024 replicas: pointer tables, mixing order
+    (up to 1024 entries, many groups) and the ordered mean at their largest."""
+    w = dataclasses.replace(W.ragged_mini(m=1024, policy="maintain"), mix=mix, exact_average=exact,
+                            shapes=(("a", (300,)), ("b", (5,)), ("c", (1030,))), rounds=2, tau=3)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    PU.compare_run(w, prob, opt, np.arange(w.d, dtype=np.int64), w.rounds, bitwise_f32=True,
+                   fused_mix=True)
+    opt.close()
+
+
 def test_empty_tensor_list_and_tau_one():
     w = dataclasses.replace(W.ragged_mini(), shapes=(("e0", (0,)), ("e1", (0,))), rounds=2, tau=1)
     prob = _problem(w, grad_layout="separate")
