@@ -58,16 +58,24 @@ class SlowMo:
         self._grad_key = None
         self._grad_arr = None
 
-    def grad_pointer_array(self, grads: Sequence[Sequence[torch.Tensor]]):
-        """ctypes array of the m * n_tensors gradient addresses (reusable)."""
+    def _pointer_array(self, tensors: Sequence[Sequence[torch.Tensor]], dtype):
         flat = []
-        for i, g in enumerate(grads):
+        for i, g in enumerate(tensors):
             for j, t in enumerate(g):
-                assert t.dtype == self.grad_dtype and t.is_contiguous() and t.device == self.device
+                assert t.dtype == dtype and t.is_contiguous() and t.device == self.device
                 assert t.numel() == self.numel[j]
                 flat.append(t.data_ptr() if t.numel() else 0)
         assert len(flat) == self.m * self.n_tensors
         return (C.c_void_p * len(flat))(*[C.c_void_p(v) if v else None for v in flat])
+
+    def grad_pointer_array(self, grads: Sequence[Sequence[torch.Tensor]]):
+        """ctypes array of the m * n_tensors gradient addresses (reusable: building
+        it walks every tensor in Python, which costs more than a kernel launch)."""
+        return self._pointer_array(grads, self.grad_dtype)
+
+    def param_pointer_array(self, tensors: Sequence[Sequence[torch.Tensor]]):
+        """The same for fp32 tensors shaped like the replicas (destinations of debias)."""
+        return self._pointer_array(tensors, torch.float32)
 
     def local_step(self, grads, lr: float) -> None:
         """grads: m lists of tensors, or an array from grad_pointer_array()."""
@@ -92,16 +100,11 @@ class SlowMo:
     def pushsum_weights(self):
         return B.slowmo_get_pushsum_weights(self.ctx, self.m)
 
-    def debias(self, z: Sequence[Sequence[torch.Tensor]]) -> None:
-        """z[i][j] <- x^{(i)}_j / w_i (fp32 CUDA tensors shaped like the replicas)."""
-        ptrs = []
-        for i in range(self.m):
-            assert len(z[i]) == len(self.numel)
-            for j, t in enumerate(z[i]):
-                assert t.dtype == torch.float32 and t.is_contiguous() and t.device == self.device
-                assert t.numel() == self.numel[j]
-                ptrs.append(t.data_ptr())
-        B.slowmo_debias(self.ctx, ptrs, torch.cuda.current_stream(self.device).cuda_stream)
+    def debias(self, z) -> None:
+        """z[i][j] <- x^{(i)}_j / w_i (fp32 CUDA tensors shaped like the replicas, or an
+        array from param_pointer_array())."""
+        arr = z if isinstance(z, C.Array) else self.param_pointer_array(z)
+        B.slowmo_debias(self.ctx, arr, torch.cuda.current_stream(self.device).cuda_stream)
 
     def outer_step(self, lr: float) -> None:
         B.slowmo_outer_step(self.ctx, lr, torch.cuda.current_stream(self.device).cuda_stream)
