@@ -135,7 +135,9 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
  * Algorithm 1 lines 3-5 for one k: one base-optimizer step on all m workers,
  *   x^{(i)} <- x^{(i)} - lr * d^{(i)},  d per Table C.1 (SGD row: h <- mu h + g~,
  *   d = mu h + g~;  Adam row: bias-corrected h / (sqrt(v) + eps)),
- *   g~ = g + weight_decay * x.
+ *   g~ = g + weight_decay * x,  x the replica itself (with gossip between the
+ *   steps: the push-sum numerator, not the de-biased x / w -- the two agree
+ *   whenever every mixing step so far was a permutation, as in the paper).
  * Adam's bias-correction exponent is the number of Adam steps taken so far
  * under the buffer policy, counting this one.
  *   grads : host array of m * n_tensors DEVICE pointers (worker-major) to the

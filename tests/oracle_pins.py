@@ -619,6 +619,111 @@ def pin_mixing_debiased_iterates_reach_consensus(make):
         _close(o.debiased()[i], mean, rtol=1e-9, atol=1e-10, what="push-sum consensus")
 
 
+# Appendix C.1: "each node cycles through the peers 2^0, 2^1, ..., 2^floor(log2(m-1))
+# hops away".  The hop lists are written out by hand, one period each.
+EXPGRAPH_HOPS = {2: [1], 3: [1, 2], 4: [1, 2], 5: [1, 2, 4], 6: [1, 2, 4], 8: [1, 2, 4],
+                 9: [1, 2, 4, 8], 16: [1, 2, 4, 8], 17: [1, 2, 4, 8, 16], 19: [1, 2, 4, 8, 16],
+                 32: [1, 2, 4, 8, 16], 33: [1, 2, 4, 8, 16, 32]}
+
+
+def pin_exponential_graph_hop_list_over_two_periods(make):
+    """Appendix C.1: the hops are 2^0 .. 2^floor(log2(m-1)) in turn, then the
+    list starts over; worker i receives from the worker `hop` ranks below it.
+    No hop is a multiple of m (nobody "receives from itself"), also for
+    m = 2^p, where a period of floor(log2 m) + 1 would add the hop m."""
+    O = type(make(np.zeros(1), m=1, tau=1, alpha=1.0, beta=0.0))
+    for m, hops in EXPGRAPH_HOPS.items():
+        for step in range(2 * len(hops) + 1):
+            hop = hops[step % len(hops)]
+            peers = np.asarray(O.exponential_graph_in_peers(m, step)).tolist()
+            assert peers == [(i - hop) % m for i in range(m)], (m, step, peers)
+            assert all(p != i for i, p in enumerate(peers)), (m, step)
+
+
+def pin_exact_average_after_push_sum_restores_the_unbiased_state(make):
+    """Algorithm C.1 + Algorithm 1 line 6.  Mixing with a column-stochastic P
+    that is not doubly stochastic moves mass between the workers but conserves
+    its total (and the total weight m), so with the plain SGD base the sum of
+    the replicas after tau steps is m*x_{t,0} - gamma*sum_i sum_k g_i,k
+    whatever the maps were: the exact average is x_{t,0} minus gamma times the
+    mean gradient sum, and with alpha = 1, beta = 0 it is the new iterate.
+    After line 6 every worker holds that one point, which is unbiased: its
+    de-biased value z = x / w must be the point itself, i.e. w = 1 again, and
+    the next outer iteration starts like the first one."""
+    rng = _rng(43)
+    T, tau, m, d, lr = 3, 4, 5, 9, 0.05
+    g = _grads(rng, T, tau, m, d)
+    x_init = rng.standard_normal(d)
+    maps = ([0, 0, 0, 2, 3], [1, 2, 3, 4, 0], [4, 4, 1, 1, 2], [0, 1, 0, 0, 0])   # no permutations but one
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.0)
+    x_t0 = x_init.copy()
+    for t in range(T):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+            o.mix_step(maps[(t * tau + k) % len(maps)])
+        assert abs(o.w.sum() - m) < 1e-12, "total push-sum weight"
+        assert np.abs(o.w - 1).max() > 1e-2, "the maps must unbalance the weights"
+        assert np.abs(o.debiased() - o.x).max() > 1e-3
+        want = x_t0 - lr / m * g[t].astype(np.float64).sum(axis=(0, 1))
+        o.outer_step(lr)
+        _close(o.x0, want, rtol=1e-12, atol=1e-13, what=f"average of the mass, t={t}")
+        for i in range(m):
+            assert np.array_equal(o.x[i], o.x0)
+            _close(o.debiased()[i], o.x0, rtol=1e-15, atol=0.0,
+                   what="z = x after the exact average (w back to 1)")
+        x_t0 = want
+
+
+def pin_no_average_keeps_the_push_sum_weights(make):
+    """Section 6 with gossip as the only exchange: without line 6 nothing but
+    the mixing steps touches the push-sum weights.  With alpha = 1, beta = 0
+    lines 7-8 return each worker's own replica, so across the outer step the
+    replicas, the weights and hence the de-biased points z = x / w stay what
+    they were, and the total weight stays m."""
+    rng = _rng(44)
+    tau, m, d, lr = 3, 4, 6, 0.05
+    g = _grads(rng, 2, tau, m, d)
+    o = make(rng.standard_normal(d), m=m, tau=tau, alpha=1.0, beta=0.0, exact_average=False)
+    for t in range(2):
+        for k in range(tau):
+            o.local_step(g[t, k], lr)
+            o.mix_step([[0, 0, 1, 1], [3, 0, 0, 2]][k % 2])
+        x, w, z = o.x.copy(), o.w.copy(), o.debiased().copy()
+        assert np.abs(w - 1).max() > 1e-2 and abs(w.sum() - m) < 1e-12
+        o.outer_step(lr)
+        _close(o.x, x, rtol=1e-13, atol=1e-14, what="replicas across the outer step")
+        _close(o.debiased(), z, rtol=1e-13, atol=1e-14, what="de-biased points across the outer step")
+        assert abs(o.w.sum() - m) < 1e-12
+
+
+def pin_weight_decay_under_push_sum_acts_on_the_numerator(make):
+    """Reading: with gossip between the steps the coupled L2 term is wd * x
+    with x the push-sum numerator (the replica itself), not wd * x / w.  The
+    base step is then linear in (x, h, g) and mixing conserves sums, so the
+    worker-mean of the replicas follows the library's Nesterov SGD with weight
+    decay on the worker-mean gradient for ANY column-stochastic maps -- the
+    mass bookkeeping push-sum rests on.  (With wd * x / w the mean would pick
+    up sum_i x_i / w_i instead of sum_i x_i and this fails.)"""
+    rng = _rng(45)
+    tau, m, d, lr, mu, wd = 6, 4, 7, 0.05, 0.9, 0.05
+    g = _grads(rng, 1, tau, m, d)
+    x_init = rng.standard_normal(d)
+    o = make(x_init, m=m, tau=tau, alpha=1.0, beta=0.0, momentum=mu, weight_decay=wd,
+             policy="maintain")
+    p = torch.tensor(x_init, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, nesterov=True, weight_decay=wd)
+    for k in range(tau):
+        o.local_step(g[0, k], lr)
+        o.mix_step([[0, 0, 1, 1], [3, 0, 0, 2], [1, 2, 3, 0]][k % 3])
+        p.grad = torch.tensor(g[0, k].astype(np.float64).mean(axis=0))
+        opt.step()
+    assert np.abs(o.w - 1).max() > 1e-2
+    # only x is mixed, h is not: mean(x) sees the buffers through mean(d_i)
+    # alone, which is what one worker driven by the mean gradient computes
+    _close(o.x.mean(axis=0), p.detach().numpy(), rtol=1e-11, atol=1e-12,
+           what="mean replica under push-sum with weight decay")
+
+
 # ------------------------------------------- per-tensor hyper-parameters
 
 def pin_parameter_groups_vs_library(make):

@@ -105,6 +105,19 @@ def test_exponential_graph_peers_match_the_oracles():
         P.slowmo_expgraph_in_peers(0, 0)
 
 
+def test_exponential_graph_hop_list_over_two_periods():
+    """Appendix C.1 names the hops: 2^0 .. 2^floor(log2(m-1)), then again from
+    the start.  The library's table against that list written out by hand
+    (two full periods and one step more), also for m = 2^p, where no hop may be
+    a multiple of m."""
+    from oracle_pins import EXPGRAPH_HOPS
+    for m, hops in EXPGRAPH_HOPS.items():
+        for step in range(2 * len(hops) + 1):
+            hop = hops[step % len(hops)]
+            got = P.slowmo_expgraph_in_peers(m, step)
+            assert got == [(i - hop) % m for i in range(m)], (m, step, got)
+
+
 def test_null_context_calls_fail_cleanly():
     lib = B.lib()
     assert lib.slowmo_local_step(None, None, 0.1, None) == B.SLOWMO_ERR_ARG

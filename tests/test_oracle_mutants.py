@@ -86,6 +86,18 @@ PY_MUTANTS = [
     ("groups_ignore_tensor_wd", "lr_j, self.momentum, wd_j)", "lr_j, self.momentum, self.weight_decay)", 0),
     ("groups_outer_uses_global_lr", "_ptr(self.u[a:b]), lr_j, self.alpha, self.beta)", "_ptr(self.u[a:b]), lr, self.alpha, self.beta)", 0),
     ("groups_outer_not_copied_back", "                self.x[:, a:b] = xs\n", "", 0),
+    ("pushsum_weights_not_reset_at_exact_average",
+     "            self.w[...] = 1     # all mass is shared equally again after the exact average\n",
+     "            pass\n", 0),
+    ("pushsum_weights_reset_without_the_average",
+     "        if self.exact_average:\n            self.w[...] = 1", "        if True:\n            self.w[...] = 1", 0),
+    ("expgraph_period_log2_m", "np.floor(np.log2(m - 1))", "np.floor(np.log2(m))", 0),
+    ("expgraph_one_hop_too_many", "int(np.floor(np.log2(m - 1))) + 1", "int(np.floor(np.log2(m - 1))) + 2", 0),
+    ("outer_averages_debiased_points",
+     "        if self.exact_average and self.bounds is None:\n",
+     "        if self.exact_average and self.bounds is None and not np.all(self.w == 1):\n"
+     "            self.x[...] = self.debiased()\n"
+     "        if self.exact_average and self.bounds is None:\n", 0),
     ("default_policy_swapped", 'policy = "reset" if base == "sgd_nesterov" else "maintain"',
      'policy = "maintain" if base == "sgd_nesterov" else "reset"', 0),
 ]
