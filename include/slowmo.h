@@ -43,7 +43,20 @@
  *    call (from a staging buffer that later calls reuse) and keep the push-sum
  *    weights on the host: do not record them into a graph.
  *  - Errors: every entry point returns a slowmo_status; nothing aborts or
- *    throws.  A call that fails leaves the context's state unchanged.
+ *    throws.  Arguments, call order and alignment are checked, and every table
+ *    a call needs is planned and on its way to the device, before the call's
+ *    first kernel is launched; counters and push-sum weights advance after its
+ *    last launch was accepted.  A call that fails therefore leaves the
+ *    context's state unchanged, with one exception: some calls issue several
+ *    kernels or copies (slowmo_mix_step and slowmo_local_mix_step launch one
+ *    kernel per connected group of workers; slowmo_local_outer_step and
+ *    slowmo_local_mix_step launch two kernels when a pointer is not 16-byte
+ *    aligned; slowmo_import_state copies up to four arrays).  If the HIP
+ *    runtime refuses one of them after an earlier one was issued, device
+ *    memory is partly updated and cannot be rolled back: the call returns
+ *    SLOWMO_ERR_HIP with a message that says so, counters and weights keep
+ *    their old values, and every later step call on that context returns
+ *    SLOWMO_ERR_STATE.  Destroy such a context.
  *    slowmo_last_error() gives a message for the most recent failure.
  */
 #ifndef SLOWMO_H
@@ -305,6 +318,9 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
  * slowmo_create overwrites replicas 1..m-1, restore them AFTER create when
  * resuming inside an outer iteration.  Per-tensor hyper-parameters are
  * configuration, not state: set them again.  Both calls synchronize `stream`.
+ * Import checks the whole header and the weights before it touches the
+ * context, then copies the arrays, waits for `stream`, and only then takes over
+ * the counters and weights.
  * Errors: ARG, NOMEM (destination too small), HIP.
  */
 size_t slowmo_export_bytes(const slowmo_ctx *ctx);

@@ -126,9 +126,11 @@ struct TableRing {
   void *d[N] = {};
   void *h[N] = {};
   hipEvent_t ev[N] = {};
-  bool used[N] = {};
-  size_t len[N] = {};  // bytes of the table in each slot
-  int cur = -1;        // slot of the most recent upload, -1 = none
+  bool used[N] = {};     // the slot's device copy holds the table of its staging copy
+  bool sent[N] = {};     // an upload from the slot's staging copy was enqueued (ev recorded)
+  size_t len[N] = {};    // bytes of the table in each slot
+  uint64_t key[N] = {};  // cheap fingerprint of the table in each slot
+  int cur = -1;          // slot of the most recent upload, -1 = none
 
   hipError_t init(char *device_base, const size_t *offsets, size_t bytes) {
     for (int i = 0; i < N; ++i) {
@@ -140,33 +142,69 @@ struct TableRing {
     }
     return hipSuccess;
   }
+  // A few words of the table (first, last, two in between) mixed with its
+  // length: distinct pointer tables differ there, so the full comparison
+  // below runs for one candidate, not for every slot.
+  static uint64_t fingerprint(const void *src, size_t bytes) {
+    const size_t words = bytes / sizeof(uint64_t);
+    uint64_t k = 0x9e3779b97f4a7c15ull ^ bytes;
+    if (words == 0) return k;
+    const size_t at[4] = {0, words / 3, 2 * words / 3, words - 1};
+    for (size_t i : at) {
+      uint64_t w;
+      std::memcpy(&w, static_cast<const char *>(src) + i * sizeof(uint64_t), sizeof(w));
+      k = (k ^ w) * 0xff51afd7ed558ccdull;
+      k ^= k >> 32;
+    }
+    return k;
+  }
   // Slot that already holds exactly this table (most recent first), or -1.
   // The staging copy of a slot always equals what its device copy holds once
   // the stream has reached the upload.
   int find(const void *src, size_t bytes) const {
-    for (int k = 0; k < N && cur >= 0; ++k) {
-      const int slot = (cur - k + N) % N;
-      if (used[slot] && len[slot] == bytes && std::memcmp(h[slot], src, bytes) == 0) return slot;
+    if (cur < 0) return -1;
+    const uint64_t k = fingerprint(src, bytes);
+    for (int i = 0; i < N; ++i) {
+      const int slot = (cur - i + N) % N;
+      if (used[slot] && key[slot] == k && len[slot] == bytes &&
+          std::memcmp(h[slot], src, bytes) == 0)
+        return slot;
     }
     return -1;
   }
-  // Uploads `bytes` from src into the next slot; returns the slot or -1.
-  int upload(const void *src, size_t bytes, hipStream_t stream, hipError_t *err) {
+  // The next slot's staging buffer, free to be written (waits until the
+  // previous upload from it has been consumed); returns the slot or -1.
+  int stage(hipError_t *err) {
     const int slot = (cur + 1) % N;
-    if (used[slot]) {
+    if (sent[slot]) {
       *err = hipEventSynchronize(ev[slot]);
       if (*err != hipSuccess) return -1;
+      sent[slot] = false;
     }
     used[slot] = false;
-    std::memcpy(h[slot], src, bytes);
-    *err = hipMemcpyAsync(d[slot], h[slot], bytes, hipMemcpyHostToDevice, stream);
-    if (*err != hipSuccess) return -1;
-    *err = hipEventRecord(ev[slot], stream);
-    if (*err != hipSuccess) return -1;
-    used[slot] = true;
-    len[slot] = bytes;
-    cur = slot;
     return slot;
+  }
+  // Sends the first `bytes` of slot's staging buffer to `dst` (the slot's own
+  // device copy when dst is NULL) and makes the slot the current one.
+  hipError_t send(int slot, size_t bytes, void *dst, hipStream_t stream) {
+    hipError_t e = hipMemcpyAsync(dst ? dst : d[slot], h[slot], bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(ev[slot], stream);
+    if (e != hipSuccess) return e;
+    sent[slot] = true;
+    used[slot] = dst == nullptr;  // a table sent elsewhere is not found again in this slot
+    len[slot] = bytes;
+    key[slot] = fingerprint(h[slot], bytes);
+    cur = slot;
+    return hipSuccess;
+  }
+  // Uploads `bytes` from src into the next slot; returns the slot or -1.
+  int upload(const void *src, size_t bytes, hipStream_t stream, hipError_t *err) {
+    const int slot = stage(err);
+    if (slot < 0) return -1;
+    std::memcpy(h[slot], src, bytes);
+    *err = send(slot, bytes, nullptr, stream);
+    return *err == hipSuccess ? slot : -1;
   }
   void destroy() {
     for (int i = 0; i < N; ++i) {
@@ -208,6 +246,14 @@ struct slowmo_ctx {
   bool params_aligned = true;  // every replica pointer is 16-byte aligned
   int32_t check_pointers = 1;  // 1: caller's tensors are checked at create; 2: also per call
 
+  // A call that launches several kernels and fails between two of them has
+  // changed device memory halfway: the context then refuses further work.
+  bool broken = false;
+  // Test hook (SLOWMO_TEST_FAIL_LAUNCH=n, read at create): the n-th kernel
+  // launch of this context (1-based) is not issued and reports a launch
+  // failure instead, so the error paths can be driven from the host.
+  int64_t fail_launch_at = 0, launches = 0;
+
   LaunchTuning tune{};
   std::string err;
 };
@@ -227,6 +273,25 @@ slowmo_status fail_hip(slowmo_ctx *ctx, hipError_t e, const char *what) {
   return fail(ctx, SLOWMO_ERR_HIP,
               std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) + ")");
 }
+
+// Every kernel launch of a context goes through here (see fail_launch_at).
+template <typename F>
+hipError_t guarded(slowmo_ctx *ctx, F &&launch) {
+  if (ctx->fail_launch_at > 0 && ++ctx->launches == ctx->fail_launch_at) return hipErrorLaunchFailure;
+  return launch();
+}
+
+// Failure after at least one kernel of a multi-kernel call was launched.
+slowmo_status fail_midway(slowmo_ctx *ctx, hipError_t e, const char *what) {
+  ctx->broken = true;
+  return fail(ctx, SLOWMO_ERR_HIP,
+              std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) +
+                  ") after part of the call's kernels were launched; replicas and buffers are "
+                  "partly updated and the context refuses further steps");
+}
+
+const char *kBrokenMsg =
+    "an earlier multi-kernel call failed halfway; the context's state is undefined: destroy it";
 
 void release(slowmo_ctx *ctx) {
   ctx->gtab.destroy();
@@ -359,6 +424,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.fuse_last = env_flag("SLOWMO_FUSE_LAST", 1) ? 1 : 0;
   ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
+  ctx->fail_launch_at = env_flag("SLOWMO_TEST_FAIL_LAUNCH", 0);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
   const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
@@ -507,6 +573,7 @@ namespace {
 // gradient pointer allows 16-byte vector loads.
 slowmo_status prepare_local(slowmo_ctx *ctx, const void *const *grads, float lr,
                             hipStream_t stream, LocalArgs *out, bool *all_aligned) {
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!grads) return fail(ctx, SLOWMO_ERR_ARG, "grads is NULL");
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k >= ctx->cfg.tau)
@@ -595,8 +662,10 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   // Under the reset policy the buffers written by the last step of an outer
   // iteration are discarded before they are read again: skip those stores.
   const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
-  hipError_t e = launch_local_step(a, c.base, c.grad_dtype == SLOWMO_BF16, ctx->buffers_zero,
-                                   dead_after, ctx->tune, stream);
+  hipError_t e = guarded(ctx, [&] {
+    return launch_local_step(a, c.base, c.grad_dtype == SLOWMO_BF16, ctx->buffers_zero, dead_after,
+                             ctx->tune, stream);
+  });
   if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
   finish_local(ctx);
   return SLOWMO_OK;
@@ -626,8 +695,9 @@ OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
   return a;
 }
 
-hipError_t launch_outer_any(const slowmo_ctx *ctx, float lr, hipStream_t stream) {
+hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
   const slowmo_config &c = ctx->cfg;
+  if (ctx->fail_launch_at > 0 && ++ctx->launches == ctx->fail_launch_at) return hipErrorLaunchFailure;
   if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
     OuterNoAvgArgs na{};
     na.tiles = ctx->d_ltiles;
@@ -647,6 +717,7 @@ hipError_t launch_outer_any(const slowmo_ctx *ctx, float lr, hipStream_t stream)
 
 slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k != ctx->cfg.tau)
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
@@ -659,6 +730,7 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
 slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads, float lr,
                                       float outer_lr, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!finite_pos(outer_lr)) return fail(ctx, SLOWMO_ERR_ARG, "outer_lr must be finite and > 0");
   if (ctx->k != ctx->cfg.tau - 1)
     return fail(ctx, SLOWMO_ERR_STATE,
@@ -671,17 +743,22 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
   if (st != SLOWMO_OK) return st;
   const slowmo_config &c = ctx->cfg;
   const bool bf16 = c.grad_dtype == SLOWMO_BF16;
-  hipError_t e;
   if (c.no_average || !aligned || !ctx->params_aligned || !ctx->tune.fuse_last) {
     // same two kernels as the separate calls
-    e = launch_local_step(a, c.base, bf16, ctx->buffers_zero, c.policy == SLOWMO_BUF_RESET,
-                          ctx->tune, stream);
-    if (e == hipSuccess) e = launch_outer_any(ctx, outer_lr, stream);
+    hipError_t e = guarded(ctx, [&] {
+      return launch_local_step(a, c.base, bf16, ctx->buffers_zero, c.policy == SLOWMO_BUF_RESET,
+                               ctx->tune, stream);
+    });
+    if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
+    e = launch_outer_any(ctx, outer_lr, stream);
+    if (e != hipSuccess) return fail_midway(ctx, e, "outer-step kernel launch");
   } else {
-    e = launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
-                                ctx->buffers_zero, c.policy, ctx->tune, stream);
+    hipError_t e = guarded(ctx, [&] {
+      return launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
+                                     ctx->buffers_zero, c.policy, ctx->tune, stream);
+    });
+    if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
   }
-  if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
   finish_local(ctx);
   finish_outer(ctx);
   return SLOWMO_OK;
@@ -720,35 +797,52 @@ std::vector<std::pair<int32_t, int32_t>> mix_launch_ranges(const std::vector<Mix
   return out;
 }
 
-slowmo_status launch_mix(slowmo_ctx *ctx, const int32_t *in_peer, hipStream_t stream) {
-  const int32_t m = ctx->cfg.m;
+// The mixing order of one call, planned on the host and uploaded; nothing has
+// been launched yet when stage_mix returns.
+struct StagedMix {
+  std::vector<std::pair<int32_t, int32_t>> ranges;  // one kernel launch each
+  const MixEntry *d_seq = nullptr;
+};
+
+slowmo_status stage_mix(slowmo_ctx *ctx, const int32_t *in_peer, bool with_idle, hipStream_t stream,
+                        StagedMix *out) {
   std::vector<MixEntry> seq;
   std::vector<float> share;
-  plan_mix(m, in_peer, seq, share);
-  if (!seq.empty() && ctx->n_otiles > 0) {
-    hipError_t e = hipSuccess;
-    const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
-    if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
-    MixArgs a{};
-    a.tiles = ctx->d_otiles;
-    a.tensors = ctx->d_tensors;
-    a.xtab_t = ctx->d_xtab_t;
-    a.ntiles = ctx->n_otiles;
-    a.m = m;
-    const MixEntry *d_seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
-    for (const auto &r : mix_launch_ranges(seq)) {
-      a.seq = d_seq + r.first;
-      a.len = r.second - r.first;
-      e = launch_mix_step(a, ctx->tune, stream);
-      if (e != hipSuccess) return fail_hip(ctx, e, "mixing kernel launch");
-    }
-  }
+  plan_mix(ctx->cfg.m, in_peer, seq, share, with_idle);
+  if (seq.empty() || ctx->n_otiles == 0) return SLOWMO_OK;  // nothing to launch
+  hipError_t e = hipSuccess;
+  const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
+  if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
+  out->d_seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
+  out->ranges = mix_launch_ranges(seq);
   return SLOWMO_OK;
 }
 
-}  // namespace
+MixArgs mix_args(const slowmo_ctx *ctx) {
+  MixArgs a{};
+  a.tiles = ctx->d_otiles;
+  a.tensors = ctx->d_tensors;
+  a.xtab_t = ctx->d_xtab_t;
+  a.ntiles = ctx->n_otiles;
+  a.m = ctx->cfg.m;
+  return a;
+}
 
-namespace {
+// Launches the gossip kernel once per group.  `launched`: kernels of this call
+// already issued before (a failure is then a failure halfway).
+slowmo_status run_mix(slowmo_ctx *ctx, const StagedMix &sm, int launched, hipStream_t stream) {
+  MixArgs a = mix_args(ctx);
+  for (const auto &r : sm.ranges) {
+    a.seq = sm.d_seq + r.first;
+    a.len = r.second - r.first;
+    const hipError_t e = guarded(ctx, [&] { return launch_mix_step(a, ctx->tune, stream); });
+    if (e != hipSuccess)
+      return launched ? fail_midway(ctx, e, "mixing kernel launch")
+                      : fail_hip(ctx, e, "mixing kernel launch");
+    ++launched;
+  }
+  return SLOWMO_OK;
+}
 
 bool check_in_peer(const slowmo_ctx *ctx, const int32_t *in_peer) {
   for (int32_t i = 0; i < ctx->cfg.m; ++i)
@@ -776,10 +870,14 @@ void mix_weights(slowmo_ctx *ctx, const int32_t *in_peer) {
 
 slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
   if (!check_in_peer(ctx, in_peer))
     return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
-  const slowmo_status st = launch_mix(ctx, in_peer, static_cast<hipStream_t>(stream_));
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  StagedMix sm;
+  slowmo_status st = stage_mix(ctx, in_peer, /*with_idle=*/false, stream, &sm);
+  if (st == SLOWMO_OK) st = run_mix(ctx, sm, 0, stream);
   if (st != SLOWMO_OK) return st;
   mix_weights(ctx, in_peer);
   return SLOWMO_OK;
@@ -788,6 +886,7 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
 slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, float lr,
                                     const int32_t *in_peer, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!in_peer) return fail(ctx, SLOWMO_ERR_ARG, "in_peer is NULL");
   if (!check_in_peer(ctx, in_peer))
     return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
@@ -798,37 +897,38 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
   if (st != SLOWMO_OK) return st;
   const slowmo_config &c = ctx->cfg;
   const bool bf16 = c.grad_dtype == SLOWMO_BF16;
-  if (!aligned || !ctx->params_aligned || !ctx->tune.fuse_mix || ctx->n_otiles == 0) {
-    // same two kernels as the separate calls
+  const bool two_kernels = !aligned || !ctx->params_aligned || !ctx->tune.fuse_mix || ctx->n_otiles == 0;
+  // both tables are on their way to the device before the first kernel is launched
+  StagedMix sm;
+  st = stage_mix(ctx, in_peer, /*with_idle=*/!two_kernels, stream, &sm);
+  if (st != SLOWMO_OK) return st;
+  if (two_kernels) {
+    // same kernels as the separate calls
     const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
-    hipError_t e = launch_local_step(a, c.base, bf16, ctx->buffers_zero, dead_after, ctx->tune, stream);
+    const hipError_t e = guarded(ctx, [&] {
+      return launch_local_step(a, c.base, bf16, ctx->buffers_zero, dead_after, ctx->tune, stream);
+    });
     if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-    finish_local(ctx);
-    st = launch_mix(ctx, in_peer, stream);
+    st = run_mix(ctx, sm, 1, stream);
     if (st != SLOWMO_OK) return st;
   } else {
-    std::vector<MixEntry> seq;
-    std::vector<float> share;
-    plan_mix(c.m, in_peer, seq, share, /*with_idle=*/true);
-    hipError_t e = hipSuccess;
-    const int slot = ctx->mixtab.upload(seq.data(), seq.size() * sizeof(MixEntry), stream, &e);
-    if (slot < 0) return fail_hip(ctx, e, "upload of the mixing entries");
-    MixArgs x{};
-    x.tiles = ctx->d_otiles;
-    x.tensors = ctx->d_tensors;
-    x.xtab_t = ctx->d_xtab_t;
-    x.ntiles = ctx->n_otiles;
-    x.m = c.m;
-    const MixEntry *d_seq = static_cast<const MixEntry *>(ctx->mixtab.d[slot]);
-    for (const auto &r : mix_launch_ranges(seq)) {
-      x.seq = d_seq + r.first;
+    MixArgs x = mix_args(ctx);
+    int launched = 0;
+    for (const auto &r : sm.ranges) {
+      x.seq = sm.d_seq + r.first;
       x.len = r.second - r.first;
-      e = launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
-                                ctx->buffers_zero, ctx->tune, stream);
-      if (e != hipSuccess) return fail_hip(ctx, e, "fused local+mixing kernel launch");
+      const hipError_t e = guarded(ctx, [&] {
+        return launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
+                                     ctx->buffers_zero, ctx->tune, stream);
+      });
+      if (e != hipSuccess)
+        return launched ? fail_midway(ctx, e, "fused local+mixing kernel launch")
+                        : fail_hip(ctx, e, "fused local+mixing kernel launch");
+      ++launched;
     }
-    finish_local(ctx);
   }
+  // counters and weights move only after the last launch was accepted
+  finish_local(ctx);
   mix_weights(ctx, in_peer);
   return SLOWMO_OK;
 }
@@ -853,8 +953,14 @@ slowmo_status slowmo_get_pushsum_weights(const slowmo_ctx *ctx, float *w) {
   return SLOWMO_OK;
 }
 
-slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
-  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+namespace {
+
+// z = x / w for every worker.  The table the kernel reads (m * n_tensors
+// destination pointers, then the m weights) is written straight into a pinned
+// staging buffer of the context and sent to `table_dev` (NULL: the staging
+// slot's own device copy inside the workspace).  Allocates nothing.
+slowmo_status debias_into(slowmo_ctx *ctx, float *const *z, void *table_dev, hipStream_t stream) {
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!z) return fail(ctx, SLOWMO_ERR_ARG, "z is NULL");
   const int32_t m = ctx->cfg.m, nt = ctx->n_tensors;
   const size_t n_ptr = static_cast<size_t>(m) * nt;
@@ -872,24 +978,32 @@ slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
     }
   }
   if (ctx->n_ltiles == 0) return SLOWMO_OK;
-  std::vector<char> table(ztab_bytes(m, nt));
-  std::memcpy(table.data(), z, n_ptr * sizeof(void *));
-  std::memcpy(table.data() + n_ptr * sizeof(void *), ctx->w.data(), m * sizeof(float));
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
   hipError_t e = hipSuccess;
-  const int slot = ctx->ztab.upload(table.data(), table.size(), stream, &e);
-  if (slot < 0) return fail_hip(ctx, e, "upload of the de-bias table");
+  const int slot = ctx->ztab.stage(&e);
+  if (slot < 0) return fail_hip(ctx, e, "waiting for a staging buffer of the de-bias table");
+  char *table = static_cast<char *>(ctx->ztab.h[slot]);
+  std::memcpy(table, z, n_ptr * sizeof(void *));
+  std::memcpy(table + n_ptr * sizeof(void *), ctx->w.data(), m * sizeof(float));
+  e = ctx->ztab.send(slot, ztab_bytes(m, nt), table_dev, stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "upload of the de-bias table");
+  const char *dev = static_cast<const char *>(table_dev ? table_dev : ctx->ztab.d[slot]);
   DebiasArgs a{};
   a.tiles = ctx->d_ltiles;
   a.slots = ctx->d_slots;
-  a.ztab = static_cast<float *const *>(ctx->ztab.d[slot]);
-  a.w = reinterpret_cast<const float *>(static_cast<const char *>(ctx->ztab.d[slot]) +
-                                        n_ptr * sizeof(void *));
+  a.ztab = reinterpret_cast<float *const *>(dev);
+  a.w = reinterpret_cast<const float *>(dev + n_ptr * sizeof(void *));
   a.ntiles = ctx->n_ltiles;
   a.n_tensors = nt;
-  e = launch_debias(a, ctx->tune, stream);
+  e = guarded(ctx, [&] { return launch_debias(a, ctx->tune, stream); });
   if (e != hipSuccess) return fail_hip(ctx, e, "de-bias kernel launch");
   return SLOWMO_OK;
+}
+
+}  // namespace
+
+slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  return debias_into(ctx, z, nullptr, static_cast<hipStream_t>(stream_));
 }
 
 slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_decay,
@@ -1002,6 +1116,7 @@ slowmo_status slowmo_export_state(slowmo_ctx *ctx, void *dst, size_t bytes, void
 
 slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  if (ctx->broken) return fail(ctx, SLOWMO_ERR_STATE, kBrokenMsg);
   if (!src) return fail(ctx, SLOWMO_ERR_ARG, "src is NULL");
   const BlobParts p = blob_parts(ctx);
   if (bytes < p.total) return fail(ctx, SLOWMO_ERR_ARG, "blob shorter than this context's state");
@@ -1015,7 +1130,8 @@ slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes
   if (hd.m != ctx->cfg.m || hd.n_tensors != ctx->n_tensors || hd.base != ctx->cfg.base ||
       hd.no_average != ctx->cfg.no_average || hd.d != ctx->layout.d || hd.d_pad != ctx->layout.d_pad)
     return fail(ctx, SLOWMO_ERR_ARG, "the blob was exported from a different configuration or tensor list");
-  if (hd.k < 0 || hd.k > ctx->cfg.tau || hd.t < 0 || hd.l < 0)
+  if (hd.k < 0 || hd.k > ctx->cfg.tau || hd.t < 0 || hd.l < 0 ||
+      (hd.buffers_zero != 0 && hd.buffers_zero != 1))
     return fail(ctx, SLOWMO_ERR_ARG, "the blob's counters do not fit this configuration");
   const char *in = static_cast<const char *>(src);
   size_t off = sizeof(hd);
@@ -1026,16 +1142,22 @@ slowmo_status slowmo_import_state(slowmo_ctx *ctx, const void *src, size_t bytes
   for (float wi : w)
     if (!finite_pos(wi)) return fail(ctx, SLOWMO_ERR_ARG, "the blob's push-sum weights are not positive");
   off += p.weights;
+  // everything checkable has been checked: only now is the context touched
+  bool copied = false;
   auto get = [&](float *dst, size_t n) {
-    if (e == hipSuccess && n)
+    if (e == hipSuccess && n) {
       e = hipMemcpyAsync(dst, in + off, n, hipMemcpyDeviceToDevice, stream);
+      copied = copied || e == hipSuccess;
+    }
     off += n;
   };
   get(ctx->x0, p.arena * p.outer_copies);
   get(ctx->u, p.arena * p.outer_copies);
   get(ctx->h, p.arena * ctx->cfg.m);
   get(ctx->v, p.arena * p.n_v);
-  if (e != hipSuccess) return fail_hip(ctx, e, "state import");
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess)
+    return copied ? fail_midway(ctx, e, "state import") : fail_hip(ctx, e, "state import");
   ctx->t = hd.t;
   ctx->k = hd.k;
   ctx->l = hd.l;
