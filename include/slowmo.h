@@ -287,6 +287,30 @@ slowmo_status slowmo_get_pushsum_weights(const slowmo_ctx *ctx, float *w);
 slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream);
 
 /*
+ * slowmo_debias for callers that cannot allocate device memory or spare
+ * workspace for it: code recorded into a HIP graph, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results bit for bit.
+ * The table its kernel reads (the m * n_tensors destination pointers and the
+ * m weights), which slowmo_debias places in the caller's workspace, lives here
+ * in a static device array inside the library (528 KiB per GPU, held until the
+ * process ends), so the call makes no hipMalloc / hipFree and no other
+ * allocating call; it fills a pinned staging buffer that slowmo_create
+ * allocated, enqueues one copy and one kernel on `stream`.
+ *   Limit: m * n_tensors <= SLOWMO_STATIC_MAX_POINTERS, else NOMEM (use
+ *   slowmo_debias).
+ *   The array is shared by all contexts on a GPU and keeps the previous
+ *   call's table; a call overwrites the part it uses and its kernel reads
+ *   nothing beyond that, so no clearing is needed.  Calls on ONE stream are
+ *   ordered and safe; calls that overlap on one GPU (different streams or
+ *   threads, any contexts) race for the array: order them.
+ *   The context's device must be the current device.
+ * Errors: as slowmo_debias; NOMEM beyond the limit; STATE if another device is
+ * current or the context is unusable.
+ */
+#define SLOWMO_STATIC_MAX_POINTERS 65536
+slowmo_status slowmo_debias_static(slowmo_ctx *ctx, float *const *z, void *stream);
+
+/*
  * The communication pattern of Appendix C.1 (one-peer, time-varying directed
  * exponential graph): at iteration `step` every worker receives from the
  * worker 2^(step mod L) ranks below it (mod m), L = floor(log2(m-1)) + 1.

@@ -22,6 +22,7 @@ SLOWMO_BUF_RESET, SLOWMO_BUF_MAINTAIN, SLOWMO_BUF_AVERAGE = 0, 1, 2
 SLOWMO_F32, SLOWMO_BF16 = 0, 1
 SLOWMO_BUF_X0, SLOWMO_BUF_U, SLOWMO_BUF_H, SLOWMO_BUF_V = 0, 1, 2, 3
 SLOWMO_MAX_WORKERS = 1024
+SLOWMO_STATIC_MAX_POINTERS = 65536
 
 STATUS_NAMES = {0: "SLOWMO_OK", -1: "SLOWMO_ERR_ARG", -2: "SLOWMO_ERR_STATE",
                 -3: "SLOWMO_ERR_ALIGN", -4: "SLOWMO_ERR_HIP", -5: "SLOWMO_ERR_NOMEM"}
@@ -33,7 +34,7 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
            "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step",
            "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix",
-           "slowmo_local_mix_step", "slowmo_check_device_range"]
+           "slowmo_local_mix_step", "slowmo_check_device_range", "slowmo_debias_static"]
 
 
 (SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
@@ -114,6 +115,8 @@ def lib() -> C.CDLL:
     L.slowmo_get_pushsum_weights.restype = C.c_int
     L.slowmo_debias.argtypes = [vp, C.POINTER(vp), vp]
     L.slowmo_debias.restype = C.c_int
+    L.slowmo_debias_static.argtypes = [vp, C.POINTER(vp), vp]
+    L.slowmo_debias_static.restype = C.c_int
     L.slowmo_expgraph_in_peers.argtypes = [i32, i64, C.POINTER(i32)]
     L.slowmo_expgraph_in_peers.restype = C.c_int
     L.slowmo_set_tensor_hparams.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
@@ -234,6 +237,13 @@ def slowmo_debias(ctx, z, stream: int = 0) -> None:
     """z: m * n_tensors device addresses that receive x^{(i)} / w_i."""
     arr = z if (z is None or isinstance(z, C.Array)) else _ptr_array(z)
     _check(lib().slowmo_debias(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_debias_static(ctx, z, stream: int = 0) -> None:
+    """slowmo_debias with its table in the library's static device array
+    (no allocation; m * n_tensors <= SLOWMO_STATIC_MAX_POINTERS)."""
+    arr = z if (z is None or isinstance(z, C.Array)) else _ptr_array(z)
+    _check(lib().slowmo_debias_static(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
 
 
 def slowmo_expgraph_in_peers(m: int, step: int):

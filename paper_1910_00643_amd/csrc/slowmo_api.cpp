@@ -246,6 +246,8 @@ struct slowmo_ctx {
   bool params_aligned = true;  // every replica pointer is 16-byte aligned
   int32_t check_pointers = 1;  // 1: caller's tensors are checked at create; 2: also per call
 
+  void *static_table = nullptr;  // this device's static scratch (slowmo_debias_static)
+
   // A call that launches several kernels and fails between two of them has
   // changed device memory halfway: the context then refuses further work.
   bool broken = false;
@@ -489,6 +491,9 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   CREATE_HIP(ctx->mixtab.init(base, sec.mixtab, mixtab_bytes(m)), "mixing-table ring");
   CREATE_HIP(ctx->ztab.init(base, sec.ztab, ztab_bytes(m, n_tensors)), "de-bias table ring");
   ctx->w.assign(m, 1.0f);
+  // set-up for the entry point that may not allocate: this device's address of
+  // the library's static scratch array (the create call runs with it current)
+  CREATE_HIP(static_scratch(ctx->device, &ctx->static_table), "address of the static scratch array");
 
   // device tables
   const Layout &L = ctx->layout;
@@ -1004,6 +1009,23 @@ slowmo_status debias_into(slowmo_ctx *ctx, float *const *z, void *table_dev, hip
 slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
   return debias_into(ctx, z, nullptr, static_cast<hipStream_t>(stream_));
+}
+
+slowmo_status slowmo_debias_static(slowmo_ctx *ctx, float *const *z, void *stream_) {
+  static_assert(SLOWMO_STATIC_MAX_POINTERS == kStaticMaxPointers, "header and library disagree");
+  static_assert(SLOWMO_MAX_WORKERS <= kStaticMaxWorkers, "weights must fit the static table");
+  if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
+  const size_t n_ptr = static_cast<size_t>(ctx->cfg.m) * ctx->n_tensors;
+  if (n_ptr > kStaticMaxPointers)
+    return fail(ctx, SLOWMO_ERR_NOMEM,
+                "m * n_tensors = " + std::to_string(n_ptr) + " exceeds SLOWMO_STATIC_MAX_POINTERS = " +
+                    std::to_string(kStaticMaxPointers) + ": use slowmo_debias");
+  int current = -1;
+  const hipError_t e = hipGetDevice(&current);
+  if (e != hipSuccess) return fail_hip(ctx, e, "hipGetDevice");
+  if (current != ctx->device)
+    return fail(ctx, SLOWMO_ERR_STATE, "the context's device is not the current device");
+  return debias_into(ctx, z, ctx->static_table, static_cast<hipStream_t>(stream_));
 }
 
 slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_decay,

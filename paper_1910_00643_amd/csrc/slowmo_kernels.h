@@ -111,6 +111,18 @@ hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d
                                  int32_t n_tensors, int base, bool bf16, bool first,
                                  const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
+
+// Static device memory for the entry point that allocates nothing: room for
+// the de-bias table (destination pointers, then the push-sum weights) of up to
+// kStaticMaxPointers (worker, tensor) pairs.
+constexpr size_t kStaticMaxPointers = 65536;
+constexpr size_t kStaticMaxWorkers = 1024;
+constexpr size_t kStaticScratchBytes =
+    kStaticMaxPointers * sizeof(void *) + kStaticMaxWorkers * sizeof(float);
+// Address of that memory on `device`.  The first call for a device must be made
+// with that device current (it asks the runtime for the symbol's address
+// there); later calls return the remembered address without any HIP call.
+hipError_t static_scratch(int device, void **ptr);
 hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &tune,
                                    hipStream_t stream);
 

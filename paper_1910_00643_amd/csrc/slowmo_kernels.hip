@@ -29,7 +29,41 @@
 // in the order written here, which is the order of Table C.1 and Eq. (2)-(3).
 #include "slowmo_kernels.h"
 
+#include <mutex>
+
+// Device memory of the allocation-free entry point (slowmo_debias_static): the
+// table its kernel reads.  One copy per GPU, held until the process ends.  In
+// host code this name is only a handle for hipGetSymbolAddress -- the address
+// kernels and copies use is the one static_scratch() returns.
+static __device__ __align__(256) unsigned char scratch[slowmo::kStaticScratchBytes];
+
 namespace slowmo {
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+}  // namespace
+
+hipError_t static_scratch(int device, void **ptr) {
+  *ptr = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    int current = -1;
+    hipError_t e = hipGetDevice(&current);
+    if (e != hipSuccess) return e;
+    if (current != device) return hipErrorInvalidDevice;  // each GPU has its own copy and address
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+  }
+  *ptr = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 namespace {
 
