@@ -12,6 +12,24 @@ from . import generator as _gen
 from .workloads import Workload
 
 
+class IndexPlan:
+    """Global element indices grouped by tensor: groups = [(tensor, offsets
+    inside it as a device index tensor)], order = positions of those elements
+    in the index array, group after group."""
+
+    def __init__(self, prob: "GpuProblem", index: np.ndarray):
+        self.index = np.asarray(index, dtype=np.int64)
+        tensor, off = prob.locate(self.index)
+        order = np.argsort(tensor, kind="stable")
+        cuts = np.searchsorted(tensor[order], np.arange(len(prob.numel) + 1))
+        self.order = order
+        self.groups = []
+        for j in range(len(prob.numel)):
+            a, b = int(cuts[j]), int(cuts[j + 1])
+            if b > a:
+                self.groups.append((j, prob.torch.from_numpy(off[order[a:b]]).to(prob.device)))
+
+
 class GpuProblem:
     """params[i][j]   worker i's replica of tensor j (fp32).  Worker 0 holds
                       the seeded x_{0,0}; the others are zero until the
@@ -112,17 +130,30 @@ class GpuProblem:
         tensor = np.searchsorted(ends, index, side="right")
         return tensor, index - self.starts[tensor]
 
-    def gather(self, tensors: Sequence, index: np.ndarray) -> np.ndarray:
+    def plan(self, index: np.ndarray) -> "IndexPlan":
+        """Bookkeeping for repeated gathers at the same global indices."""
+        return IndexPlan(self, index)
+
+    def gather(self, tensors: Sequence, index) -> np.ndarray:
         """Values of a per-tensor list (e.g. one worker's replica) at global
-        element indices, as a host float32 array."""
+        element indices (an array, or a plan() of one), as a host float32 array."""
         torch = self.torch
-        tensor, off = self.locate(index)
-        out = np.empty(index.shape, dtype=np.float32)
-        for j in np.unique(tensor):
-            sel = np.nonzero(tensor == j)[0]
-            idx = torch.from_numpy(off[sel]).to(self.device)
-            out[sel] = tensors[int(j)].reshape(-1)[idx].to(torch.float32).cpu().numpy()
+        plan = index if isinstance(index, IndexPlan) else IndexPlan(self, index)
+        out = np.empty(plan.index.shape, dtype=np.float32)
+        if plan.index.size == 0:
+            return out
+        parts = [tensors[j].reshape(-1)[idx] for j, idx in plan.groups]
+        out[plan.order] = torch.cat(parts).to(torch.float32).cpu().numpy()
         return out
+
+    def gather_all(self, tensors: Sequence) -> np.ndarray:
+        """All values of a per-tensor list in global element order (one
+        concatenation on the device, one copy), as a host float32 array."""
+        torch = self.torch
+        if self.d == 0:
+            return np.empty(0, dtype=np.float32)
+        flat = torch.cat([t.reshape(-1) for t in tensors]).to(torch.float32)
+        return flat.cpu().numpy()
 
     def sample_indices(self, n_random: int, edges: Sequence[int] = (), halo: int = 8,
                        seed: int = 0) -> np.ndarray:

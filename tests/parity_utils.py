@@ -17,24 +17,34 @@ from slowmo_inputs import workloads as W
 # divided by gamma, so the same bound is applied to gamma*u, which has x's units.
 # h and v are sums of gradient-sized (sigma) resp. sigma^2-sized terms: the same
 # relative bound with sigma resp. sigma^2 as the unit.
-def assert_params_close(got, want, what):
-    want = np.asarray(want, dtype=np.float64)
-    err = np.abs(np.asarray(got, dtype=np.float64) - want) / (1.0 + np.abs(want))
-    assert err.max(initial=0.0) <= 1e-5, f"{what}: max |d|/(1+|x|) = {err.max():.3e}"
+def _worst(got, want, scale, unit):
+    """max over all elements of scale*|got - want| / (unit + scale*|want|),
+    one row (worker) at a time so that whole-model arrays need no huge
+    temporaries."""
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    if got.ndim == 2 and got.size > (1 << 24):
+        return max((_worst(g, w_, scale, unit) for g, w_ in zip(got, want)), default=0.0)
+    want = want.astype(np.float64, copy=False)
+    err = scale * np.abs(got.astype(np.float64) - want) / (unit + scale * np.abs(want))
     return float(err.max(initial=0.0))
+
+
+def assert_params_close(got, want, what):
+    worst = _worst(got, want, 1.0, 1.0)
+    assert worst <= 1e-5, f"{what}: max |d|/(1+|x|) = {worst:.3e}"
+    return worst
 
 
 def assert_u_close(got, want, lr, what):
-    want = np.asarray(want, dtype=np.float64)
-    err = lr * np.abs(np.asarray(got, dtype=np.float64) - want) / (1.0 + lr * np.abs(want))
-    assert err.max(initial=0.0) <= 1e-5, f"{what}: max = {err.max():.3e}"
-    return float(err.max(initial=0.0))
+    worst = _worst(got, want, lr, 1.0)
+    assert worst <= 1e-5, f"{what}: max = {worst:.3e}"
+    return worst
 
 
 def assert_buffer_close(got, want, what, unit):
-    want = np.asarray(want, dtype=np.float64)
-    err = np.abs(np.asarray(got, dtype=np.float64) - want) / (unit + np.abs(want))
-    assert err.max(initial=0.0) <= 1e-5, f"{what}: max |d|/({unit:g}+|.|) = {err.max():.3e}"
+    worst = _worst(got, want, 1.0, unit)
+    assert worst <= 1e-5, f"{what}: max |d|/({unit:g}+|.|) = {worst:.3e}"
 
 
 def buffer_snapshot_step(w):
@@ -47,8 +57,13 @@ def buffer_snapshot_step(w):
 
 
 # ---- oracle side ----------------------------------------------------------------
-def make_oracle(w, index, prec="f64"):
-    return O.SlowMoOracle(G.initial_params(w.seed, index), m=w.m, tau=w.tau,
+def make_oracle(w, index, prec="f64", x_init=None):
+    """index: the global element indices the oracle runs on (None: all of
+    them, which needs x_init).  x_init: the starting point at those indices if
+    it was read back from the device generator instead of computed on the host."""
+    if x_init is None:
+        x_init = G.initial_params(w.seed, index)
+    return O.SlowMoOracle(x_init, m=w.m, tau=w.tau,
                           alpha=w.f32("alpha"), beta=w.f32("beta"), base=w.base,
                           policy=w.policy, momentum=w.f32("momentum"),
                           weight_decay=w.f32("weight_decay"), beta1=w.f32("beta1"),
@@ -62,9 +77,12 @@ def _oracle_groups(w, index):
     values are the fp32 numbers the library receives."""
     if w.tensor_wd is None and w.tensor_lr_scale is None:
         return {}
-    ends = w.tensor_starts + np.asarray(w.numel, dtype=np.int64)
-    tensor = np.searchsorted(ends, np.asarray(index, dtype=np.int64), side="right")
-    sizes = np.bincount(tensor, minlength=len(w.numel))
+    if index is None:
+        sizes = np.asarray(w.numel, dtype=np.int64)
+    else:
+        ends = w.tensor_starts + np.asarray(w.numel, dtype=np.int64)
+        tensor = np.searchsorted(ends, np.asarray(index, dtype=np.int64), side="right")
+        sizes = np.bincount(tensor, minlength=len(w.numel))
     f32 = lambda vals: None if vals is None else [float(np.float32(v)) for v in vals]  # noqa: E731
     return dict(tensor_sizes=sizes.tolist(), tensor_weight_decay=f32(w.tensor_wd),
                 tensor_lr_scale=f32(w.tensor_lr_scale))
@@ -75,17 +93,42 @@ def oracle_grads(w, index, step):
                      for i in range(w.m)])
 
 
-def run_oracles(w, index, rounds, precs=("f64",)):
+def device_grads(w, prob, index, step):
+    """The gradients of global step `step` at `index` (None: everywhere) as the
+    DEVICE generator writes them into ring slot 0 -- the same bits as the host
+    generator's (a test of its own), without NumPy's generation time."""
+    prob.fill_grads(0, step)
+    return np.stack([gather(prob, prob.grads[0][i], index) for i in range(w.m)])
+
+
+_plans = {}
+
+
+def gather(prob, tensors, index):
+    """Values at `index` (None: everywhere).  The grouping of an index array
+    by tensor is worked out once and kept while that array is alive."""
+    if index is None:
+        return prob.gather_all(tensors)
+    key = (id(prob), id(index))
+    if key not in _plans or _plans[key][0] is not index:
+        if len(_plans) > 8:
+            _plans.clear()
+        _plans[key] = (index, prob.plan(index))
+    return prob.gather(tensors, _plans[key][1])
+
+
+def run_oracles(w, index, rounds, precs=("f64",), x_init=None, grad_fn=None):
     """Runs the oracle builds named in `precs` side by side on the same
-    gradients.  Returns {prec: (oracle after the last outer step, snapshot
-    taken after the local steps of the last round: dict with x, h, v)}."""
-    os_ = {p: make_oracle(w, index, p) for p in precs}
+    gradients (grad_fn(step) -> (m, n) float32, default: the host generator).
+    Returns {prec: (oracle after the last outer step, snapshot taken after the
+    local steps of the last round: dict with x, h, v)}."""
+    os_ = {p: make_oracle(w, index, p, x_init) for p in precs}
     lr = w.f32("lr")
     snaps = {p: {} for p in precs}
     kb = buffer_snapshot_step(w)
     for t in range(rounds):
         for k in range(w.tau):
-            g = oracle_grads(w, index, t * w.tau + k)
+            g = grad_fn(t * w.tau + k) if grad_fn else oracle_grads(w, index, t * w.tau + k)
             for p, o in os_.items():
                 o.local_step(g, lr)
                 if w.mix == "expgraph":     # stochastic gradient push: step, then gossip
@@ -163,32 +206,38 @@ def run_gpu(w, prob, opt, rounds, index, fused_last=False, fused_mix=False):
 def gpu_state(w, prob, opt, index, with_outer=True):
     nt = len(prob.numel)
     out = dict(
-        x=np.stack([prob.gather(prob.params[i], index) for i in range(w.m)]),
-        h=np.stack([prob.gather([opt.buffer("h", j, i) for j in range(nt)], index)
+        x=np.stack([gather(prob, prob.params[i], index) for i in range(w.m)]),
+        h=np.stack([gather(prob, [opt.buffer("h", j, i) for j in range(nt)], index)
                     for i in range(w.m)]))
     out["v"] = None
     if w.base == "adam":
-        out["v"] = np.stack([prob.gather([opt.buffer("v", j, i) for j in range(nt)], index)
+        out["v"] = np.stack([gather(prob, [opt.buffer("v", j, i) for j in range(nt)], index)
                              for i in range(w.m)])
     if with_outer and w.exact_average:
-        out["x0"] = prob.gather([opt.buffer("x0", j) for j in range(nt)], index)
-        out["u"] = prob.gather([opt.buffer("u", j) for j in range(nt)], index)
+        out["x0"] = gather(prob, [opt.buffer("x0", j) for j in range(nt)], index)
+        out["u"] = gather(prob, [opt.buffer("u", j) for j in range(nt)], index)
     elif with_outer:            # every worker has its own x0 and u
         for key in ("x0", "u"):
-            out[key] = np.stack([prob.gather([opt.buffer(key, j, i) for j in range(nt)], index)
+            out[key] = np.stack([gather(prob, [opt.buffer(key, j, i) for j in range(nt)], index)
                                  for i in range(w.m)])
     return out
 
 
 def compare_run(w, prob, opt, index, rounds, bitwise_f32=False, fused_last=False,
-                fused_mix=False):
-    """Full comparison of a finished GPU run against the oracle on `index`.
-    With fused_last, every outer iteration but the final one (whose replicas
-    are inspected before the outer step) ends with slowmo_local_outer_step."""
+                fused_mix=False, device_inputs=False):
+    """Full comparison of a finished GPU run against the oracle on `index`
+    (None: every element).  With fused_last, every outer iteration but the
+    final one (whose replicas are inspected before the outer step) ends with
+    slowmo_local_outer_step.  device_inputs: the oracle's starting point and
+    gradients are read back from the device generator (for index sets too
+    large to generate with NumPy in reasonable time)."""
     lr = w.f32("lr")
+    x_init = gather(prob, prob.params[0], index) if device_inputs else None   # before any step
     snap = run_gpu(w, prob, opt, rounds, index, fused_last=fused_last, fused_mix=fused_mix)
     final = gpu_state(w, prob, opt, index)
-    res = run_oracles(w, index, rounds, ("f64", "f32") if bitwise_f32 else ("f64",))
+    grad_fn = (lambda step: device_grads(w, prob, index, step)) if device_inputs else None
+    res = run_oracles(w, index, rounds, ("f64", "f32") if bitwise_f32 else ("f64",),
+                      x_init=x_init, grad_fn=grad_fn)
     o64, s64 = res["f64"]
     worst = {}
     worst["x_local"] = assert_params_close(snap["x"], s64["x"], "replicas after the local steps")

@@ -758,15 +758,46 @@ def test_failed_mixing_calls_leave_replicas_weights_and_counters_unchanged():
     opt.close()
 
 
+# ---- full sizes, every element ---------------------------------------------------
+def _every_element(w, rounds):
+    """The whole model, in the launch configuration bench.py times (separate
+    parameter allocations, 512-byte aligned gradient tensors, the fused call at
+    the end of every outer iteration but the last, which ends with the two
+    separate calls): every element of every replica, of h, x0 and u against the
+    fp64 oracle within the tolerance and against the fp32 oracle bit for bit.
+    The oracle's inputs are read back from the device generator."""
+    prob = _problem(w, ring=2, grad_layout="padded")
+    opt = PU.make_gpu(w, prob)
+    worst = PU.compare_run(w, prob, opt, None, rounds, bitwise_f32=True, fused_last=True,
+                           device_inputs=True)
+    print(w.name, "every element of", w.d, "x", w.m, "workers,", rounds, "rounds: worst errors",
+          worst, flush=True)
+    opt.close()
+
+
+def test_resnet18_shaped_every_element():
+    w = W.resnet18()
+    _every_element(w, w.rounds)             # all 20 outer iterations
+
+
+def test_resnet50_shaped_every_element():
+    _every_element(W.resnet50(), 2)         # 32 replicas of 25.6M elements, 24 local steps
+
+
 # ---- full sizes, sampled elements ------------------------------------------------
-def _sampled(w, rounds, n_random, ring=2, halo=4):
+def _sampled(w, rounds, n_random, ring=2, halo=4, slab=None):
+    """slab = (first, count): a dense run of consecutive global indices checked
+    in full in addition to the sample; its inputs for the oracle are read back
+    from the device generator."""
     prob = _problem(w, ring=ring, grad_layout="padded")     # the layout bench.py times
     opt = PU.make_gpu(w, prob)
     idx = prob.sample_indices(n_random, edges=_tile_edges(w), halo=halo, seed=w.seed)
+    if slab is not None:
+        idx = np.union1d(idx, np.arange(slab[0], slab[0] + slab[1], dtype=np.int64))
     # as bench.py runs it: outer iterations end with the fused call where that applies
     worst = PU.compare_run(w, prob, opt, idx, rounds, bitwise_f32=(w.base == "sgd_nesterov"),
                            fused_last=(w.exact_average and w.mix == "none"),
-                           fused_mix=(w.mix != "none"))
+                           fused_mix=(w.mix != "none"), device_inputs=slab is not None)
     print(w.name, "sampled", idx.size, "worst errors", worst)
     opt.close()
 
@@ -782,8 +813,13 @@ def test_resnet50_shaped_sampled():
 
 
 def test_transformer_big_shaped_sampled():
+    """Sampled indices plus a dense slab of 3.2M consecutive elements that runs
+    from inside the embedding across the first encoder layer's q, k (weights
+    and biases) into v: six tensors, two of them 1024 elements long."""
     w = W.transformer_big()
-    _sampled(w, w.rounds, 3000)
+    emb = w.numel[0]
+    assert emb == 32768 * 1024 and w.numel[1:5] == [1024 * 1024, 1024, 1024 * 1024, 1024]
+    _sampled(w, w.rounds, 3000, slab=(emb - 1_000_000, 3_200_000))
 
 
 def test_resnet50_shaped_noaverage_sampled():
@@ -815,4 +851,5 @@ def test_stress_1e9_sampled():
     """d = 1e9, m = 8: 96 GB of replicas, momentum and gradients; element and
     byte offsets beyond 32 bits."""
     w = W.stress()
-    _sampled(w, w.rounds, 6000, ring=1)
+    # dense slab: 4M elements across the 2 GiB byte offset of the replica (element 2^29)
+    _sampled(w, w.rounds, 6000, ring=1, slab=((1 << 29) - 2_000_000, 4_000_000))
