@@ -22,17 +22,36 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+LIB = os.path.join(ROOT, "paper_1910_00643_amd", "libslowmo.so")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {
-    "resnet50": 16407838272,            # profiles/resnet50_local_step_outer_step.md
-    "transformer_big": 43766547359,     # profiles/transformer_big_local_step_outer_step.md
-    # k_local_mix_step, per step (all its launches), profiles/resnet50_average_noaverage_mixing.md
-    ("resnet50", "expgraph"): 16366373785,
-    ("resnet50", "random"): 17971173213,
-}
+
+def mangled(kernel: str) -> str:
+    """The symbol-name fragment of a kernel given as rocprofv3 prints it, e.g.
+    'k_local_step<0, false, true>' -> '12k_local_stepILi0ELb0ELb1EEE' (integer
+    and bool template arguments only, which is all the library's kernels have)."""
+    name, _, rest = kernel.partition("<")
+    args = [a.strip() for a in rest.rstrip(">").split(",")] if rest else []
+    enc = "".join("Lb1E" if a == "true" else "Lb0E" if a == "false" else f"Li{int(a)}E"
+                  for a in args)
+    return f"{len(name)}{name}" + (f"I{enc}E" if args else "")
+
+
+def measured_traffic(workload: str, variant: str):
+    """HBM bytes per launch of the variant's dominant kernel from the rocprofv3
+    --pmc runs recorded in profiles/traffic.json (written together with the
+    profile summaries by slowmo_inputs/profile_summary.py), or None: nothing
+    recorded, or the library no longer contains the kernel it was measured for
+    (the number would be stale)."""
+    try:
+        entries = json.load(open(TRAFFIC_FILE))["entries"]
+        lib = open(LIB, "rb").read()
+    except (OSError, ValueError, KeyError):
+        return None
+    for e in entries:
+        if e["workload"] == workload and e["variant"] == variant:
+            return e["bytes_per_launch"] if mangled(e["kernel"]).encode() in lib else None
+    return None
 
 
 def local_bytes_per_update(w, first: bool, last: bool = False) -> int:
@@ -104,9 +123,30 @@ def build_problem(w, ring):
     return prob, opt
 
 
-def run_rounds(w, opt, arrays, rounds, events=None, fused=False, fused_mix=False):
+def _bracket(events, kind):
+    """Context manager: HIP events on torch's current stream -- the stream the
+    library's kernels are launched on -- around one library call."""
+    import contextlib
+    import torch
+
+    @contextlib.contextmanager
+    def cm():
+        if events is None:
+            yield
+            return
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        yield
+        b.record()
+        events[kind].append((a, b))
+    return cm()
+
+
+def run_rounds(w, opt, arrays, rounds, events=None, marks=None, fused=False, fused_mix=False):
     """`rounds` outer iterations.  With `events`, brackets every call with HIP
-    events on the stream the kernels are launched on (torch's current one)."""
+    events; with `marks`, records one event at the start of every outer
+    iteration and one after the last (per-iteration durations without any
+    synchronization inside the timed region)."""
     import torch
     import paper_1910_00643_amd as P
     ring = len(arrays)
@@ -116,77 +156,150 @@ def run_rounds(w, opt, arrays, rounds, events=None, fused=False, fused_mix=False
     elif w.mix == "random":     # any in-neighbour map: the general (push-sum) kernel
         from slowmo_inputs.workloads import in_peers
         peers = [in_peers(w, s).tolist() for s in range(16)]
+    reset = w.policy == "reset"
+
+    def mark():
+        if marks is not None:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            marks.append(e)
+
     for _ in range(rounds):
+        mark()
         for k in range(w.tau):
             if fused and k == w.tau - 1:        # last local step + outer step, one call
-                if events is not None:
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                opt.local_outer_step(arrays[k % ring], w.lr)
-                if events is not None:
-                    b.record()
-                    events["fused_last_outer"].append((a, b))
+                with _bracket(events, "fused_last_outer"):
+                    opt.local_outer_step(arrays[k % ring], w.lr)
                 break
             if peers is not None and fused_mix:     # local step + gossip step, one call
-                if events is not None:
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                opt.local_mix_step(arrays[k % ring], w.lr, peers[k % len(peers)])
-                if events is not None:
-                    b.record()
-                    reset = w.policy == "reset"
-                    events["local_mix_first" if (reset and k == 0) else "local_mix"].append((a, b))
+                with _bracket(events, "local_mix_first" if (reset and k == 0) else "local_mix"):
+                    opt.local_mix_step(arrays[k % ring], w.lr, peers[k % len(peers)])
                 continue
-            if events is not None:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-            opt.local_step(arrays[k % ring], w.lr)
-            if events is not None:
-                b.record()
-                reset = w.policy == "reset"
-                kind = ("local_first" if (reset and k == 0) else
-                        "local_last" if (reset and k == w.tau - 1) else "local")
-                events[kind].append((a, b))
+            kind = ("local_first" if (reset and k == 0) else
+                    "local_last" if (reset and k == w.tau - 1) else "local")
+            with _bracket(events, kind):
+                opt.local_step(arrays[k % ring], w.lr)
             if peers is not None:           # SGP as base optimizer: gossip after every step
-                if events is not None:
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                opt.mix_step(peers[k % len(peers)])
-                if events is not None:
-                    b.record()
-                    events["mix"].append((a, b))
+                with _bracket(events, "mix"):
+                    opt.mix_step(peers[k % len(peers)])
         else:
-            if events is not None:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-            opt.outer_step(w.lr)
-            if events is not None:
-                b.record()
-                events["outer"].append((a, b))
+            with _bracket(events, "outer"):
+                opt.outer_step(w.lr)
+    mark()
 
 
-def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False):
+def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False, kernel_rounds=None):
+    """Returns (wall seconds of the `steps` timed outer iterations, their
+    individual durations in ms from HIP events, average ms per call kind from a
+    second pass of `kernel_rounds` iterations with events around every call)."""
     import torch
     ring = ring or w.tau
     prob, opt = build_problem(w, ring)
     arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(ring)]
     run_rounds(w, opt, arrays, warmup, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
+    marks = []
     t0 = time.perf_counter()
-    run_rounds(w, opt, arrays, steps, fused=fused, fused_mix=fused_mix)
+    run_rounds(w, opt, arrays, steps, marks=marks, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    round_ms = [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
     # second pass: per-kernel durations from HIP events around every launch
     events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": [],
               "fused_last_outer": [], "local_mix": [], "local_mix_first": []}
-    run_rounds(w, opt, arrays, steps, events, fused=fused, fused_mix=fused_mix)
+    run_rounds(w, opt, arrays, kernel_rounds or steps, events, fused=fused, fused_mix=fused_mix)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
                for k, v in events.items()}
     opt.close()
     del prob, opt
     torch.cuda.empty_cache()
-    return wall, kern_ms
+    return wall, round_ms, kern_ms
+
+
+def _median(v):
+    v = sorted(v)
+    n = len(v)
+    return None if not n else v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
+
+
+def variant_name(w) -> str:
+    """Key of a workload variant in profiles/traffic.json."""
+    if w.mix != "none":
+        return "mix_" + w.mix
+    if not w.exact_average:
+        return "no_average"
+    return "default" if w.policy in ("reset", "maintain") else "policy_" + w.policy
+
+
+def describe(w) -> str:
+    return (f"{w.name}-shaped tensor list ({len(w.numel)} tensors, d={w.d}), m={w.m}, tau={w.tau}, "
+            f"base={w.base}, grads={w.grad_dtype}, policy={w.policy}, alpha={w.alpha}, "
+            f"beta={w.beta}" + ("" if w.exact_average else ", no exact average")
+            + ("" if w.mix == "none" else f", gossip={w.mix}"))
+
+
+def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None):
+    """One workload variant: throughput over `steps` outer iterations (one
+    timed region, synchronized on both sides), the spread of the individual
+    iterations, and the roofline of every kernel kind that ran."""
+    fused = fusable(w) and not unfused
+    fused_mix = w.mix != "none" and not unfused
+    wall, round_ms, kern_ms = time_workload(w, steps, warmup, ring, fused=fused,
+                                            fused_mix=fused_mix, kernel_rounds=kernel_rounds)
+    rb = round_bytes(w, fused, fused_mix)
+    reset = w.policy == "reset"
+    per_launch = {          # algorithmic HBM bytes of one call of each kind
+        "local": local_bytes_per_update(w, False) * w.m * w.d,
+        "local_first": local_bytes_per_update(w, True) * w.m * w.d,
+        "local_last": local_bytes_per_update(w, reset and w.tau == 1, True) * w.m * w.d,
+        # the fused local+gossip kernel moves the local step's bytes (gossip adds none)
+        "local_mix": local_bytes_per_update(w, False) * w.m * w.d,
+        "local_mix_first": local_bytes_per_update(w, True) * w.m * w.d,
+        "mix": 8 * w.m * w.d,
+        "outer": outer_bytes_per_element(w) * w.d,
+        "fused_last_outer": fused_bytes_per_element(w) * w.d,
+    }
+    names = {"local": "k_local_step (steady state)", "local_first": "k_local_step (buffers read as zero)",
+             "local_last": "k_local_step (buffers not stored)",
+             "local_mix": "k_local_mix_step (steady state; all launches of one step)",
+             "local_mix_first": "k_local_mix_step (buffers read as zero)",
+             "mix": "k_mix_step (all launches of one step)",
+             "outer": "k_outer_noavg" if not w.exact_average else "k_outer_step",
+             "fused_last_outer": "k_local_outer_step"}
+    kernels = {}
+    for kind, ms in kern_ms.items():
+        if ms:
+            gbps = per_launch[kind] / (ms * 1e-3) / 1e9
+            kernels[kind] = {"kernel": names[kind], "ms": ms, "achieved": gbps, "unit": "GB/s",
+                             "frac": gbps / HBM_PEAK_GBPS,
+                             "algorithmic_bytes_per_launch": per_launch[kind]}
+    # the kernel kind the round spends most of its time in
+    calls = {"local": w.tau - (2 if reset else 0) - (1 if fused and not reset else 0),
+             "local_mix": w.tau - (1 if reset else 0)}
+    dominant = "local_mix" if "local_mix" in kernels else "local" if "local" in kernels else \
+        max(kernels, key=lambda k: kernels[k]["ms"] * calls.get(k, 1))
+    dom = kernels[dominant]
+    med = _median(round_ms)
+    return {
+        "workload": describe(w),
+        "value": w.updates_per_round * steps / wall, "unit": "updates/s", "steps": steps,
+        "ms_per_step": 1e3 * wall / steps,
+        "round_ms": {"median": med, "min": min(round_ms), "max": max(round_ms), "n": len(round_ms),
+                     "how": "HIP events at the start of every outer iteration inside the one "
+                            "timed region (no synchronization between them)"},
+        "value_at_median_round": w.updates_per_round / (med * 1e-3),
+        "hbm_gbps_whole_round": rb / wall * steps / 1e9,
+        "hbm_frac_whole_round": rb / wall * steps / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_round": rb,
+        "fused_calls": {"last_local_plus_outer": fused, "local_plus_gossip": fused_mix},
+        "roofline": {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved"],
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac"],
+                     "algorithmic_bytes_per_launch": dom["algorithmic_bytes_per_launch"],
+                     "traffic": measured_traffic(w.name, variant_name(w))},
+        "kernels": kernels,
+        "gradient_sets_resident": ring,
+    }
 
 
 def cpu_baseline(w, budget_s=12.0):
@@ -237,6 +350,10 @@ def cpu_baseline(w, budget_s=12.0):
                       f"{spent:.1f} s of oracle time"}
 
 
+def default_ring(w) -> int:
+    return min(w.tau, 16 if w.name == "transformer_big" else w.tau, 2 if w.name == "stress" else w.tau)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -257,29 +374,37 @@ def main():
                          "instead of the single call slowmo_local_outer_step (same results)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true",
-                    help="skip the short extra run of the other target workload "
-                         "(Transformer-big-shaped, reported under 'other_workloads')")
+                    help="skip the short runs of the other workloads and variants (reported "
+                         "under 'other_workloads')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel three times (a kernel of known "
                          "traffic for scaling rocprofv3 counters)")
+    ap.add_argument("--ladder", action="store_true",
+                    help="instead of the benchmark: the microbenchmark ladder of access shapes "
+                         "(slowmo_inputs/ladder.py), m and floats per stream from --ladder-m/-n")
+    ap.add_argument("--ladder-m", type=int, default=32)
+    ap.add_argument("--ladder-n", type=int, default=25_559_040)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (m logical workers share it); "
                  "--gpus N with N > 1 is not supported and no multi-GPU figure is reported")
+    import dataclasses
+
     import torch
     from slowmo_inputs import workloads as W
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.ladder:
+        from slowmo_inputs import ladder
+        ladder.main(args.ladder_m, args.ladder_n)
+        return
     w = W.BY_NAME[args.workload]()
-    import dataclasses
     if args.policy:
         w = dataclasses.replace(w, policy=args.policy)
     if args.no_average:
         w = dataclasses.replace(w, exact_average=False)
     if args.mix:
         w = dataclasses.replace(w, mix=args.mix)
-    ring = args.ring or min(w.tau, 16 if w.name == "transformer_big" else w.tau,
-                            2 if w.name == "stress" else w.tau)
     if args.calibrate_copy:
         from slowmo_inputs import device
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
@@ -289,81 +414,42 @@ def main():
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
-    fused = fusable(w) and not args.unfused
-    fused_mix = w.mix != "none" and not args.unfused
-    wall, kern_ms = time_workload(w, args.steps, args.warmup, ring, fused=fused, fused_mix=fused_mix)
-    ms_per_step = 1e3 * wall / args.steps
-    value = w.updates_per_round * args.steps / wall
-    local_bytes = local_bytes_per_update(w, False) * w.m * w.d
-    # with gossip fused into the local step that kernel is the dominant one: same
-    # algorithmic bytes as a local step (the gossip adds no traffic)
-    dominant = "local_mix" if fused_mix and kern_ms.get("local_mix") else "local"
-    achieved = local_bytes / (kern_ms[dominant] * 1e-3) / 1e9
+    res = measure(w, args.steps, args.warmup, args.ring or default_ring(w), unfused=args.unfused)
     out = {
         "metric": "param-element updates/s (m*d*tau per round)",
-        "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "value": res["value"], "unit": "updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}-shaped tensor list ({len(w.numel)} tensors, d={w.d}), "
-                               f"m={w.m}, tau={w.tau}, base={w.base}, grads={w.grad_dtype}, "
-                               f"policy={w.policy}, alpha={w.alpha}, beta={w.beta}"
-                               + ("" if w.exact_average else ", no exact average")
-                               + ("" if w.mix == "none" else f", gossip={w.mix}"),
+        "config": {"workload": res["workload"],
                    "step": "one outer iteration: tau local steps on all m workers + outer step"
                            + (" (the last local step and the outer step as one fused call)"
-                              if fused else "")
+                              if res["fused_calls"]["last_local_plus_outer"] else "")
                            + (" (every local step and the gossip step after it as one fused call)"
-                              if fused_mix else ""),
-                   "gradient_sets_resident": ring},
-        "hbm_gbps_whole_round": round_bytes(w, fused, fused_mix) / wall * args.steps / 1e9,
-        "hbm_frac_whole_round": round_bytes(w, fused, fused_mix) / wall * args.steps / 1e9
-                                / HBM_PEAK_GBPS,
-        "algorithmic_bytes_per_round": round_bytes(w, fused, fused_mix),
-        "kernel_ms": kern_ms,
-        "roofline": {"bound": "hbm", "kernel": ("k_local_mix_step (steady state)" if dominant == "local_mix"
-                                                else "k_local_step (steady state)"),
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS,
-                     "algorithmic_bytes_per_launch": local_bytes,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name if dominant == "local"
-                                                           else (w.name, w.mix))},
+                              if res["fused_calls"]["local_plus_gossip"] else ""),
+                   "gradient_sets_resident": res["gradient_sets_resident"]},
     }
-    if kern_ms.get("outer"):
-        ob = outer_bytes_per_element(w) * w.d
-        out["outer_kernel"] = {"achieved": ob / (kern_ms["outer"] * 1e-3) / 1e9, "unit": "GB/s",
-                               "frac": ob / (kern_ms["outer"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                               "algorithmic_bytes_per_launch": ob}
-    if kern_ms.get("fused_last_outer"):
-        fb = fused_bytes_per_element(w) * w.d
-        ms = kern_ms["fused_last_outer"]
-        out["fused_last_outer_kernel"] = {"achieved": fb / (ms * 1e-3) / 1e9, "unit": "GB/s",
-                                          "frac": fb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                                          "algorithmic_bytes_per_launch": fb}
-    if kern_ms.get("mix"):
-        mb = 8 * w.m * w.d
-        out["mix_kernel"] = {"achieved": mb / (kern_ms["mix"] * 1e-3) / 1e9, "unit": "GB/s",
-                             "frac": mb / (kern_ms["mix"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                             "algorithmic_bytes_per_launch": mb}
+    for key in ("round_ms", "value_at_median_round", "hbm_gbps_whole_round", "hbm_frac_whole_round",
+                "algorithmic_bytes_per_round", "roofline", "kernels"):
+        out[key] = res[key]
     if (not args.no_others and args.workload == "resnet50" and not args.policy
-            and not args.no_average and not args.mix):
-        # the second workload the bandwidth target is stated for, three timed iterations
-        w2 = W.transformer_big()
-        f2 = fusable(w2) and not args.unfused
-        wall2, k2 = time_workload(w2, 3, 1, 16, fused=f2)
-        lb2 = local_bytes_per_update(w2, False) * w2.m * w2.d
-        out["other_workloads"] = [{
-            "workload": f"{w2.name}-shaped tensor list ({len(w2.numel)} tensors, d={w2.d}), "
-                        f"m={w2.m}, tau={w2.tau}, base={w2.base}, grads={w2.grad_dtype}, "
-                        f"policy={w2.policy}",
-            "value": w2.updates_per_round * 3 / wall2, "unit": "updates/s", "steps": 3,
-            "ms_per_step": 1e3 * wall2 / 3,
-            "hbm_frac_whole_round": round_bytes(w2, f2) / wall2 * 3 / 1e9 / HBM_PEAK_GBPS,
-            "roofline": {"bound": "hbm", "kernel": "k_local_step (steady state)",
-                         "achieved": lb2 / (k2["local"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
-                         "unit": "GB/s", "frac": lb2 / (k2["local"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                         "algorithmic_bytes_per_launch": lb2,
-                         "traffic": MEASURED_TRAFFIC_BYTES.get(w2.name)},
-            "kernel_ms": k2}]
+            and not args.no_average and not args.mix and not args.unfused):
+        # Short runs of the other configurations and of the variants beyond the
+        # base path, so that every figure quoted for them is measured here.
+        r50 = W.resnet50()
+        others = [(W.transformer_big(), 3, 1, 2), (W.tiny(), 10, 2, None), (W.resnet18(), 5, 1, None),
+                  (W.stress(), 3, 1, 1),
+                  (dataclasses.replace(r50, policy="average"), 3, 1, 2),
+                  (dataclasses.replace(r50, exact_average=False), 3, 1, 2),
+                  (dataclasses.replace(r50, mix="expgraph"), 3, 1, 2),
+                  (dataclasses.replace(r50, mix="random"), 3, 1, 2),
+                  (dataclasses.replace(W.transformer_big(), mix="expgraph"), 2, 1, 1)]
+        out["other_workloads"] = []
+        for w2, steps2, warm2, krounds in others:
+            r2 = measure(w2, steps2, warm2, default_ring(w2), kernel_rounds=krounds)
+            r2["variant"] = variant_name(w2)
+            if w2.name == "transformer_big" and w2.mix == "none" and not args.no_cpu_baseline:
+                r2["cpu_baseline"] = cpu_baseline(w2, budget_s=10.0)
+            out["other_workloads"].append(r2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -427,6 +427,8 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
   ctx->fail_launch_at = env_flag("SLOWMO_TEST_FAIL_LAUNCH", 0);
+  ctx->tune.two_pass = env_flag("SLOWMO_TWO_PASS", 0) ? 1 : 0;
+  ctx->tune.bcast_piece = std::max(env_flag("SLOWMO_BCAST_PIECE_KB", 1024), 1);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
   const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
@@ -700,9 +702,30 @@ OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
   return a;
 }
 
-hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
+// Whether the copy of x_{t+1,0} into the replicas runs as a pass of its own
+// (a worker-major pass writes one stream per workgroup; m streams written side
+// by side by one wave are the slowest access shape of this chip).
+bool two_pass(const slowmo_ctx *ctx) {
+  return ctx->tune.two_pass && !ctx->cfg.no_average && ctx->cfg.m > 1;
+}
+
+hipError_t launch_broadcast_pass(slowmo_ctx *ctx, hipStream_t stream) {
+  BroadcastArgs b{};
+  b.tiles = ctx->d_ltiles;
+  b.slots = ctx->d_slots;
+  b.x0 = ctx->x0;
+  b.d_pad = ctx->layout.d_pad;
+  b.per_worker = ctx->n_ltiles / ctx->cfg.m;
+  b.piece_tiles = ctx->tune.bcast_piece;
+  b.m = ctx->cfg.m;
+  return guarded(ctx, [&] { return launch_broadcast(b, ctx->tune, stream); });
+}
+
+// Lines 6-8 and the copy into the replicas.  `launched`: kernels of the same
+// call already issued (a failure is then a failure halfway).
+slowmo_status run_outer(slowmo_ctx *ctx, float lr, int launched, hipStream_t stream) {
   const slowmo_config &c = ctx->cfg;
-  if (ctx->fail_launch_at > 0 && ++ctx->launches == ctx->fail_launch_at) return hipErrorLaunchFailure;
+  hipError_t e;
   if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
     OuterNoAvgArgs na{};
     na.tiles = ctx->d_ltiles;
@@ -713,9 +736,20 @@ hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
     na.lr = lr;
     na.alpha = c.alpha;
     na.beta = c.beta;
-    return launch_outer_noavg_step(na, ctx->tune, stream);
+    e = guarded(ctx, [&] { return launch_outer_noavg_step(na, ctx->tune, stream); });
+  } else {
+    e = guarded(ctx, [&] {
+      return launch_outer_step(outer_args(ctx, lr), !two_pass(ctx), ctx->tune, stream);
+    });
   }
-  return launch_outer_step(outer_args(ctx, lr), ctx->tune, stream);
+  if (e != hipSuccess)
+    return launched ? fail_midway(ctx, e, "outer-step kernel launch")
+                    : fail_hip(ctx, e, "outer-step kernel launch");
+  if (two_pass(ctx)) {
+    e = launch_broadcast_pass(ctx, stream);
+    if (e != hipSuccess) return fail_midway(ctx, e, "launch of the copy into the replicas");
+  }
+  return SLOWMO_OK;
 }
 
 }  // namespace
@@ -726,8 +760,8 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k != ctx->cfg.tau)
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
-  hipError_t e = launch_outer_any(ctx, lr, static_cast<hipStream_t>(stream_));
-  if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
+  const slowmo_status st = run_outer(ctx, lr, 0, static_cast<hipStream_t>(stream_));
+  if (st != SLOWMO_OK) return st;
   finish_outer(ctx);
   return SLOWMO_OK;
 }
@@ -749,20 +783,24 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
   const slowmo_config &c = ctx->cfg;
   const bool bf16 = c.grad_dtype == SLOWMO_BF16;
   if (c.no_average || !aligned || !ctx->params_aligned || !ctx->tune.fuse_last) {
-    // same two kernels as the separate calls
-    hipError_t e = guarded(ctx, [&] {
+    // same kernels as the separate calls
+    const hipError_t e = guarded(ctx, [&] {
       return launch_local_step(a, c.base, bf16, ctx->buffers_zero, c.policy == SLOWMO_BUF_RESET,
                                ctx->tune, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-    e = launch_outer_any(ctx, outer_lr, stream);
-    if (e != hipSuccess) return fail_midway(ctx, e, "outer-step kernel launch");
+    st = run_outer(ctx, outer_lr, 1, stream);
+    if (st != SLOWMO_OK) return st;
   } else {
     hipError_t e = guarded(ctx, [&] {
       return launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
-                                     ctx->buffers_zero, c.policy, ctx->tune, stream);
+                                     ctx->buffers_zero, c.policy, !two_pass(ctx), ctx->tune, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
+    if (two_pass(ctx)) {
+      e = launch_broadcast_pass(ctx, stream);
+      if (e != hipSuccess) return fail_midway(ctx, e, "launch of the copy into the replicas");
+    }
   }
   finish_local(ctx);
   finish_outer(ctx);

@@ -29,6 +29,7 @@
 // in the order written here, which is the order of Table C.1 and Eq. (2)-(3).
 #include "slowmo_kernels.h"
 
+#include <algorithm>
 #include <mutex>
 
 // Device memory of the allocation-free entry point (slowmo_debias_static): the
@@ -318,7 +319,9 @@ __device__ __forceinline__ void average_arena(float *__restrict__ b0, int64_t st
 }
 
 // AVG: 0 = lines 6-8 only; 1 = also average h over the workers; 2 = h and v.
-template <bool NT, int AVG>
+// BCAST: write x_{t+1,0} into the m replicas here; false leaves that to
+// k_broadcast (a wave then writes two streams instead of m + 2).
+template <bool NT, int AVG, bool BCAST>
 __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
@@ -354,9 +357,12 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       uv[c] = ue;
     }
     st4<NTS>(u + e0, uv);
-    st4<NTS>(x0 + e0, xn);
-    SLOWMO_PRAGMA_UNROLL_OUTER
-    for (int i = 0; i < m; ++i) st4<NTS>(xp[i] + eo + e0, xn);
+    // the broadcast pass reads x0 again right away: keep it cacheable then
+    st4<NTS && BCAST>(x0 + e0, xn);
+    if constexpr (BCAST) {
+      SLOWMO_PRAGMA_UNROLL_OUTER
+      for (int i = 0; i < m; ++i) st4<NTS>(xp[i] + eo + e0, xn);
+    }
   } else {
     const int e1 = e0 + 4 < n ? e0 + 4 : n;
     for (int j = e0; j < e1; ++j) {
@@ -366,7 +372,8 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       float xn = outer_elem(s, ld1(x0 + j), ue, p);
       st1(u + j, ue);
       st1(x0 + j, xn);
-      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
+      if constexpr (BCAST)
+        for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
     }
   }
   // line 2 of the next outer iteration, strategy "average"
@@ -405,6 +412,41 @@ __global__ __launch_bounds__(kOuterBlock) void k_init_broadcast(
       for (int c = 0; c < x0_copies; ++c) st1(x0 + c * d_pad + j, v);
       for (int i = 1; i < m; ++i) st1(xp[i] + eo + j, v);
     }
+  }
+}
+
+// ---- x_{t+1,0} into every replica, as a pass of its own -------------------------
+// Local-step tiling (one workgroup = 256 elements of one (worker, tensor)): a
+// workgroup writes ONE stream, the shape in which this chip writes fastest.
+// Every worker reads the whole of x0; to have all but the first of those reads
+// served by a cache, x0 is cut into pieces of `piece` tiles, eight pieces side
+// by side forming a slab, and XCD c (workgroups b with b % 8 == c) copies piece
+// c of a slab into worker 0, then worker 1, ... before it moves to the next
+// slab: the piece stays in that XCD's L2 while the m workers take their turn.
+template <bool NT>
+__global__ __launch_bounds__(kLocalBlock) void k_broadcast(
+    const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
+    const float *__restrict__ x0base, int64_t d_pad, int per_worker, int piece, int m) {
+  const int xcd = blockIdx.x % kXcd, q = blockIdx.x / kXcd;  // q: sequence number on this XCD
+  const int i = q % piece;
+  const int w = (q / piece) % m;
+  const int slab = q / (piece * m);
+  const int64_t k = (static_cast<int64_t>(slab) * kXcd + xcd) * piece + i;  // tile of the worker
+  if (k >= per_worker) return;
+  const TileRef t = tiles[static_cast<int64_t>(w) * per_worker + k];
+  const SlotInfo s = slots[t.owner];
+  const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;
+  float *x = s.x + go;
+  const float *x0 = x0base + (s.so - static_cast<int64_t>(w) * d_pad) + go;
+  const int64_t left = s.numel - go;
+  const int n = left < kLocalTile ? static_cast<int>(left) : kLocalTile;
+  const int e0 = 4 * static_cast<int>(threadIdx.x);
+  if (e0 >= n) return;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && e0 + 4 <= n) {
+    st4<NT>(x + e0, ld4<false>(x0 + e0));
+  } else {
+    const int e1 = e0 + 4 < n ? e0 + 4 : n;
+    for (int j = e0; j < e1; ++j) st1(x + j, ld1(x0 + j));
   }
 }
 
@@ -461,7 +503,7 @@ __global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
 // replicas are read once and written once (the unfused pair writes and
 // re-reads them), and under "reset" / "average" the per-worker buffers of this
 // step are never written.
-template <int BASE, bool BF16, bool FIRST, int POLICY, bool NT>
+template <int BASE, bool BF16, bool FIRST, int POLICY, bool NT, bool BCAST>
 __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
@@ -538,9 +580,11 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
       uv[c] = ue;
     }
     st4<NT>(u + e0, uv);
-    st4<NT>(x0 + e0, xn);
+    st4<NT && BCAST>(x0 + e0, xn);
+    if constexpr (BCAST) {
 #pragma unroll 8
-    for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
+      for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
+    }
     if constexpr (POLICY == 2) {
       V4 mh, mv;
 #pragma unroll
@@ -582,7 +626,8 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
       float xn = outer_elem(s, ld1(x0 + j), ue, p);
       st1(u + j, ue);
       st1(x0 + j, xn);
-      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
+      if constexpr (BCAST)
+        for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
       if constexpr (POLICY == 2) {
         for (int i = 0; i < m; ++i) {
           st1(h0 + i * d_pad + j, sh / p.m_f);
@@ -930,30 +975,52 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
               : launch_local_b<1, false>(a, first, last, t, s);
 }
 
-template <bool NT, int AVG>
+template <bool NT, int AVG, bool BCAST>
 hipError_t launch_outer_t(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(a.ntiles, t);
   const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
-  hipLaunchKernelGGL((k_outer_step<NT, AVG>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s,
-                     a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad, a.ntiles,
-                     g.chunk, g.run, a.m, p);
+  hipLaunchKernelGGL((k_outer_step<NT, AVG, BCAST>), dim3(g.blocks), dim3(kOuterBlock),
+                     t.outer_lds, s, a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v,
+                     a.d_pad, a.ntiles, g.chunk, g.run, a.m, p);
   return hipGetLastError();
 }
 
-hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.ntiles <= 0) return hipSuccess;
+template <bool NT, bool BCAST>
+hipError_t launch_outer_a(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
+  return avg == 0 ? launch_outer_t<NT, 0, BCAST>(a, t, s)
+                  : avg == 1 ? launch_outer_t<NT, 1, BCAST>(a, t, s)
+                             : launch_outer_t<NT, 2, BCAST>(a, t, s);
+}
+
+hipError_t launch_outer_step(const OuterArgs &a, bool broadcast, const LaunchTuning &t,
+                             hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  if (t.nontemporal)
+    return broadcast ? launch_outer_a<true, true>(a, t, s) : launch_outer_a<true, false>(a, t, s);
+  return broadcast ? launch_outer_a<false, true>(a, t, s) : launch_outer_a<false, false>(a, t, s);
+}
+
+hipError_t launch_broadcast(const BroadcastArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.per_worker <= 0) return hipSuccess;
+  const int64_t eighth = (a.per_worker + kXcd - 1) / kXcd;
+  const int piece = static_cast<int>(std::min<int64_t>(std::max(a.piece_tiles, 1), eighth));
+  const int64_t n_slabs = (a.per_worker + static_cast<int64_t>(kXcd) * piece - 1) / (kXcd * piece);
+  const int64_t blocks = n_slabs * a.m * piece * kXcd;
+  if (blocks > INT32_MAX - 64) return hipErrorInvalidValue;
   if (t.nontemporal) {
-    return avg == 0 ? launch_outer_t<true, 0>(a, t, s)
-                    : avg == 1 ? launch_outer_t<true, 1>(a, t, s) : launch_outer_t<true, 2>(a, t, s);
+    hipLaunchKernelGGL((k_broadcast<true>), dim3(static_cast<unsigned>(blocks)), dim3(kLocalBlock),
+                       0, s, a.tiles, a.slots, a.x0, a.d_pad, a.per_worker, piece, a.m);
+  } else {
+    hipLaunchKernelGGL((k_broadcast<false>), dim3(static_cast<unsigned>(blocks)), dim3(kLocalBlock),
+                       0, s, a.tiles, a.slots, a.x0, a.d_pad, a.per_worker, piece, a.m);
   }
-  return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
-                  : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
+  return hipGetLastError();
 }
 
 namespace {
 
-template <int BASE, bool BF16, bool FIRST, int POLICY>
+template <int BASE, bool BF16, bool FIRST, int POLICY, bool BCAST>
 hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
                           const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(o.ntiles, t);
@@ -961,46 +1028,55 @@ hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
   const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
   const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true>), dim3(g.blocks),
-                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
-                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true, BCAST>),
+                       dim3(g.blocks), dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
+                       o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
+                       p);
   } else {
-    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false>), dim3(g.blocks),
-                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
-                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false, BCAST>),
+                       dim3(g.blocks), dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
+                       o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
+                       p);
   }
   return hipGetLastError();
 }
 
+template <int BASE, bool BF16, bool FIRST, int POLICY>
+hipError_t launch_fused_b(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool broadcast,
+                          const LaunchTuning &t, hipStream_t s) {
+  return broadcast ? launch_fused_t<BASE, BF16, FIRST, POLICY, true>(l, o, n_tensors, t, s)
+                   : launch_fused_t<BASE, BF16, FIRST, POLICY, false>(l, o, n_tensors, t, s);
+}
+
 template <int BASE, bool BF16, bool FIRST>
 hipError_t launch_fused_p(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
-                          const LaunchTuning &t, hipStream_t s) {
+                          bool broadcast, const LaunchTuning &t, hipStream_t s) {
   switch (policy) {
-    case 0: return launch_fused_t<BASE, BF16, FIRST, 0>(l, o, n_tensors, t, s);
-    case 1: return launch_fused_t<BASE, BF16, FIRST, 1>(l, o, n_tensors, t, s);
-    default: return launch_fused_t<BASE, BF16, FIRST, 2>(l, o, n_tensors, t, s);
+    case 0: return launch_fused_b<BASE, BF16, FIRST, 0>(l, o, n_tensors, broadcast, t, s);
+    case 1: return launch_fused_b<BASE, BF16, FIRST, 1>(l, o, n_tensors, broadcast, t, s);
+    default: return launch_fused_b<BASE, BF16, FIRST, 2>(l, o, n_tensors, broadcast, t, s);
   }
 }
 
 template <int BASE, bool BF16>
 hipError_t launch_fused_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
-                          int policy, const LaunchTuning &t, hipStream_t s) {
-  return first ? launch_fused_p<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
-               : launch_fused_p<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
+                          int policy, bool broadcast, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_fused_p<BASE, BF16, true>(l, o, n_tensors, policy, broadcast, t, s)
+               : launch_fused_p<BASE, BF16, false>(l, o, n_tensors, policy, broadcast, t, s);
 }
 
 }  // namespace
 
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
-                                   int base, bool bf16, bool first, int policy,
+                                   int base, bool bf16, bool first, int policy, bool broadcast,
                                    const LaunchTuning &t, hipStream_t s) {
   if (o.ntiles <= 0) return hipSuccess;
   if (base == 0) {
-    return bf16 ? launch_fused_f<0, true>(l, o, n_tensors, first, policy, t, s)
-                : launch_fused_f<0, false>(l, o, n_tensors, first, policy, t, s);
+    return bf16 ? launch_fused_f<0, true>(l, o, n_tensors, first, policy, broadcast, t, s)
+                : launch_fused_f<0, false>(l, o, n_tensors, first, policy, broadcast, t, s);
   }
-  return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, t, s)
-              : launch_fused_f<1, false>(l, o, n_tensors, first, policy, t, s);
+  return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, broadcast, t, s)
+              : launch_fused_f<1, false>(l, o, n_tensors, first, policy, broadcast, t, s);
 }
 
 hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &t,

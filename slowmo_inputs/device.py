@@ -9,18 +9,19 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "gradgen.hip")
+SOURCES = [SRC, os.path.join(_HERE, "csrc", "streambench.hip")]
 LIB_PATH = os.path.join(_HERE, "libslowmo_inputs.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB_PATH) and \
-            os.path.getmtime(LIB_PATH) >= os.path.getmtime(SRC):
+            all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(f) for f in SOURCES):
         return LIB_PATH
     hipcc = "/opt/rocm/bin/hipcc" if os.path.exists("/opt/rocm/bin/hipcc") else "hipcc"
     cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-x", "hip", SRC, "-o", LIB_PATH]
+           "-x", "hip", *SOURCES, "-o", LIB_PATH]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + r.stderr)
@@ -39,6 +40,9 @@ def lib() -> C.CDLL:
         _lib.slowmo_inputs_fill.restype = C.c_int
         _lib.slowmo_inputs_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         _lib.slowmo_inputs_calib_copy.restype = C.c_int
+        _lib.slowmo_inputs_streambench.argtypes = [C.c_void_p, C.c_int64] + [C.c_int32] * 5 + \
+            [C.c_int64] + [C.c_int32] * 6 + [C.c_void_p]
+        _lib.slowmo_inputs_streambench.restype = C.c_int
     return _lib
 
 
@@ -91,3 +95,19 @@ def calib_copy(src, dst) -> None:
                                         torch.cuda.current_stream(src.device).cuda_stream)
     if rc != 0:
         raise RuntimeError(f"slowmo_inputs_calib_copy failed with hipError {rc}")
+
+
+def streambench(buf, stride: int, units: int, S: int, R: int, W: int, in_place: bool, n: int,
+                B: int = 64, VPT: int = 1, nt: int = 3, order: int = 0, remap: bool = True,
+                iters: int = 1) -> None:
+    """One launch of the stream microbenchmark kernel (csrc/streambench.hip) on
+    the fp32 CUDA tensor `buf` seen as units x S streams of n floats, `stride`
+    floats apart.  nt: 1 = non-temporal loads, 2 = non-temporal stores, 3 = both."""
+    import torch
+    assert buf.is_cuda and buf.is_contiguous() and buf.dtype == torch.float32
+    assert buf.numel() >= units * S * stride
+    rc = lib().slowmo_inputs_streambench(buf.data_ptr(), stride, units, S, R, W, int(in_place), n,
+                                         B, VPT, int(nt), order, int(remap), iters,
+                                         torch.cuda.current_stream(buf.device).cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"slowmo_inputs_streambench failed with hipError {rc}")

@@ -1,0 +1,104 @@
+"""The microbenchmark ladder behind the kernels' access shape: plain read /
+write / copy ceilings, the local step's 3-read/2-write mix under different
+workgroup shapes, dispatch orders and cache hints, and the m-stream patterns of
+the kernels that walk all workers per workgroup.  Every line is one shape of
+csrc/streambench.hip, timed with HIP events on the launch stream
+(`python bench.py --ladder`).  Measurement only."""
+from __future__ import annotations
+
+import json
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def cases(m: int, n: int):
+    """(label, kwargs of device.streambench, HBM bytes per launch)."""
+    f = 4 * n
+    out = []
+
+    def add(label, units, S, R, W, in_place=True, **kw):
+        out.append((label, dict(units=units, S=S, R=R, W=W, in_place=in_place, **kw),
+                    units * (R + W) * f))
+
+    # ceilings.  A workgroup that moves 1 KiB is bound by the rate at which
+    # workgroups are dispatched, so the plain streams also run with 16 KiB each.
+    add("read,  1 KiB per workgroup (dispatch-bound)", m, 1, 1, 0)
+    add("write, 1 KiB per workgroup (dispatch-bound)", m, 1, 0, 1)
+    add("read,  256 threads x 4 vec4/lane", m, 1, 1, 0, B=256, VPT=4)
+    add("write, 256 threads x 4 vec4/lane", m, 1, 0, 1, B=256, VPT=4)
+    add("write, 256 threads x 4 vec4/lane, plain stores", m, 1, 0, 1, B=256, VPT=4, nt=0)
+    add("copy (1 read, 1 write), 1 KiB per stream and workgroup", m, 2, 1, 1, in_place=False)
+    add("copy, 256 threads x 4 vec4/lane", m, 2, 1, 1, in_place=False, B=256, VPT=4)
+    # the SGD local step's mix: x, h, g read; x, h written
+    add("3r/2w  64 threads, 1 vec4/lane, retire, NT, XCD-contiguous  [library shape]", m, 3, 3, 2)
+    add("3r/2w  same, plain loads and stores", m, 3, 3, 2, nt=0)
+    add("3r/2w  same, NT loads, plain stores", m, 3, 3, 2, nt=1)
+    add("3r/2w  same, plain loads, NT stores", m, 3, 3, 2, nt=2)
+    add("3r/2w  same, NT, workgroup b takes tile b (no XCD remap)", m, 3, 3, 2, remap=False)
+    add("3r/2w  128 threads", m, 3, 3, 2, B=128)
+    add("3r/2w  256 threads", m, 3, 3, 2, B=256)
+    add("3r/2w  1024 threads", m, 3, 3, 2, B=1024)
+    add("3r/2w  64 threads, 4 vec4/lane (4 KiB per stream and wave)", m, 3, 3, 2, VPT=4)
+    add("3r/2w  256 threads, 4 vec4/lane", m, 3, 3, 2, B=256, VPT=4)
+    add("3r/2w  64 threads, workgroup loops over 16 consecutive tiles", m, 3, 3, 2, iters=16)
+    add("3r/2w  256 threads, workgroup loops over 64 consecutive tiles", m, 3, 3, 2, B=256, iters=64)
+    add("3r/2w  library shape, tiles dispatched worker-minor (tile k of every worker, then k+1)",
+        m, 3, 3, 2, order=1)
+    add("3r/2w  out of place (x, h written to other arrays)", m, 5, 3, 2, in_place=False)
+    # all m workers per workgroup (outer step, gossip): m+2 streams read and written in place
+    for B, V in ((64, 1), (64, 4), (256, 1), (256, 4), (256, 16), (512, 16), (1024, 4), (1024, 16)):
+        add(f"{m + 2} streams in place per workgroup, {B} threads, {V} vec4/lane", 1, m + 2, m + 2,
+            m + 2, B=B, VPT=V)
+    add(f"{m + 2} streams in place, 1024 threads, 16 vec4/lane, no XCD remap", 1, m + 2, m + 2, m + 2,
+        B=1024, VPT=16, remap=False)
+    add(f"{m + 2} streams in place, 64 threads, 1 vec4/lane, no XCD remap", 1, m + 2, m + 2, m + 2,
+        remap=False)
+    add(f"{m + 2} streams in place, 64 threads, NT loads, plain stores", 1, m + 2, m + 2, m + 2, nt=1)
+    add(f"{m} streams read per workgroup (nothing written)", 1, m, m, 0)
+    add(f"{m} streams read, 1024 threads x 16 vec4/lane", 1, m, m, 0, B=1024, VPT=16)
+    add(f"{m} streams written per workgroup (nothing read)", 1, m, 0, m)
+    add(f"{m} streams written, plain stores", 1, m, 0, m, nt=0)
+    add(f"{m} streams written, 1024 threads x 16 vec4/lane", 1, m, 0, m, B=1024, VPT=16)
+    add(f"{m + 2} streams read, 2 of them written in place", 1, m + 2, m + 2, 2)
+    add(f"{m + 2} streams read, 2 other streams written", 1, m + 4, m + 2, 2, in_place=False)
+    add(f"{m + 2} streams read, 2 written in place, plain stores", 1, m + 2, m + 2, 2, nt=1)
+    add(f"{m + 2} streams read, 2 written in place, 1024 threads x 16 vec4/lane", 1, m + 2, m + 2, 2,
+        B=1024, VPT=16)
+    add(f"{3 * m + 2} streams read, 2 written (last local step + average, no copy back)", 1,
+        3 * m + 2, 3 * m + 2, 2)
+    add(f"{3 * m + 2} streams read, 2 written, 1024 threads x 16 vec4/lane", 1, 3 * m + 2, 3 * m + 2,
+        2, B=1024, VPT=16)
+    return out
+
+
+def run(m: int = 32, n: int = 25_559_040, reps: int = 5, device: str = "cuda:0"):
+    """Times every case (1 untimed + `reps` timed launches, HIP events on the
+    launch stream).  n is a multiple of every tile size used (65 536 floats)."""
+    import torch
+    from . import device as D
+    assert n % 65536 == 0
+    stride = n + 65536                         # streams start 256 KiB after the previous one ends
+    all_cases = cases(m, n)
+    most = max(kw["units"] * kw["S"] for _, kw, _ in all_cases)
+    buf = torch.zeros(most * stride, dtype=torch.float32, device=device)
+    rows = []
+    for label, kw, nbytes in all_cases:
+        D.streambench(buf, stride, n=n, **kw)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            D.streambench(buf, stride, n=n, **kw)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        rows.append({"shape": label, "ms": ms, "GB/s": nbytes / ms / 1e6,
+                     "frac": nbytes / ms / 1e6 / HBM_PEAK_GBPS, "bytes": nbytes})
+    return {"m": m, "floats_per_stream": n, "reps": reps, "rows": rows}
+
+
+def main(m: int = 32, n: int = 25_559_040):
+    res = run(m, n)
+    for r in res["rows"]:
+        print(f"{r['frac']:.3f}  {r['GB/s']:7.0f} GB/s  {r['ms']:7.3f} ms  {r['shape']}", flush=True)
+    print(json.dumps(res))
