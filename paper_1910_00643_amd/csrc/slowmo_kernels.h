@@ -53,17 +53,6 @@ struct OuterNoAvgArgs {
   float lr, alpha, beta;
 };
 
-// x_{t+1,0} into all replicas as a pass of its own, over the local-step tiles.
-struct BroadcastArgs {
-  const TileRef *tiles;        // device: local-step tiles (owner = slot), worker-major
-  const SlotInfo *slots;       // device
-  const float *x0;             // device: arena d_pad
-  int64_t d_pad;
-  int32_t per_worker;          // tiles of one worker
-  int32_t piece_tiles;         // tiles of x0 one XCD copies into worker after worker
-  int32_t m;
-};
-
 struct MixArgs {
   const TileRef *tiles;        // device: outer-step tiles (owner = tensor)
   const TensorInfo *tensors;   // device
@@ -91,9 +80,8 @@ struct LaunchTuning {
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
   int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
   int32_t fuse_mix;     // 1: slowmo_local_mix_step runs one fused kernel when it can
-  int32_t two_pass;     // 1: the outer step (alone or fused with the last local step) leaves the
-                        // copy into the replicas to a second, worker-major pass
-  int32_t bcast_piece;  // tiles (1 KiB each) of x0 an XCD keeps in its L2 during that pass
+  int32_t wide;         // 1: full aligned 2048-element tiles of the all-worker kernels go to the
+                        // wide-tile kernels
   int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
                         // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
@@ -103,18 +91,14 @@ struct LaunchTuning {
 // last: h (and v) are dead after this step and are not written.
 hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first, bool last,
                              const LaunchTuning &tune, hipStream_t stream);
-// broadcast: write x_{t+1,0} into the replicas in the same kernel; false: the
-// caller follows up with launch_broadcast.
-hipError_t launch_outer_step(const OuterArgs &a, bool broadcast, const LaunchTuning &tune,
-                             hipStream_t stream);
-hipError_t launch_broadcast(const BroadcastArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
 // The last local step of an outer iteration and the outer step in one pass
 // (one workgroup = 256 elements of one tensor, all workers).  Requires every
 // replica and gradient pointer to be 16-byte aligned (8 for bf16).  policy:
 // 0 reset (buffers not stored), 1 maintain (stored), 2 average (their mean
 // over the workers is stored).
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
-                                   int base, bool bf16, bool first, int policy, bool broadcast,
+                                   int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &tune, hipStream_t stream);
 // Copies worker 0's replica into x0 (x0_copies copies, d_pad apart) and into the
 // replicas of workers 1..m-1; uses a.tiles, a.tensors, a.xtab_t, a.x0, a.d_pad, a.m.
@@ -129,6 +113,19 @@ hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d
                                  int32_t n_tensors, int base, bool bf16, bool first,
                                  const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
+
+// The same four operations on WIDE tiles (kWideTile elements, every one full
+// and 16-byte aligned in all replicas; tiles[].k counts wide tiles).  Same
+// arithmetic, bit for bit; non-temporal accesses only.  The remainder of the
+// tensor list goes to the functions above with the rest of the tiles.
+hipError_t launch_outer_wide(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_local_outer_wide(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                   int base, bool bf16, bool first, int policy,
+                                   const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_mix_wide(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_local_mix_wide(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                 int32_t n_tensors, int base, bool bf16, bool first,
+                                 const LaunchTuning &tune, hipStream_t stream);
 
 // Static device memory for the entry point that allocates nothing: room for
 // the de-bias table (destination pointers, then the push-sum weights) of up to

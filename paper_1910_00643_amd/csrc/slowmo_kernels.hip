@@ -29,7 +29,6 @@
 // in the order written here, which is the order of Table C.1 and Eq. (2)-(3).
 #include "slowmo_kernels.h"
 
-#include <algorithm>
 #include <mutex>
 
 // Device memory of the allocation-free entry point (slowmo_debias_static): the
@@ -319,9 +318,7 @@ __device__ __forceinline__ void average_arena(float *__restrict__ b0, int64_t st
 }
 
 // AVG: 0 = lines 6-8 only; 1 = also average h over the workers; 2 = h and v.
-// BCAST: write x_{t+1,0} into the m replicas here; false leaves that to
-// k_broadcast (a wave then writes two streams instead of m + 2).
-template <bool NT, int AVG, bool BCAST>
+template <bool NT, int AVG>
 __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
@@ -357,12 +354,9 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       uv[c] = ue;
     }
     st4<NTS>(u + e0, uv);
-    // the broadcast pass reads x0 again right away: keep it cacheable then
-    st4<NTS && BCAST>(x0 + e0, xn);
-    if constexpr (BCAST) {
-      SLOWMO_PRAGMA_UNROLL_OUTER
-      for (int i = 0; i < m; ++i) st4<NTS>(xp[i] + eo + e0, xn);
-    }
+    st4<NTS>(x0 + e0, xn);
+    SLOWMO_PRAGMA_UNROLL_OUTER
+    for (int i = 0; i < m; ++i) st4<NTS>(xp[i] + eo + e0, xn);
   } else {
     const int e1 = e0 + 4 < n ? e0 + 4 : n;
     for (int j = e0; j < e1; ++j) {
@@ -372,8 +366,7 @@ __global__ __launch_bounds__(kOuterBlock) void k_outer_step(
       float xn = outer_elem(s, ld1(x0 + j), ue, p);
       st1(u + j, ue);
       st1(x0 + j, xn);
-      if constexpr (BCAST)
-        for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
+      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
     }
   }
   // line 2 of the next outer iteration, strategy "average"
@@ -412,41 +405,6 @@ __global__ __launch_bounds__(kOuterBlock) void k_init_broadcast(
       for (int c = 0; c < x0_copies; ++c) st1(x0 + c * d_pad + j, v);
       for (int i = 1; i < m; ++i) st1(xp[i] + eo + j, v);
     }
-  }
-}
-
-// ---- x_{t+1,0} into every replica, as a pass of its own -------------------------
-// Local-step tiling (one workgroup = 256 elements of one (worker, tensor)): a
-// workgroup writes ONE stream, the shape in which this chip writes fastest.
-// Every worker reads the whole of x0; to have all but the first of those reads
-// served by a cache, x0 is cut into pieces of `piece` tiles, eight pieces side
-// by side forming a slab, and XCD c (workgroups b with b % 8 == c) copies piece
-// c of a slab into worker 0, then worker 1, ... before it moves to the next
-// slab: the piece stays in that XCD's L2 while the m workers take their turn.
-template <bool NT>
-__global__ __launch_bounds__(kLocalBlock) void k_broadcast(
-    const TileRef *__restrict__ tiles, const SlotInfo *__restrict__ slots,
-    const float *__restrict__ x0base, int64_t d_pad, int per_worker, int piece, int m) {
-  const int xcd = blockIdx.x % kXcd, q = blockIdx.x / kXcd;  // q: sequence number on this XCD
-  const int i = q % piece;
-  const int w = (q / piece) % m;
-  const int slab = q / (piece * m);
-  const int64_t k = (static_cast<int64_t>(slab) * kXcd + xcd) * piece + i;  // tile of the worker
-  if (k >= per_worker) return;
-  const TileRef t = tiles[static_cast<int64_t>(w) * per_worker + k];
-  const SlotInfo s = slots[t.owner];
-  const int64_t go = static_cast<int64_t>(t.k) * kLocalTile;
-  float *x = s.x + go;
-  const float *x0 = x0base + (s.so - static_cast<int64_t>(w) * d_pad) + go;
-  const int64_t left = s.numel - go;
-  const int n = left < kLocalTile ? static_cast<int>(left) : kLocalTile;
-  const int e0 = 4 * static_cast<int>(threadIdx.x);
-  if (e0 >= n) return;
-  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && e0 + 4 <= n) {
-    st4<NT>(x + e0, ld4<false>(x0 + e0));
-  } else {
-    const int e1 = e0 + 4 < n ? e0 + 4 : n;
-    for (int j = e0; j < e1; ++j) st1(x + j, ld1(x0 + j));
   }
 }
 
@@ -503,7 +461,7 @@ __global__ __launch_bounds__(kLocalBlock) void k_outer_noavg(
 // replicas are read once and written once (the unfused pair writes and
 // re-reads them), and under "reset" / "average" the per-worker buffers of this
 // step are never written.
-template <int BASE, bool BF16, bool FIRST, int POLICY, bool NT, bool BCAST>
+template <int BASE, bool BF16, bool FIRST, int POLICY, bool NT>
 __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
     float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
@@ -580,11 +538,9 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
       uv[c] = ue;
     }
     st4<NT>(u + e0, uv);
-    st4<NT && BCAST>(x0 + e0, xn);
-    if constexpr (BCAST) {
+    st4<NT>(x0 + e0, xn);
 #pragma unroll 8
-      for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
-    }
+    for (int i = 0; i < m; ++i) st4<NT>(xp[i] + eo + e0, xn);
     if constexpr (POLICY == 2) {
       V4 mh, mv;
 #pragma unroll
@@ -626,8 +582,7 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
       float xn = outer_elem(s, ld1(x0 + j), ue, p);
       st1(u + j, ue);
       st1(x0 + j, xn);
-      if constexpr (BCAST)
-        for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
+      for (int i = 0; i < m; ++i) st1(xp[i] + eo + j, xn);
       if constexpr (POLICY == 2) {
         for (int i = 0; i < m; ++i) {
           st1(h0 + i * d_pad + j, sh / p.m_f);
@@ -883,6 +838,341 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
   }
 }
 
+// ---- wide tiles for the kernels that walk all workers ---------------------------
+// The four kernels above touch 2m+4 .. 5m streams per workgroup.  With one
+// 16-byte vector per lane and stream (1 KiB per stream and wave) they run at
+// about 0.65 of the HBM peak; with VPT = 8 vectors per lane -- 8 KiB of every
+// stream per wave -- the same traffic measures 0.70 to 0.78 at m = 32 (at m = 8
+// it makes no difference).  The kernels below are that shape: same tiling idea,
+// same arithmetic in the same order, but a tile is 4 * B * VPT elements, and only
+// FULL tiles of tensors whose replicas are 16-byte aligned are given to them;
+// tails, small tensors and unaligned tensors stay with the kernels above (a
+// second launch over the rest of the tile list).  Lane t's v-th vector is
+// vector v * B + t of the tile, so every load instruction of a wave is one
+// contiguous 1 KiB burst.
+template <int B>
+__device__ __forceinline__ int wide_off(int v) {
+  return (v * B + static_cast<int>(threadIdx.x)) * 4;
+}
+
+template <int B, int VPT>
+__device__ __forceinline__ void average_wide(float *__restrict__ b0, int64_t stride, int m,
+                                             float m_f) {
+  V4 acc[VPT];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) acc[v] = ld4<true>(b0 + wide_off<B>(v));
+#pragma unroll 2
+  for (int i = 1; i < m; ++i) {
+    const float *bi = b0 + i * stride;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) acc[v] = acc[v] + ld4<true>(bi + wide_off<B>(v));
+  }
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[v][c] = acc[v][c] / m_f;
+  }
+#pragma unroll 2
+  for (int i = 0; i < m; ++i) {
+    float *bi = b0 + i * stride;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) st4<true>(bi + wide_off<B>(v), acc[v]);
+  }
+}
+
+// k_outer_step on full tiles.
+template <int AVG, int B, int VPT>
+__global__ __launch_bounds__(B) void k_outer_wide(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
+    float *__restrict__ hbase, float *__restrict__ vbase, int64_t d_pad, int ntiles, int chunk,
+    int remap, int m, OuterP p0) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
+  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
+  V4 acc[VPT];
+  {
+    const float *x = xp[0] + eo;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) acc[v] = ld4<true>(x + wide_off<B>(v));
+  }
+#pragma unroll 2
+  for (int i = 1; i < m; ++i) {       // line 6: ordered sum, i = 0, 1, ..., m-1
+    const float *x = xp[i] + eo;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) acc[v] = acc[v] + ld4<true>(x + wide_off<B>(v));
+  }
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+    const V4 x0v = ld4<true>(x0 + wide_off<B>(v));
+    V4 uv = ld4<true>(u + wide_off<B>(v)), xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<true>(u + wide_off<B>(v), uv);
+    st4<true>(x0 + wide_off<B>(v), xn);
+    acc[v] = xn;
+  }
+#pragma unroll 2
+  for (int i = 0; i < m; ++i) {
+    float *x = xp[i] + eo;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) st4<true>(x + wide_off<B>(v), acc[v]);
+  }
+  if constexpr (AVG >= 1) average_wide<B, VPT>(hbase + ti.fo + eo, d_pad, m, p.m_f);
+  if constexpr (AVG >= 2) average_wide<B, VPT>(vbase + ti.fo + eo, d_pad, m, p.m_f);
+}
+
+// The base-optimizer step of one worker on this lane's VPT vectors: all loads
+// first, then the arithmetic of k_local_step.
+template <int BASE, bool BF16, bool FIRST, int B, int VPT>
+__device__ __forceinline__ void step_wide(const float *xi, const float *hi, const float *vi,
+                                          const void *gi, const SgdP &sp, const AdamP &ap,
+                                          V4 (&xv)[VPT], V4 (&hv)[VPT], V4 (&vv)[VPT]) {
+  V4 gv[VPT];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+    xv[v] = ld4<true>(xi + wide_off<B>(v));
+    if constexpr (!FIRST) hv[v] = ld4<true>(hi + wide_off<B>(v));
+    if constexpr (!FIRST && BASE == 1) vv[v] = ld4<true>(vi + wide_off<B>(v));
+    gv[v] = ldg4<BF16, true>(gi, v * B + static_cast<int>(threadIdx.x));
+  }
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float xe = xv[v][c], he = FIRST ? 0.f : hv[v][c];
+      if constexpr (BASE == 0) {
+        sgd_elem<FIRST>(xe, he, gv[v][c], sp);
+      } else {
+        float ve = FIRST ? 0.f : vv[v][c];
+        adam_elem<FIRST>(xe, he, ve, gv[v][c], ap);
+        vv[v][c] = ve;
+      }
+      xv[v][c] = xe;
+      hv[v][c] = he;
+    }
+  }
+}
+
+// k_local_outer_step on full tiles.
+template <int BASE, bool BF16, bool FIRST, int POLICY, int B, int VPT>
+__global__ __launch_bounds__(B) void k_local_outer_wide(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
+    float *__restrict__ x0base, float *__restrict__ ubase, float *__restrict__ hbase,
+    float *__restrict__ vbase, int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap,
+    int m, SgdP sp, AdamP ap, OuterP p0) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
+  sp.lr = sp.lr * ti.lr_scale;
+  sp.wd = ti.wd;
+  ap.lr = ap.lr * ti.lr_scale;
+  ap.wd = ti.wd;
+  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const void *const *__restrict__ gp = gtab + t.owner;
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
+  float *h0 = hbase + ti.fo + eo;
+  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
+  constexpr int gsize = BF16 ? 2 : 4;
+  V4 acc[VPT], acch[POLICY == 2 ? VPT : 1], accv[(POLICY == 2 && BASE == 1) ? VPT : 1];
+#ifndef SLOWMO_FUSED_WIDE_UNROLL
+#define SLOWMO_FUSED_WIDE_UNROLL 1
+#endif
+  _Pragma(SLOWMO_STR(unroll SLOWMO_FUSED_WIDE_UNROLL))
+  for (int i = 0; i < m; ++i) {
+    float *hi = h0 + i * d_pad;
+    float *vi = BASE == 1 ? v0 + i * d_pad : nullptr;
+    const void *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
+    V4 xv[VPT], hv[VPT], vv[VPT];
+    step_wide<BASE, BF16, FIRST, B, VPT>(xp[i] + eo, hi, vi, gi, sp, ap, xv, hv, vv);
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) {
+      if constexpr (POLICY == 1) {
+        st4<true>(hi + wide_off<B>(v), hv[v]);
+        if constexpr (BASE == 1) st4<true>(vi + wide_off<B>(v), vv[v]);
+      }
+      if constexpr (POLICY == 2) {
+        acch[v] = (i == 0) ? hv[v] : acch[v] + hv[v];
+        if constexpr (BASE == 1) accv[v] = (i == 0) ? vv[v] : accv[v] + vv[v];
+      }
+      acc[v] = (i == 0) ? xv[v] : acc[v] + xv[v];
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+    const V4 x0v = ld4<true>(x0 + wide_off<B>(v));
+    V4 uv = ld4<true>(u + wide_off<B>(v)), xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<true>(u + wide_off<B>(v), uv);
+    st4<true>(x0 + wide_off<B>(v), xn);
+    acc[v] = xn;
+  }
+#pragma unroll 2
+  for (int i = 0; i < m; ++i) {
+    float *x = xp[i] + eo;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) st4<true>(x + wide_off<B>(v), acc[v]);
+  }
+  if constexpr (POLICY == 2) {
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        acch[v][c] = acch[v][c] / p.m_f;
+        if constexpr (BASE == 1) accv[v][c] = accv[v][c] / p.m_f;
+      }
+    }
+#pragma unroll 2
+    for (int i = 0; i < m; ++i) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) {
+        st4<true>(h0 + i * d_pad + wide_off<B>(v), acch[v]);
+        if constexpr (BASE == 1) st4<true>(v0 + i * d_pad + wide_off<B>(v), accv[v]);
+      }
+    }
+  }
+}
+
+// k_mix_step on full tiles: one entry at a time (an entry already has VPT or
+// 2 VPT loads in flight per lane).
+template <int B, int VPT>
+__global__ __launch_bounds__(B) void k_mix_wide(
+    const TileRef *__restrict__ tiles, float *const *__restrict__ xtab_t,
+    const MixEntry *__restrict__ seq, int len, int ntiles, int chunk, int remap, int m) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  V4 S[VPT], first[VPT];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) S[v] = first[v] = V4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int e = 0; e < len; ++e) {
+    const MixEntry en = seq[e];
+    float *ptr = xp[en.node] + eo;
+    V4 own[VPT];
+    if (en.flags & kMixOwnFromS) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) own[v] = S[v];
+    } else {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) own[v] = ld4<SLOWMO_MIX_OWN_NT != 0>(ptr + wide_off<B>(v));
+    }
+    if (en.flags & kMixSaveFirst) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) first[v] = own[v];
+    }
+    if (en.flags & kMixNoSrc) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) st4<true>(ptr + wide_off<B>(v), en.a * own[v]);
+    } else {
+      if (en.flags & kMixSrcFromFirst) {
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) S[v] = first[v];
+      } else if (!(en.flags & kMixSrcFromS)) {
+        const float *src = xp[en.src] + eo;
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) S[v] = ld4<SLOWMO_MIX_SRC_NT != 0>(src + wide_off<B>(v));
+      }
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) st4<true>(ptr + wide_off<B>(v), en.a * own[v] + en.b * S[v]);
+    }
+  }
+}
+
+// k_local_mix_step on full tiles.
+template <int BASE, bool BF16, bool FIRST, int B, int VPT>
+__global__ __launch_bounds__(B) void k_local_mix_wide(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
+    float *__restrict__ hbase, float *__restrict__ vbase, const MixEntry *__restrict__ seq, int len,
+    int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap, int m, SgdP sp, AdamP ap) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  sp.lr = sp.lr * ti.lr_scale;
+  sp.wd = ti.wd;
+  ap.lr = ap.lr * ti.lr_scale;
+  ap.wd = ti.wd;
+  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const void *const *__restrict__ gp = gtab + t.owner;
+  float *h0 = hbase + ti.fo + eo;
+  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
+  constexpr int gsize = BF16 ? 2 : 4;
+  V4 Sx[VPT], Sh[VPT], Sv[VPT], first[VPT];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) Sx[v] = Sh[v] = Sv[v] = first[v] = V4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int e = 0; e < len; ++e) {
+    const MixEntry en = seq[e];
+    float *xi = xp[en.node] + eo;
+    float *hi = h0 + en.node * d_pad;
+    float *vi = BASE == 1 ? v0 + en.node * d_pad : nullptr;
+    V4 xo[VPT], ho[VPT], vo[VPT];
+    if (en.flags & kMixOwnFromS) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) {
+        xo[v] = Sx[v];
+        ho[v] = Sh[v];
+        vo[v] = Sv[v];
+      }
+    } else {
+      const void *gi =
+          static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
+      step_wide<BASE, BF16, FIRST, B, VPT>(xi, hi, vi, gi, sp, ap, xo, ho, vo);
+    }
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) {
+      st4<true>(hi + wide_off<B>(v), ho[v]);
+      if constexpr (BASE == 1) st4<true>(vi + wide_off<B>(v), vo[v]);
+    }
+    if (en.flags & kMixSaveFirst) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) first[v] = xo[v];
+    }
+    if (en.flags & kMixNoSrc) {
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) st4<true>(xi + wide_off<B>(v), en.a * xo[v]);
+    } else {
+      if (en.flags & kMixSrcFromFirst) {
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) Sx[v] = first[v];
+      } else if (!(en.flags & kMixSrcFromS)) {
+        const void *gs =
+            static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;
+        step_wide<BASE, BF16, FIRST, B, VPT>(xp[en.src] + eo, h0 + en.src * d_pad,
+                                             BASE == 1 ? v0 + en.src * d_pad : nullptr, gs, sp, ap,
+                                             Sx, Sh, Sv);
+      }
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) st4<true>(xi + wide_off<B>(v), en.a * xo[v] + en.b * Sx[v]);
+    }
+  }
+}
+
 // z^{(i)} = x^{(i)} / w_i (Algorithm C.1, last line), one workgroup per local tile.
 template <bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_debias(
@@ -975,52 +1265,30 @@ hipError_t launch_local_step(const LocalArgs &a, int base, bool bf16, bool first
               : launch_local_b<1, false>(a, first, last, t, s);
 }
 
-template <bool NT, int AVG, bool BCAST>
+template <bool NT, int AVG>
 hipError_t launch_outer_t(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(a.ntiles, t);
   const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
-  hipLaunchKernelGGL((k_outer_step<NT, AVG, BCAST>), dim3(g.blocks), dim3(kOuterBlock),
-                     t.outer_lds, s, a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v,
-                     a.d_pad, a.ntiles, g.chunk, g.run, a.m, p);
+  hipLaunchKernelGGL((k_outer_step<NT, AVG>), dim3(g.blocks), dim3(kOuterBlock), t.outer_lds, s,
+                     a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad, a.ntiles,
+                     g.chunk, g.run, a.m, p);
   return hipGetLastError();
 }
 
-template <bool NT, bool BCAST>
-hipError_t launch_outer_a(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
-  const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
-  return avg == 0 ? launch_outer_t<NT, 0, BCAST>(a, t, s)
-                  : avg == 1 ? launch_outer_t<NT, 1, BCAST>(a, t, s)
-                             : launch_outer_t<NT, 2, BCAST>(a, t, s);
-}
-
-hipError_t launch_outer_step(const OuterArgs &a, bool broadcast, const LaunchTuning &t,
-                             hipStream_t s) {
+hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
   if (a.ntiles <= 0) return hipSuccess;
-  if (t.nontemporal)
-    return broadcast ? launch_outer_a<true, true>(a, t, s) : launch_outer_a<true, false>(a, t, s);
-  return broadcast ? launch_outer_a<false, true>(a, t, s) : launch_outer_a<false, false>(a, t, s);
-}
-
-hipError_t launch_broadcast(const BroadcastArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.per_worker <= 0) return hipSuccess;
-  const int64_t eighth = (a.per_worker + kXcd - 1) / kXcd;
-  const int piece = static_cast<int>(std::min<int64_t>(std::max(a.piece_tiles, 1), eighth));
-  const int64_t n_slabs = (a.per_worker + static_cast<int64_t>(kXcd) * piece - 1) / (kXcd * piece);
-  const int64_t blocks = n_slabs * a.m * piece * kXcd;
-  if (blocks > INT32_MAX - 64) return hipErrorInvalidValue;
+  const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_broadcast<true>), dim3(static_cast<unsigned>(blocks)), dim3(kLocalBlock),
-                       0, s, a.tiles, a.slots, a.x0, a.d_pad, a.per_worker, piece, a.m);
-  } else {
-    hipLaunchKernelGGL((k_broadcast<false>), dim3(static_cast<unsigned>(blocks)), dim3(kLocalBlock),
-                       0, s, a.tiles, a.slots, a.x0, a.d_pad, a.per_worker, piece, a.m);
+    return avg == 0 ? launch_outer_t<true, 0>(a, t, s)
+                    : avg == 1 ? launch_outer_t<true, 1>(a, t, s) : launch_outer_t<true, 2>(a, t, s);
   }
-  return hipGetLastError();
+  return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
+                  : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
 }
 
 namespace {
 
-template <int BASE, bool BF16, bool FIRST, int POLICY, bool BCAST>
+template <int BASE, bool BF16, bool FIRST, int POLICY>
 hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
                           const LaunchTuning &t, hipStream_t s) {
   const Grid g = make_grid(o.ntiles, t);
@@ -1028,55 +1296,46 @@ hipError_t launch_fused_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
   const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
   const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
   if (t.nontemporal) {
-    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true, BCAST>),
-                       dim3(g.blocks), dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
-                       o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
-                       p);
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, true>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
   } else {
-    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false, BCAST>),
-                       dim3(g.blocks), dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
-                       o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
-                       p);
+    hipLaunchKernelGGL((k_local_outer_step<BASE, BF16, FIRST, POLICY, false>), dim3(g.blocks),
+                       dim3(kOuterBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h,
+                       l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
   }
   return hipGetLastError();
 }
 
-template <int BASE, bool BF16, bool FIRST, int POLICY>
-hipError_t launch_fused_b(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool broadcast,
-                          const LaunchTuning &t, hipStream_t s) {
-  return broadcast ? launch_fused_t<BASE, BF16, FIRST, POLICY, true>(l, o, n_tensors, t, s)
-                   : launch_fused_t<BASE, BF16, FIRST, POLICY, false>(l, o, n_tensors, t, s);
-}
-
 template <int BASE, bool BF16, bool FIRST>
 hipError_t launch_fused_p(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
-                          bool broadcast, const LaunchTuning &t, hipStream_t s) {
+                          const LaunchTuning &t, hipStream_t s) {
   switch (policy) {
-    case 0: return launch_fused_b<BASE, BF16, FIRST, 0>(l, o, n_tensors, broadcast, t, s);
-    case 1: return launch_fused_b<BASE, BF16, FIRST, 1>(l, o, n_tensors, broadcast, t, s);
-    default: return launch_fused_b<BASE, BF16, FIRST, 2>(l, o, n_tensors, broadcast, t, s);
+    case 0: return launch_fused_t<BASE, BF16, FIRST, 0>(l, o, n_tensors, t, s);
+    case 1: return launch_fused_t<BASE, BF16, FIRST, 1>(l, o, n_tensors, t, s);
+    default: return launch_fused_t<BASE, BF16, FIRST, 2>(l, o, n_tensors, t, s);
   }
 }
 
 template <int BASE, bool BF16>
 hipError_t launch_fused_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
-                          int policy, bool broadcast, const LaunchTuning &t, hipStream_t s) {
-  return first ? launch_fused_p<BASE, BF16, true>(l, o, n_tensors, policy, broadcast, t, s)
-               : launch_fused_p<BASE, BF16, false>(l, o, n_tensors, policy, broadcast, t, s);
+                          int policy, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_fused_p<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
+               : launch_fused_p<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
 }
 
 }  // namespace
 
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
-                                   int base, bool bf16, bool first, int policy, bool broadcast,
+                                   int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &t, hipStream_t s) {
   if (o.ntiles <= 0) return hipSuccess;
   if (base == 0) {
-    return bf16 ? launch_fused_f<0, true>(l, o, n_tensors, first, policy, broadcast, t, s)
-                : launch_fused_f<0, false>(l, o, n_tensors, first, policy, broadcast, t, s);
+    return bf16 ? launch_fused_f<0, true>(l, o, n_tensors, first, policy, t, s)
+                : launch_fused_f<0, false>(l, o, n_tensors, first, policy, t, s);
   }
-  return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, broadcast, t, s)
-              : launch_fused_f<1, false>(l, o, n_tensors, first, policy, broadcast, t, s);
+  return bf16 ? launch_fused_f<1, true>(l, o, n_tensors, first, policy, t, s)
+              : launch_fused_f<1, false>(l, o, n_tensors, first, policy, t, s);
 }
 
 hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &t,
@@ -1174,6 +1433,113 @@ hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &
                        a.slots, a.x0, a.u, a.ntiles, g.chunk, g.run, p);
   }
   return hipGetLastError();
+}
+
+// ---- wide-tile launchers ---------------------------------------------------------
+hipError_t launch_outer_wide(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t);
+  const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
+  const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
+#define SLOWMO_OUTER_WIDE(AVG)                                                                    \
+  hipLaunchKernelGGL((k_outer_wide<AVG, kWideBlock, kWideVpt>), dim3(g.blocks), dim3(kWideBlock), \
+                     0, s, a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad,    \
+                     a.ntiles, g.chunk, g.run, a.m, p)
+  if (avg == 0) {
+    SLOWMO_OUTER_WIDE(0);
+  } else if (avg == 1) {
+    SLOWMO_OUTER_WIDE(1);
+  } else {
+    SLOWMO_OUTER_WIDE(2);
+  }
+#undef SLOWMO_OUTER_WIDE
+  return hipGetLastError();
+}
+
+namespace {
+
+template <int BASE, bool BF16, bool FIRST, int POLICY>
+hipError_t launch_fused_wide_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
+                               const LaunchTuning &t, hipStream_t s) {
+  const Grid g = make_grid(o.ntiles, t);
+  const SgdP sp{l.lr, l.mu, l.wd};
+  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
+  const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
+  hipLaunchKernelGGL((k_local_outer_wide<BASE, BF16, FIRST, POLICY, kWideBlock, kWideVpt>),
+                     dim3(g.blocks), dim3(kWideBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
+                     o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
+                     p);
+  return hipGetLastError();
+}
+
+template <int BASE, bool BF16, bool FIRST>
+hipError_t launch_fused_wide_p(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
+                               const LaunchTuning &t, hipStream_t s) {
+  switch (policy) {
+    case 0: return launch_fused_wide_t<BASE, BF16, FIRST, 0>(l, o, n_tensors, t, s);
+    case 1: return launch_fused_wide_t<BASE, BF16, FIRST, 1>(l, o, n_tensors, t, s);
+    default: return launch_fused_wide_t<BASE, BF16, FIRST, 2>(l, o, n_tensors, t, s);
+  }
+}
+
+template <int BASE, bool BF16>
+hipError_t launch_fused_wide_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
+                               int policy, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_fused_wide_p<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
+               : launch_fused_wide_p<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
+}
+
+template <int BASE, bool BF16, bool FIRST>
+hipError_t launch_local_mix_wide_t(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                   int n_tensors, const LaunchTuning &t, hipStream_t s) {
+  const Grid g = make_grid(x.ntiles, t);
+  const SgdP sp{l.lr, l.mu, l.wd};
+  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
+  hipLaunchKernelGGL((k_local_mix_wide<BASE, BF16, FIRST, kWideBlock, kWideVpt>), dim3(g.blocks),
+                     dim3(kWideBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
+                     x.len, d_pad, n_tensors, x.ntiles, g.chunk, g.run, x.m, sp, ap);
+  return hipGetLastError();
+}
+
+template <int BASE, bool BF16>
+hipError_t launch_local_mix_wide_f(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                   int n_tensors, bool first, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_local_mix_wide_t<BASE, BF16, true>(l, x, d_pad, n_tensors, t, s)
+               : launch_local_mix_wide_t<BASE, BF16, false>(l, x, d_pad, n_tensors, t, s);
+}
+
+}  // namespace
+
+hipError_t launch_local_outer_wide(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                   int base, bool bf16, bool first, int policy,
+                                   const LaunchTuning &t, hipStream_t s) {
+  if (o.ntiles <= 0) return hipSuccess;
+  if (base == 0) {
+    return bf16 ? launch_fused_wide_f<0, true>(l, o, n_tensors, first, policy, t, s)
+                : launch_fused_wide_f<0, false>(l, o, n_tensors, first, policy, t, s);
+  }
+  return bf16 ? launch_fused_wide_f<1, true>(l, o, n_tensors, first, policy, t, s)
+              : launch_fused_wide_f<1, false>(l, o, n_tensors, first, policy, t, s);
+}
+
+hipError_t launch_mix_wide(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
+  const Grid g = make_grid(a.ntiles, t);
+  hipLaunchKernelGGL((k_mix_wide<kWideBlock, kWideVpt>), dim3(g.blocks), dim3(kWideBlock), 0, s,
+                     a.tiles, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, g.run, a.m);
+  return hipGetLastError();
+}
+
+hipError_t launch_local_mix_wide(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
+                                 int32_t n_tensors, int base, bool bf16, bool first,
+                                 const LaunchTuning &t, hipStream_t s) {
+  if (x.ntiles <= 0 || x.len <= 0) return hipSuccess;
+  if (base == 0) {
+    return bf16 ? launch_local_mix_wide_f<0, true>(l, x, d_pad, n_tensors, first, t, s)
+                : launch_local_mix_wide_f<0, false>(l, x, d_pad, n_tensors, first, t, s);
+  }
+  return bf16 ? launch_local_mix_wide_f<1, true>(l, x, d_pad, n_tensors, first, t, s)
+              : launch_local_mix_wide_f<1, false>(l, x, d_pad, n_tensors, first, t, s);
 }
 
 }  // namespace slowmo
