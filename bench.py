@@ -105,13 +105,16 @@ def round_bytes(w, fused: bool = False, fused_mix: bool = False) -> int:
     return w.d * (w.m * per_worker_elem + tail)
 
 
+PARAM_LAYOUT = "separate"       # --param-layout
+
+
 def build_problem(w, ring):
     import torch
     from slowmo_inputs.gpu_problem import GpuProblem
     from paper_1910_00643_amd.optimizer import SlowMo, make_config
     # parameters: one allocation per tensor and worker; gradients: every tensor
     # 512-byte aligned, as separately allocated .grad tensors would be
-    prob = GpuProblem(w, "cuda:0", ring=ring, grad_layout="padded")
+    prob = GpuProblem(w, "cuda:0", ring=ring, grad_layout="padded", param_layout=PARAM_LAYOUT)
     cfg = make_config(m=w.m, tau=w.tau, alpha=w.alpha, beta=w.beta, base=w.base,
                       policy=w.policy, grad_dtype=w.grad_dtype, momentum=w.momentum,
                       weight_decay=w.weight_decay, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
@@ -142,11 +145,14 @@ def _bracket(events, kind):
     return cm()
 
 
-def run_rounds(w, opt, arrays, rounds, events=None, marks=None, fused=False, fused_mix=False):
+def run_rounds(w, opt, arrays, rounds, events=None, marks=None, fused=False, fused_mix=False,
+               z=None):
     """`rounds` outer iterations.  With `events`, brackets every call with HIP
     events; with `marks`, records one event at the start of every outer
     iteration and one after the last (per-iteration durations without any
-    synchronization inside the timed region)."""
+    synchronization inside the timed region).  With `z` (a pointer array of
+    destination tensors) the de-biased parameters are written after every gossip
+    step, as a gradient evaluation at z would need them."""
     import torch
     import paper_1910_00643_amd as P
     ring = len(arrays)
@@ -174,6 +180,9 @@ def run_rounds(w, opt, arrays, rounds, events=None, marks=None, fused=False, fus
             if peers is not None and fused_mix:     # local step + gossip step, one call
                 with _bracket(events, "local_mix_first" if (reset and k == 0) else "local_mix"):
                     opt.local_mix_step(arrays[k % ring], w.lr, peers[k % len(peers)])
+                if z is not None:
+                    with _bracket(events, "debias"):
+                        opt.debias(z)
                 continue
             kind = ("local_first" if (reset and k == 0) else
                     "local_last" if (reset and k == w.tau - 1) else "local")
@@ -182,13 +191,17 @@ def run_rounds(w, opt, arrays, rounds, events=None, marks=None, fused=False, fus
             if peers is not None:           # SGP as base optimizer: gossip after every step
                 with _bracket(events, "mix"):
                     opt.mix_step(peers[k % len(peers)])
+                if z is not None:
+                    with _bracket(events, "debias"):
+                        opt.debias(z)
         else:
             with _bracket(events, "outer"):
                 opt.outer_step(w.lr)
     mark()
 
 
-def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False, kernel_rounds=None):
+def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False, kernel_rounds=None,
+                  debias=False):
     """Returns (wall seconds of the `steps` timed outer iterations, their
     individual durations in ms from HIP events, average ms per call kind from a
     second pass of `kernel_rounds` iterations with events around every call)."""
@@ -196,18 +209,23 @@ def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False, ker
     ring = ring or w.tau
     prob, opt = build_problem(w, ring)
     arrays = [opt.grad_pointer_array(prob.grads[s]) for s in range(ring)]
-    run_rounds(w, opt, arrays, warmup, fused=fused, fused_mix=fused_mix)
+    z = None
+    if debias:
+        zt = [[torch.empty_like(t) for t in p] for p in prob.params]
+        z = opt.param_pointer_array(zt)
+    run_rounds(w, opt, arrays, warmup, fused=fused, fused_mix=fused_mix, z=z)
     torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
-    run_rounds(w, opt, arrays, steps, marks=marks, fused=fused, fused_mix=fused_mix)
+    run_rounds(w, opt, arrays, steps, marks=marks, fused=fused, fused_mix=fused_mix, z=z)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     round_ms = [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
     # second pass: per-kernel durations from HIP events around every launch
     events = {"local": [], "local_first": [], "local_last": [], "outer": [], "mix": [],
-              "fused_last_outer": [], "local_mix": [], "local_mix_first": []}
-    run_rounds(w, opt, arrays, kernel_rounds or steps, events, fused=fused, fused_mix=fused_mix)
+              "fused_last_outer": [], "local_mix": [], "local_mix_first": [], "debias": []}
+    run_rounds(w, opt, arrays, kernel_rounds or steps, events, fused=fused, fused_mix=fused_mix,
+               z=z)
     torch.cuda.synchronize()
     kern_ms = {k: (sum(a.elapsed_time(b) for a, b in v) / len(v) if v else None)
                for k, v in events.items()}
@@ -239,15 +257,16 @@ def describe(w) -> str:
             + ("" if w.mix == "none" else f", gossip={w.mix}"))
 
 
-def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None):
+def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None, debias=False):
     """One workload variant: throughput over `steps` outer iterations (one
     timed region, synchronized on both sides), the spread of the individual
     iterations, and the roofline of every kernel kind that ran."""
     fused = fusable(w) and not unfused
     fused_mix = w.mix != "none" and not unfused
     wall, round_ms, kern_ms = time_workload(w, steps, warmup, ring, fused=fused,
-                                            fused_mix=fused_mix, kernel_rounds=kernel_rounds)
-    rb = round_bytes(w, fused, fused_mix)
+                                            fused_mix=fused_mix, kernel_rounds=kernel_rounds,
+                                            debias=debias)
+    rb = round_bytes(w, fused, fused_mix) + (8 * w.m * w.d * w.tau if debias else 0)
     reset = w.policy == "reset"
     per_launch = {          # algorithmic HBM bytes of one call of each kind
         "local": local_bytes_per_update(w, False) * w.m * w.d,
@@ -259,6 +278,7 @@ def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None):
         "mix": 8 * w.m * w.d,
         "outer": outer_bytes_per_element(w) * w.d,
         "fused_last_outer": fused_bytes_per_element(w) * w.d,
+        "debias": 8 * w.m * w.d,
     }
     names = {"local": "k_local_step (steady state)", "local_first": "k_local_step (buffers read as zero)",
              "local_last": "k_local_step (buffers not stored)",
@@ -266,7 +286,7 @@ def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None):
              "local_mix_first": "k_local_mix_step (buffers read as zero)",
              "mix": "k_mix_step (all launches of one step)",
              "outer": "k_outer_noavg" if not w.exact_average else "k_outer_step",
-             "fused_last_outer": "k_local_outer_step"}
+             "fused_last_outer": "k_local_outer_step", "debias": "k_debias"}
     kernels = {}
     for kind, ms in kern_ms.items():
         if ms:
@@ -372,6 +392,13 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="end every outer iteration with slowmo_local_step + slowmo_outer_step "
                          "instead of the single call slowmo_local_outer_step (same results)")
+    ap.add_argument("--debias", action="store_true",
+                    help="with --mix: also write the de-biased parameters z = x / w after every "
+                         "gossip step (slowmo_debias)")
+    ap.add_argument("--param-layout", default="separate", choices=["separate", "arena"],
+                    help="separate (the benchmark's layout): every parameter tensor of every "
+                         "worker is its own allocation; arena: one allocation for all workers, "
+                         "tensors 512-byte aligned (reported in addition, never instead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short runs of the other workloads and variants (reported "
@@ -398,6 +425,8 @@ def main():
         from slowmo_inputs import ladder
         ladder.main(args.ladder_m, args.ladder_n)
         return
+    global PARAM_LAYOUT
+    PARAM_LAYOUT = args.param_layout
     w = W.BY_NAME[args.workload]()
     if args.policy:
         w = dataclasses.replace(w, policy=args.policy)
@@ -414,7 +443,8 @@ def main():
         torch.cuda.synchronize()
         del a, b
         torch.cuda.empty_cache()
-    res = measure(w, args.steps, args.warmup, args.ring or default_ring(w), unfused=args.unfused)
+    res = measure(w, args.steps, args.warmup, args.ring or default_ring(w), unfused=args.unfused,
+                  debias=args.debias and w.mix != "none")
     out = {
         "metric": "param-element updates/s (m*d*tau per round)",
         "value": res["value"], "unit": "updates/s", "n_gpus": 1, "steps": args.steps,

@@ -37,11 +37,11 @@ size_t ztab_bytes(int32_t m, int32_t n_tensors) {
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kGradSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, wtiles, rtiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kGradSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
-                       size_t n_otiles, size_t n_wtiles) {
+                       size_t n_otiles) {
   Sections s{};
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -64,9 +64,6 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.tensors = take(static_cast<size_t>(n_tensors) * sizeof(TensorInfo));
   s.ltiles = take(n_ltiles * sizeof(TileRef));
   s.otiles = take(n_otiles * sizeof(TileRef));
-  // wide tiles and what they leave over (at most every ordinary tile: no replica aligned)
-  s.wtiles = take(n_wtiles * sizeof(TileRef));
-  s.rtiles = take(n_otiles * sizeof(TileRef));
   s.total = off;
   return s;
 }
@@ -234,12 +231,6 @@ struct slowmo_ctx {
   TileRef *d_ltiles = nullptr;
   TileRef *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
-  // When wide tiles are in use the kernels that walk all workers run twice:
-  // over the wide tiles (whole 2048-element pieces of aligned tensors) and over
-  // the ordinary tiles these leave over.  Otherwise n_wtiles = 0 and the rest
-  // list is the whole ordinary list.
-  TileRef *d_wtiles = nullptr, *d_rtiles = nullptr;
-  int32_t n_wtiles = 0, n_rtiles = 0;
 
   TableRing<kGradSlots> gtab;  // gradient-pointer tables of recent calls (m * n_tensors each)
   TableRing<kSlots> mixtab;  // update order of the current mixing step (at most m entries)
@@ -301,29 +292,8 @@ slowmo_status fail_midway(slowmo_ctx *ctx, hipError_t e, const char *what) {
                   "partly updated and the context refuses further steps");
 }
 
-// A kernel that walks all workers per workgroup runs over the wide tiles (if
-// any) with `wide`, then over the ordinary tiles they leave over with `rest`;
-// both take (tiles, count) and return a hipError_t.  *launched counts the
-// kernels of the current call issued so far: a failure after the first one is
-// a failure halfway.
-template <typename FW, typename FR>
-slowmo_status run_tiled(slowmo_ctx *ctx, int *launched, const char *what, FW &&wide, FR &&rest);
-
 const char *kBrokenMsg =
     "an earlier multi-kernel call failed halfway; the context's state is undefined: destroy it";
-
-template <typename FW, typename FR>
-slowmo_status run_tiled(slowmo_ctx *ctx, int *launched, const char *what, FW &&wide, FR &&rest) {
-  for (int pass = 0; pass < 2; ++pass) {
-    const TileRef *tiles = pass == 0 ? ctx->d_wtiles : ctx->d_rtiles;
-    const int32_t n = pass == 0 ? ctx->n_wtiles : ctx->n_rtiles;
-    if (n <= 0) continue;
-    const hipError_t e = guarded(ctx, [&] { return pass == 0 ? wide(tiles, n) : rest(tiles, n); });
-    if (e != hipSuccess) return *launched ? fail_midway(ctx, e, what) : fail_hip(ctx, e, what);
-    ++*launched;
-  }
-  return SLOWMO_OK;
-}
 
 void release(slowmo_ctx *ctx) {
   ctx->gtab.destroy();
@@ -351,8 +321,7 @@ size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int
   Layout L = make_layout(n_tensors, numel);
   return make_sections(*cfg, n_tensors, L,
                        static_cast<size_t>(count_local_tiles(cfg->m, n_tensors, numel)),
-                       static_cast<size_t>(count_outer_tiles(n_tensors, numel)),
-                       static_cast<size_t>(count_wide_tiles(n_tensors, numel)))
+                       static_cast<size_t>(count_outer_tiles(n_tensors, numel)))
       .total;
 }
 
@@ -458,16 +427,11 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
   ctx->fail_launch_at = env_flag("SLOWMO_TEST_FAIL_LAUNCH", 0);
-  // wide tiles pay off when many workers are walked per workgroup (measured:
-  // +5 to +15 % at m = 32, nothing at m = 8); -1 = decide by m
-  const int32_t wide = env_flag("SLOWMO_WIDE", -1);
-  ctx->tune.wide = (wide < 0 ? m >= 16 : wide != 0) && ctx->tune.nontemporal;
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
   const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
   const Sections sec = make_sections(*cfg, n_tensors, ctx->layout, static_cast<size_t>(n_ltiles),
-                                     static_cast<size_t>(n_otiles),
-                                     static_cast<size_t>(count_wide_tiles(n_tensors, numel)));
+                                     static_cast<size_t>(n_otiles));
   if (state_bytes < sec.total) {
     delete ctx;
     return fail(nullptr, SLOWMO_ERR_NOMEM, "state workspace is smaller than slowmo_state_bytes()");
@@ -511,8 +475,6 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->d_tensors = reinterpret_cast<TensorInfo *>(base + sec.tensors);
   ctx->d_ltiles = reinterpret_cast<TileRef *>(base + sec.ltiles);
   ctx->d_otiles = reinterpret_cast<TileRef *>(base + sec.otiles);
-  ctx->d_wtiles = reinterpret_cast<TileRef *>(base + sec.wtiles);
-  ctx->d_rtiles = reinterpret_cast<TileRef *>(base + sec.rtiles);
   ctx->n_ltiles = static_cast<int32_t>(n_ltiles);
   ctx->n_otiles = static_cast<int32_t>(n_otiles);
 
@@ -571,32 +533,6 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
     CREATE_HIP(hipMemcpyAsync(ctx->d_otiles, ot.data(), ot.size() * sizeof(TileRef),
                               hipMemcpyHostToDevice, stream),
                "upload of the outer-step tiles");
-  // wide tiles: the whole kWideTile pieces of every tensor all of whose replicas
-  // are 16-byte aligned; the rest list: the ordinary tiles behind them, and all
-  // tiles of the other tensors
-  std::vector<TileRef> wt, rt;
-  if (ctx->tune.wide) {
-    constexpr int64_t per_wide = kWideTile / kOuterTile;
-    for (int32_t j = 0; j < n_tensors; ++j) {
-      const int64_t n_wide = tinfo[j].unaligned ? 0 : numel[j] / kWideTile;
-      for (int64_t k = 0; k < n_wide; ++k) wt.push_back({j, static_cast<int32_t>(k)});
-      for (int64_t k = n_wide * per_wide; k * kOuterTile < numel[j]; ++k)
-        rt.push_back({j, static_cast<int32_t>(k)});
-    }
-    if (!wt.empty())
-      CREATE_HIP(hipMemcpyAsync(ctx->d_wtiles, wt.data(), wt.size() * sizeof(TileRef),
-                                hipMemcpyHostToDevice, stream),
-                 "upload of the wide tiles");
-    if (!rt.empty())
-      CREATE_HIP(hipMemcpyAsync(ctx->d_rtiles, rt.data(), rt.size() * sizeof(TileRef),
-                                hipMemcpyHostToDevice, stream),
-                 "upload of the tiles the wide ones leave over");
-    ctx->n_wtiles = static_cast<int32_t>(wt.size());
-    ctx->n_rtiles = static_cast<int32_t>(rt.size());
-  } else {
-    ctx->d_rtiles = ctx->d_otiles;
-    ctx->n_rtiles = ctx->n_otiles;
-  }
   CREATE_HIP(hipMemcpyAsync(ctx->d_tensors, tinfo.data(), tinfo.size() * sizeof(TensorInfo),
                             hipMemcpyHostToDevice, stream),
              "upload of the tensor table");
@@ -764,10 +700,9 @@ OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
   return a;
 }
 
-// Lines 6-8 and the copy into the replicas.  *launched: kernels of the same call
-// already issued (a failure is then a failure halfway).
-slowmo_status run_outer(slowmo_ctx *ctx, float lr, int *launched, hipStream_t stream) {
+hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
   const slowmo_config &c = ctx->cfg;
+  if (ctx->fail_launch_at > 0 && ++ctx->launches == ctx->fail_launch_at) return hipErrorLaunchFailure;
   if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
     OuterNoAvgArgs na{};
     na.tiles = ctx->d_ltiles;
@@ -778,23 +713,9 @@ slowmo_status run_outer(slowmo_ctx *ctx, float lr, int *launched, hipStream_t st
     na.lr = lr;
     na.alpha = c.alpha;
     na.beta = c.beta;
-    const hipError_t e = guarded(ctx, [&] { return launch_outer_noavg_step(na, ctx->tune, stream); });
-    if (e != hipSuccess)
-      return *launched ? fail_midway(ctx, e, "outer-step kernel launch")
-                       : fail_hip(ctx, e, "outer-step kernel launch");
-    ++*launched;
-    return SLOWMO_OK;
+    return launch_outer_noavg_step(na, ctx->tune, stream);
   }
-  OuterArgs a = outer_args(ctx, lr);
-  auto with = [&](const TileRef *tiles, int32_t n) {
-    a.tiles = tiles;
-    a.ntiles = n;
-    return a;
-  };
-  return run_tiled(
-      ctx, launched, "outer-step kernel launch",
-      [&](const TileRef *t, int32_t n) { return launch_outer_wide(with(t, n), ctx->tune, stream); },
-      [&](const TileRef *t, int32_t n) { return launch_outer_step(with(t, n), ctx->tune, stream); });
+  return launch_outer_step(outer_args(ctx, lr), ctx->tune, stream);
 }
 
 }  // namespace
@@ -805,9 +726,8 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k != ctx->cfg.tau)
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
-  int launched = 0;
-  const slowmo_status st = run_outer(ctx, lr, &launched, static_cast<hipStream_t>(stream_));
-  if (st != SLOWMO_OK) return st;
+  hipError_t e = launch_outer_any(ctx, lr, static_cast<hipStream_t>(stream_));
+  if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
   finish_outer(ctx);
   return SLOWMO_OK;
 }
@@ -828,35 +748,22 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
   if (st != SLOWMO_OK) return st;
   const slowmo_config &c = ctx->cfg;
   const bool bf16 = c.grad_dtype == SLOWMO_BF16;
-  int launched = 0;
   if (c.no_average || !aligned || !ctx->params_aligned || !ctx->tune.fuse_last) {
-    // same kernels as the separate calls
-    const hipError_t e = guarded(ctx, [&] {
+    // same two kernels as the separate calls
+    hipError_t e = guarded(ctx, [&] {
       return launch_local_step(a, c.base, bf16, ctx->buffers_zero, c.policy == SLOWMO_BUF_RESET,
                                ctx->tune, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-    launched = 1;
-    st = run_outer(ctx, outer_lr, &launched, stream);
+    e = launch_outer_any(ctx, outer_lr, stream);
+    if (e != hipSuccess) return fail_midway(ctx, e, "outer-step kernel launch");
   } else {
-    OuterArgs o = outer_args(ctx, outer_lr);
-    auto with = [&](const TileRef *tiles, int32_t n) {
-      o.tiles = tiles;
-      o.ntiles = n;
-      return o;
-    };
-    st = run_tiled(
-        ctx, &launched, "fused local+outer kernel launch",
-        [&](const TileRef *t, int32_t n) {
-          return launch_local_outer_wide(a, with(t, n), ctx->n_tensors, c.base, bf16,
-                                         ctx->buffers_zero, c.policy, ctx->tune, stream);
-        },
-        [&](const TileRef *t, int32_t n) {
-          return launch_local_outer_step(a, with(t, n), ctx->n_tensors, c.base, bf16,
-                                         ctx->buffers_zero, c.policy, ctx->tune, stream);
-        });
+    hipError_t e = guarded(ctx, [&] {
+      return launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
+                                     ctx->buffers_zero, c.policy, ctx->tune, stream);
+    });
+    if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
   }
-  if (st != SLOWMO_OK) return st;
   finish_local(ctx);
   finish_outer(ctx);
   return SLOWMO_OK;
@@ -918,29 +825,26 @@ slowmo_status stage_mix(slowmo_ctx *ctx, const int32_t *in_peer, bool with_idle,
 
 MixArgs mix_args(const slowmo_ctx *ctx) {
   MixArgs a{};
+  a.tiles = ctx->d_otiles;
   a.tensors = ctx->d_tensors;
   a.xtab_t = ctx->d_xtab_t;
+  a.ntiles = ctx->n_otiles;
   a.m = ctx->cfg.m;
   return a;
 }
 
-// Launches the gossip kernel once per group (and per tile list).  *launched:
-// kernels of this call already issued before.
-slowmo_status run_mix(slowmo_ctx *ctx, const StagedMix &sm, int *launched, hipStream_t stream) {
+// Launches the gossip kernel once per group.  `launched`: kernels of this call
+// already issued before (a failure is then a failure halfway).
+slowmo_status run_mix(slowmo_ctx *ctx, const StagedMix &sm, int launched, hipStream_t stream) {
   MixArgs a = mix_args(ctx);
-  auto with = [&](const TileRef *tiles, int32_t n) {
-    a.tiles = tiles;
-    a.ntiles = n;
-    return a;
-  };
   for (const auto &r : sm.ranges) {
     a.seq = sm.d_seq + r.first;
     a.len = r.second - r.first;
-    const slowmo_status st = run_tiled(
-        ctx, launched, "mixing kernel launch",
-        [&](const TileRef *t, int32_t n) { return launch_mix_wide(with(t, n), ctx->tune, stream); },
-        [&](const TileRef *t, int32_t n) { return launch_mix_step(with(t, n), ctx->tune, stream); });
-    if (st != SLOWMO_OK) return st;
+    const hipError_t e = guarded(ctx, [&] { return launch_mix_step(a, ctx->tune, stream); });
+    if (e != hipSuccess)
+      return launched ? fail_midway(ctx, e, "mixing kernel launch")
+                      : fail_hip(ctx, e, "mixing kernel launch");
+    ++launched;
   }
   return SLOWMO_OK;
 }
@@ -977,9 +881,8 @@ slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *str
     return fail(ctx, SLOWMO_ERR_ARG, "in_peer entries must lie in 0..m-1");
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   StagedMix sm;
-  int launched = 0;
   slowmo_status st = stage_mix(ctx, in_peer, /*with_idle=*/false, stream, &sm);
-  if (st == SLOWMO_OK) st = run_mix(ctx, sm, &launched, stream);
+  if (st == SLOWMO_OK) st = run_mix(ctx, sm, 0, stream);
   if (st != SLOWMO_OK) return st;
   mix_weights(ctx, in_peer);
   return SLOWMO_OK;
@@ -1004,7 +907,6 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
   StagedMix sm;
   st = stage_mix(ctx, in_peer, /*with_idle=*/!two_kernels, stream, &sm);
   if (st != SLOWMO_OK) return st;
-  int launched = 0;
   if (two_kernels) {
     // same kernels as the separate calls
     const bool dead_after = c.policy == SLOWMO_BUF_RESET && ctx->k == c.tau - 1;
@@ -1012,30 +914,22 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
       return launch_local_step(a, c.base, bf16, ctx->buffers_zero, dead_after, ctx->tune, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-    launched = 1;
-    st = run_mix(ctx, sm, &launched, stream);
+    st = run_mix(ctx, sm, 1, stream);
     if (st != SLOWMO_OK) return st;
   } else {
     MixArgs x = mix_args(ctx);
-    auto with = [&](const TileRef *tiles, int32_t n) {
-      x.tiles = tiles;
-      x.ntiles = n;
-      return x;
-    };
+    int launched = 0;
     for (const auto &r : sm.ranges) {
       x.seq = sm.d_seq + r.first;
       x.len = r.second - r.first;
-      st = run_tiled(
-          ctx, &launched, "fused local+mixing kernel launch",
-          [&](const TileRef *t, int32_t n) {
-            return launch_local_mix_wide(a, with(t, n), ctx->layout.d_pad, ctx->n_tensors, c.base,
-                                         bf16, ctx->buffers_zero, ctx->tune, stream);
-          },
-          [&](const TileRef *t, int32_t n) {
-            return launch_local_mix_step(a, with(t, n), ctx->layout.d_pad, ctx->n_tensors, c.base,
-                                         bf16, ctx->buffers_zero, ctx->tune, stream);
-          });
-      if (st != SLOWMO_OK) return st;
+      const hipError_t e = guarded(ctx, [&] {
+        return launch_local_mix_step(a, x, ctx->layout.d_pad, ctx->n_tensors, c.base, bf16,
+                                     ctx->buffers_zero, ctx->tune, stream);
+      });
+      if (e != hipSuccess)
+        return launched ? fail_midway(ctx, e, "fused local+mixing kernel launch")
+                        : fail_hip(ctx, e, "fused local+mixing kernel launch");
+      ++launched;
     }
   }
   // counters and weights move only after the last launch was accepted

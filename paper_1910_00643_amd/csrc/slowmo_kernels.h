@@ -80,8 +80,6 @@ struct LaunchTuning {
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
   int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
   int32_t fuse_mix;     // 1: slowmo_local_mix_step runs one fused kernel when it can
-  int32_t wide;         // 1: full aligned 2048-element tiles of the all-worker kernels go to the
-                        // wide-tile kernels
   int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
                         // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
@@ -113,19 +111,6 @@ hipError_t launch_local_mix_step(const LocalArgs &l, const MixArgs &x, int64_t d
                                  int32_t n_tensors, int base, bool bf16, bool first,
                                  const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_debias(const DebiasArgs &a, const LaunchTuning &tune, hipStream_t stream);
-
-// The same four operations on WIDE tiles (kWideTile elements, every one full
-// and 16-byte aligned in all replicas; tiles[].k counts wide tiles).  Same
-// arithmetic, bit for bit; non-temporal accesses only.  The remainder of the
-// tensor list goes to the functions above with the rest of the tiles.
-hipError_t launch_outer_wide(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
-hipError_t launch_local_outer_wide(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
-                                   int base, bool bf16, bool first, int policy,
-                                   const LaunchTuning &tune, hipStream_t stream);
-hipError_t launch_mix_wide(const MixArgs &a, const LaunchTuning &tune, hipStream_t stream);
-hipError_t launch_local_mix_wide(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
-                                 int32_t n_tensors, int base, bool bf16, bool first,
-                                 const LaunchTuning &tune, hipStream_t stream);
 
 // Static device memory for the entry point that allocates nothing: room for
 // the de-bias table (destination pointers, then the push-sum weights) of up to

@@ -838,341 +838,6 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
   }
 }
 
-// ---- wide tiles for the kernels that walk all workers ---------------------------
-// The four kernels above touch 2m+4 .. 5m streams per workgroup.  With one
-// 16-byte vector per lane and stream (1 KiB per stream and wave) they run at
-// about 0.65 of the HBM peak; with VPT = 8 vectors per lane -- 8 KiB of every
-// stream per wave -- the same traffic measures 0.70 to 0.78 at m = 32 (at m = 8
-// it makes no difference).  The kernels below are that shape: same tiling idea,
-// same arithmetic in the same order, but a tile is 4 * B * VPT elements, and only
-// FULL tiles of tensors whose replicas are 16-byte aligned are given to them;
-// tails, small tensors and unaligned tensors stay with the kernels above (a
-// second launch over the rest of the tile list).  Lane t's v-th vector is
-// vector v * B + t of the tile, so every load instruction of a wave is one
-// contiguous 1 KiB burst.
-template <int B>
-__device__ __forceinline__ int wide_off(int v) {
-  return (v * B + static_cast<int>(threadIdx.x)) * 4;
-}
-
-template <int B, int VPT>
-__device__ __forceinline__ void average_wide(float *__restrict__ b0, int64_t stride, int m,
-                                             float m_f) {
-  V4 acc[VPT];
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) acc[v] = ld4<true>(b0 + wide_off<B>(v));
-#pragma unroll 2
-  for (int i = 1; i < m; ++i) {
-    const float *bi = b0 + i * stride;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) acc[v] = acc[v] + ld4<true>(bi + wide_off<B>(v));
-  }
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[v][c] = acc[v][c] / m_f;
-  }
-#pragma unroll 2
-  for (int i = 0; i < m; ++i) {
-    float *bi = b0 + i * stride;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) st4<true>(bi + wide_off<B>(v), acc[v]);
-  }
-}
-
-// k_outer_step on full tiles.
-template <int AVG, int B, int VPT>
-__global__ __launch_bounds__(B) void k_outer_wide(
-    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
-    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
-    float *__restrict__ hbase, float *__restrict__ vbase, int64_t d_pad, int ntiles, int chunk,
-    int remap, int m, OuterP p0) {
-  const int tile = tile_of(blockIdx.x, chunk, remap);
-  if (tile >= ntiles) return;
-  const TileRef t = tiles[tile];
-  const TensorInfo ti = tensors[t.owner];
-  const OuterP p = for_tensor(p0, ti.lr_scale);
-  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
-  float *x0 = x0base + ti.fo + eo;
-  float *u = ubase + ti.fo + eo;
-  V4 acc[VPT];
-  {
-    const float *x = xp[0] + eo;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) acc[v] = ld4<true>(x + wide_off<B>(v));
-  }
-#pragma unroll 2
-  for (int i = 1; i < m; ++i) {       // line 6: ordered sum, i = 0, 1, ..., m-1
-    const float *x = xp[i] + eo;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) acc[v] = acc[v] + ld4<true>(x + wide_off<B>(v));
-  }
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-    const V4 x0v = ld4<true>(x0 + wide_off<B>(v));
-    V4 uv = ld4<true>(u + wide_off<B>(v)), xn;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      float ue = uv[c];
-      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
-      uv[c] = ue;
-    }
-    st4<true>(u + wide_off<B>(v), uv);
-    st4<true>(x0 + wide_off<B>(v), xn);
-    acc[v] = xn;
-  }
-#pragma unroll 2
-  for (int i = 0; i < m; ++i) {
-    float *x = xp[i] + eo;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) st4<true>(x + wide_off<B>(v), acc[v]);
-  }
-  if constexpr (AVG >= 1) average_wide<B, VPT>(hbase + ti.fo + eo, d_pad, m, p.m_f);
-  if constexpr (AVG >= 2) average_wide<B, VPT>(vbase + ti.fo + eo, d_pad, m, p.m_f);
-}
-
-// The base-optimizer step of one worker on this lane's VPT vectors: all loads
-// first, then the arithmetic of k_local_step.
-template <int BASE, bool BF16, bool FIRST, int B, int VPT>
-__device__ __forceinline__ void step_wide(const float *xi, const float *hi, const float *vi,
-                                          const void *gi, const SgdP &sp, const AdamP &ap,
-                                          V4 (&xv)[VPT], V4 (&hv)[VPT], V4 (&vv)[VPT]) {
-  V4 gv[VPT];
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-    xv[v] = ld4<true>(xi + wide_off<B>(v));
-    if constexpr (!FIRST) hv[v] = ld4<true>(hi + wide_off<B>(v));
-    if constexpr (!FIRST && BASE == 1) vv[v] = ld4<true>(vi + wide_off<B>(v));
-    gv[v] = ldg4<BF16, true>(gi, v * B + static_cast<int>(threadIdx.x));
-  }
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      float xe = xv[v][c], he = FIRST ? 0.f : hv[v][c];
-      if constexpr (BASE == 0) {
-        sgd_elem<FIRST>(xe, he, gv[v][c], sp);
-      } else {
-        float ve = FIRST ? 0.f : vv[v][c];
-        adam_elem<FIRST>(xe, he, ve, gv[v][c], ap);
-        vv[v][c] = ve;
-      }
-      xv[v][c] = xe;
-      hv[v][c] = he;
-    }
-  }
-}
-
-// k_local_outer_step on full tiles.
-template <int BASE, bool BF16, bool FIRST, int POLICY, int B, int VPT>
-__global__ __launch_bounds__(B) void k_local_outer_wide(
-    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
-    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
-    float *__restrict__ x0base, float *__restrict__ ubase, float *__restrict__ hbase,
-    float *__restrict__ vbase, int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap,
-    int m, SgdP sp, AdamP ap, OuterP p0) {
-  const int tile = tile_of(blockIdx.x, chunk, remap);
-  if (tile >= ntiles) return;
-  const TileRef t = tiles[tile];
-  const TensorInfo ti = tensors[t.owner];
-  const OuterP p = for_tensor(p0, ti.lr_scale);
-  sp.lr = sp.lr * ti.lr_scale;
-  sp.wd = ti.wd;
-  ap.lr = ap.lr * ti.lr_scale;
-  ap.wd = ti.wd;
-  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
-  const void *const *__restrict__ gp = gtab + t.owner;
-  float *x0 = x0base + ti.fo + eo;
-  float *u = ubase + ti.fo + eo;
-  float *h0 = hbase + ti.fo + eo;
-  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
-  constexpr int gsize = BF16 ? 2 : 4;
-  V4 acc[VPT], acch[POLICY == 2 ? VPT : 1], accv[(POLICY == 2 && BASE == 1) ? VPT : 1];
-#ifndef SLOWMO_FUSED_WIDE_UNROLL
-#define SLOWMO_FUSED_WIDE_UNROLL 1
-#endif
-  _Pragma(SLOWMO_STR(unroll SLOWMO_FUSED_WIDE_UNROLL))
-  for (int i = 0; i < m; ++i) {
-    float *hi = h0 + i * d_pad;
-    float *vi = BASE == 1 ? v0 + i * d_pad : nullptr;
-    const void *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
-    V4 xv[VPT], hv[VPT], vv[VPT];
-    step_wide<BASE, BF16, FIRST, B, VPT>(xp[i] + eo, hi, vi, gi, sp, ap, xv, hv, vv);
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) {
-      if constexpr (POLICY == 1) {
-        st4<true>(hi + wide_off<B>(v), hv[v]);
-        if constexpr (BASE == 1) st4<true>(vi + wide_off<B>(v), vv[v]);
-      }
-      if constexpr (POLICY == 2) {
-        acch[v] = (i == 0) ? hv[v] : acch[v] + hv[v];
-        if constexpr (BASE == 1) accv[v] = (i == 0) ? vv[v] : accv[v] + vv[v];
-      }
-      acc[v] = (i == 0) ? xv[v] : acc[v] + xv[v];
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-    const V4 x0v = ld4<true>(x0 + wide_off<B>(v));
-    V4 uv = ld4<true>(u + wide_off<B>(v)), xn;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      float ue = uv[c];
-      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
-      uv[c] = ue;
-    }
-    st4<true>(u + wide_off<B>(v), uv);
-    st4<true>(x0 + wide_off<B>(v), xn);
-    acc[v] = xn;
-  }
-#pragma unroll 2
-  for (int i = 0; i < m; ++i) {
-    float *x = xp[i] + eo;
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) st4<true>(x + wide_off<B>(v), acc[v]);
-  }
-  if constexpr (POLICY == 2) {
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        acch[v][c] = acch[v][c] / p.m_f;
-        if constexpr (BASE == 1) accv[v][c] = accv[v][c] / p.m_f;
-      }
-    }
-#pragma unroll 2
-    for (int i = 0; i < m; ++i) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) {
-        st4<true>(h0 + i * d_pad + wide_off<B>(v), acch[v]);
-        if constexpr (BASE == 1) st4<true>(v0 + i * d_pad + wide_off<B>(v), accv[v]);
-      }
-    }
-  }
-}
-
-// k_mix_step on full tiles: one entry at a time (an entry already has VPT or
-// 2 VPT loads in flight per lane).
-template <int B, int VPT>
-__global__ __launch_bounds__(B) void k_mix_wide(
-    const TileRef *__restrict__ tiles, float *const *__restrict__ xtab_t,
-    const MixEntry *__restrict__ seq, int len, int ntiles, int chunk, int remap, int m) {
-  const int tile = tile_of(blockIdx.x, chunk, remap);
-  if (tile >= ntiles) return;
-  const TileRef t = tiles[tile];
-  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
-  V4 S[VPT], first[VPT];
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) S[v] = first[v] = V4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-  for (int e = 0; e < len; ++e) {
-    const MixEntry en = seq[e];
-    float *ptr = xp[en.node] + eo;
-    V4 own[VPT];
-    if (en.flags & kMixOwnFromS) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) own[v] = S[v];
-    } else {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) own[v] = ld4<SLOWMO_MIX_OWN_NT != 0>(ptr + wide_off<B>(v));
-    }
-    if (en.flags & kMixSaveFirst) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) first[v] = own[v];
-    }
-    if (en.flags & kMixNoSrc) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) st4<true>(ptr + wide_off<B>(v), en.a * own[v]);
-    } else {
-      if (en.flags & kMixSrcFromFirst) {
-#pragma unroll
-        for (int v = 0; v < VPT; ++v) S[v] = first[v];
-      } else if (!(en.flags & kMixSrcFromS)) {
-        const float *src = xp[en.src] + eo;
-#pragma unroll
-        for (int v = 0; v < VPT; ++v) S[v] = ld4<SLOWMO_MIX_SRC_NT != 0>(src + wide_off<B>(v));
-      }
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) st4<true>(ptr + wide_off<B>(v), en.a * own[v] + en.b * S[v]);
-    }
-  }
-}
-
-// k_local_mix_step on full tiles.
-template <int BASE, bool BF16, bool FIRST, int B, int VPT>
-__global__ __launch_bounds__(B) void k_local_mix_wide(
-    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
-    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
-    float *__restrict__ hbase, float *__restrict__ vbase, const MixEntry *__restrict__ seq, int len,
-    int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap, int m, SgdP sp, AdamP ap) {
-  const int tile = tile_of(blockIdx.x, chunk, remap);
-  if (tile >= ntiles) return;
-  const TileRef t = tiles[tile];
-  const TensorInfo ti = tensors[t.owner];
-  sp.lr = sp.lr * ti.lr_scale;
-  sp.wd = ti.wd;
-  ap.lr = ap.lr * ti.lr_scale;
-  ap.wd = ti.wd;
-  const int64_t eo = static_cast<int64_t>(t.k) * (4 * B * VPT);
-  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
-  const void *const *__restrict__ gp = gtab + t.owner;
-  float *h0 = hbase + ti.fo + eo;
-  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
-  constexpr int gsize = BF16 ? 2 : 4;
-  V4 Sx[VPT], Sh[VPT], Sv[VPT], first[VPT];
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) Sx[v] = Sh[v] = Sv[v] = first[v] = V4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-  for (int e = 0; e < len; ++e) {
-    const MixEntry en = seq[e];
-    float *xi = xp[en.node] + eo;
-    float *hi = h0 + en.node * d_pad;
-    float *vi = BASE == 1 ? v0 + en.node * d_pad : nullptr;
-    V4 xo[VPT], ho[VPT], vo[VPT];
-    if (en.flags & kMixOwnFromS) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) {
-        xo[v] = Sx[v];
-        ho[v] = Sh[v];
-        vo[v] = Sv[v];
-      }
-    } else {
-      const void *gi =
-          static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
-      step_wide<BASE, BF16, FIRST, B, VPT>(xi, hi, vi, gi, sp, ap, xo, ho, vo);
-    }
-#pragma unroll
-    for (int v = 0; v < VPT; ++v) {
-      st4<true>(hi + wide_off<B>(v), ho[v]);
-      if constexpr (BASE == 1) st4<true>(vi + wide_off<B>(v), vo[v]);
-    }
-    if (en.flags & kMixSaveFirst) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) first[v] = xo[v];
-    }
-    if (en.flags & kMixNoSrc) {
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) st4<true>(xi + wide_off<B>(v), en.a * xo[v]);
-    } else {
-      if (en.flags & kMixSrcFromFirst) {
-#pragma unroll
-        for (int v = 0; v < VPT; ++v) Sx[v] = first[v];
-      } else if (!(en.flags & kMixSrcFromS)) {
-        const void *gs =
-            static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;
-        step_wide<BASE, BF16, FIRST, B, VPT>(xp[en.src] + eo, h0 + en.src * d_pad,
-                                             BASE == 1 ? v0 + en.src * d_pad : nullptr, gs, sp, ap,
-                                             Sx, Sh, Sv);
-      }
-#pragma unroll
-      for (int v = 0; v < VPT; ++v) st4<true>(xi + wide_off<B>(v), en.a * xo[v] + en.b * Sx[v]);
-    }
-  }
-}
-
 // z^{(i)} = x^{(i)} / w_i (Algorithm C.1, last line), one workgroup per local tile.
 template <bool NT>
 __global__ __launch_bounds__(kLocalBlock) void k_debias(
@@ -1433,113 +1098,6 @@ hipError_t launch_outer_noavg_step(const OuterNoAvgArgs &a, const LaunchTuning &
                        a.slots, a.x0, a.u, a.ntiles, g.chunk, g.run, p);
   }
   return hipGetLastError();
-}
-
-// ---- wide-tile launchers ---------------------------------------------------------
-hipError_t launch_outer_wide(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.ntiles <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t);
-  const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
-  const int avg = a.avg_h ? (a.avg_v ? 2 : 1) : 0;
-#define SLOWMO_OUTER_WIDE(AVG)                                                                    \
-  hipLaunchKernelGGL((k_outer_wide<AVG, kWideBlock, kWideVpt>), dim3(g.blocks), dim3(kWideBlock), \
-                     0, s, a.tiles, a.tensors, a.xtab_t, a.x0, a.u, a.avg_h, a.avg_v, a.d_pad,    \
-                     a.ntiles, g.chunk, g.run, a.m, p)
-  if (avg == 0) {
-    SLOWMO_OUTER_WIDE(0);
-  } else if (avg == 1) {
-    SLOWMO_OUTER_WIDE(1);
-  } else {
-    SLOWMO_OUTER_WIDE(2);
-  }
-#undef SLOWMO_OUTER_WIDE
-  return hipGetLastError();
-}
-
-namespace {
-
-template <int BASE, bool BF16, bool FIRST, int POLICY>
-hipError_t launch_fused_wide_t(const LocalArgs &l, const OuterArgs &o, int n_tensors,
-                               const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(o.ntiles, t);
-  const SgdP sp{l.lr, l.mu, l.wd};
-  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
-  const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
-  hipLaunchKernelGGL((k_local_outer_wide<BASE, BF16, FIRST, POLICY, kWideBlock, kWideVpt>),
-                     dim3(g.blocks), dim3(kWideBlock), 0, s, o.tiles, o.tensors, o.xtab_t, l.gtab,
-                     o.x0, o.u, l.h, l.v, o.d_pad, n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap,
-                     p);
-  return hipGetLastError();
-}
-
-template <int BASE, bool BF16, bool FIRST>
-hipError_t launch_fused_wide_p(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
-                               const LaunchTuning &t, hipStream_t s) {
-  switch (policy) {
-    case 0: return launch_fused_wide_t<BASE, BF16, FIRST, 0>(l, o, n_tensors, t, s);
-    case 1: return launch_fused_wide_t<BASE, BF16, FIRST, 1>(l, o, n_tensors, t, s);
-    default: return launch_fused_wide_t<BASE, BF16, FIRST, 2>(l, o, n_tensors, t, s);
-  }
-}
-
-template <int BASE, bool BF16>
-hipError_t launch_fused_wide_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
-                               int policy, const LaunchTuning &t, hipStream_t s) {
-  return first ? launch_fused_wide_p<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
-               : launch_fused_wide_p<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
-}
-
-template <int BASE, bool BF16, bool FIRST>
-hipError_t launch_local_mix_wide_t(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
-                                   int n_tensors, const LaunchTuning &t, hipStream_t s) {
-  const Grid g = make_grid(x.ntiles, t);
-  const SgdP sp{l.lr, l.mu, l.wd};
-  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
-  hipLaunchKernelGGL((k_local_mix_wide<BASE, BF16, FIRST, kWideBlock, kWideVpt>), dim3(g.blocks),
-                     dim3(kWideBlock), 0, s, x.tiles, x.tensors, x.xtab_t, l.gtab, l.h, l.v, x.seq,
-                     x.len, d_pad, n_tensors, x.ntiles, g.chunk, g.run, x.m, sp, ap);
-  return hipGetLastError();
-}
-
-template <int BASE, bool BF16>
-hipError_t launch_local_mix_wide_f(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
-                                   int n_tensors, bool first, const LaunchTuning &t, hipStream_t s) {
-  return first ? launch_local_mix_wide_t<BASE, BF16, true>(l, x, d_pad, n_tensors, t, s)
-               : launch_local_mix_wide_t<BASE, BF16, false>(l, x, d_pad, n_tensors, t, s);
-}
-
-}  // namespace
-
-hipError_t launch_local_outer_wide(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
-                                   int base, bool bf16, bool first, int policy,
-                                   const LaunchTuning &t, hipStream_t s) {
-  if (o.ntiles <= 0) return hipSuccess;
-  if (base == 0) {
-    return bf16 ? launch_fused_wide_f<0, true>(l, o, n_tensors, first, policy, t, s)
-                : launch_fused_wide_f<0, false>(l, o, n_tensors, first, policy, t, s);
-  }
-  return bf16 ? launch_fused_wide_f<1, true>(l, o, n_tensors, first, policy, t, s)
-              : launch_fused_wide_f<1, false>(l, o, n_tensors, first, policy, t, s);
-}
-
-hipError_t launch_mix_wide(const MixArgs &a, const LaunchTuning &t, hipStream_t s) {
-  if (a.ntiles <= 0 || a.len <= 0) return hipSuccess;
-  const Grid g = make_grid(a.ntiles, t);
-  hipLaunchKernelGGL((k_mix_wide<kWideBlock, kWideVpt>), dim3(g.blocks), dim3(kWideBlock), 0, s,
-                     a.tiles, a.xtab_t, a.seq, a.len, a.ntiles, g.chunk, g.run, a.m);
-  return hipGetLastError();
-}
-
-hipError_t launch_local_mix_wide(const LocalArgs &l, const MixArgs &x, int64_t d_pad,
-                                 int32_t n_tensors, int base, bool bf16, bool first,
-                                 const LaunchTuning &t, hipStream_t s) {
-  if (x.ntiles <= 0 || x.len <= 0) return hipSuccess;
-  if (base == 0) {
-    return bf16 ? launch_local_mix_wide_f<0, true>(l, x, d_pad, n_tensors, first, t, s)
-                : launch_local_mix_wide_f<0, false>(l, x, d_pad, n_tensors, first, t, s);
-  }
-  return bf16 ? launch_local_mix_wide_f<1, true>(l, x, d_pad, n_tensors, first, t, s)
-              : launch_local_mix_wide_f<1, false>(l, x, d_pad, n_tensors, first, t, s);
 }
 
 }  // namespace slowmo

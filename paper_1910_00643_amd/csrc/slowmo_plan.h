@@ -30,13 +30,6 @@ constexpr int32_t kLocalBlock = SLOWMO_LOCAL_BLOCK;
 constexpr int32_t kLocalTile = 4 * kLocalBlock;
 constexpr int32_t kOuterBlock = SLOWMO_OUTER_BLOCK;
 constexpr int32_t kOuterTile = 4 * kOuterBlock;
-// Wide tiles of the kernels that walk all workers: kWideVpt vectors per lane
-// (8 KiB of every stream per wave).  Only whole wide tiles of 16-byte aligned
-// tensors are cut this way; the rest of the tensor list keeps kOuterTile.
-constexpr int32_t kWideBlock = 64;
-constexpr int32_t kWideVpt = 8;
-constexpr int32_t kWideTile = 4 * kWideBlock * kWideVpt;
-static_assert(kWideTile % kOuterTile == 0, "a wide tile is a whole number of ordinary tiles");
 
 // One tile of either kernel: the k-th piece of a tensor.  For the local step
 // `owner` is the slot (worker * n_tensors + tensor); for the outer step it is
@@ -112,8 +105,6 @@ Layout make_layout(int32_t n_tensors, const int64_t *numel);
 // Number of tiles of each kind (no allocation).
 int64_t count_local_tiles(int32_t m, int32_t n_tensors, const int64_t *numel);
 int64_t count_outer_tiles(int32_t n_tensors, const int64_t *numel);
-// Whole kWideTile pieces over all tensors (an upper bound on the wide tiles in use).
-int64_t count_wide_tiles(int32_t n_tensors, const int64_t *numel);
 
 // Tiles in launch order: worker-major, tensors in list order, offsets ascending.
 void plan_local(int32_t m, int32_t n_tensors, const int64_t *numel, std::vector<PlanRun> &runs);

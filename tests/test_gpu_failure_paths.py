@@ -35,17 +35,10 @@ def _make(w, prob, fail_launch_at=0):
     reports a launch failure without launching anything."""
     if fail_launch_at:
         os.environ["SLOWMO_TEST_FAIL_LAUNCH"] = str(fail_launch_at)
-    # ordinary tiles only: the tests below count the launches of a call, and wide
-    # tiles add one launch per kernel (they have a parity test of their own)
-    wide = os.environ.get("SLOWMO_WIDE")
-    os.environ["SLOWMO_WIDE"] = "0"
     try:
         return PU.make_gpu(w, prob)
     finally:
         os.environ.pop("SLOWMO_TEST_FAIL_LAUNCH", None)
-        os.environ.pop("SLOWMO_WIDE", None)
-        if wide is not None:
-            os.environ["SLOWMO_WIDE"] = wide
 
 
 def _everything(w, prob, opt, idx):

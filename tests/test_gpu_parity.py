@@ -393,47 +393,6 @@ def test_fused_last_local_and_outer_step(base, grad_dtype, policy, tau, layouts)
             assert np.array_equal(res[0]["v"], res[1]["v"])
 
 
-@pytest.mark.parametrize("base,grad_dtype,policy,mix,layouts", [
-    ("sgd_nesterov", "f32", "reset", "none", ("separate", "padded")),
-    ("sgd_nesterov", "bf16", "average", "none", ("separate", "separate")),
-    ("adam", "bf16", "maintain", "none", ("separate", "padded")),
-    ("adam", "f32", "average", "none", ("arena", "separate")),
-    ("sgd_nesterov", "f32", "reset", "expgraph", ("separate", "padded")),
-    ("sgd_nesterov", "f32", "maintain", "random", ("arena", "separate")),
-    ("adam", "bf16", "maintain", "random", ("separate", "padded")),
-    ("sgd_nesterov", "f32", "reset", "random", ("flat", "flat")),      # unaligned: no wide tiles
-])
-def test_wide_tiles_give_the_same_bits_as_ordinary_tiles(base, grad_dtype, policy, mix, layouts):
-    """The kernels that walk all workers (outer step, fused last step, gossip,
-    fused gossip) with 2048-element tiles for the whole pieces of aligned
-    tensors (SLOWMO_WIDE=1; chosen by itself from m = 16 on) against the same
-    run with ordinary tiles only: every replica, buffer, x0 and u bit for bit,
-    each run also against the oracle.  Tensor sizes sit on both sides of the
-    wide tile's 2048 elements."""
-    import os
-    sizes = (2047, 2048, 2049, 0, 4096, 4101, 10_000, 300, 6144)
-    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, m=5, policy=policy),
-                            shapes=tuple((f"t{j}", (n,)) for j, n in enumerate(sizes)), mix=mix,
-                            tau=3, rounds=3)
-    idx = np.arange(w.d, dtype=np.int64)
-    res = []
-    for wide in ("0", "1"):
-        os.environ["SLOWMO_WIDE"] = wide
-        try:
-            prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
-            opt = PU.make_gpu(w, prob)
-        finally:
-            os.environ.pop("SLOWMO_WIDE", None)
-        PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
-                       fused_last=(mix == "none"), fused_mix=(mix != "none"))
-        res.append((PU.gpu_state(w, prob, opt, idx), opt.pushsum_weights()))
-        opt.close()
-    assert res[0][1] == res[1][1]
-    for key in ("x", "x0", "u") + (() if policy == "reset" else ("h",)) + \
-            (("v",) if base == "adam" and policy != "reset" else ()):
-        assert np.array_equal(res[0][0][key], res[1][0][key]), key
-
-
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
