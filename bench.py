@@ -235,6 +235,50 @@ def time_workload(w, steps, warmup, ring=None, fused=False, fused_mix=False, ker
     return wall, round_ms, kern_ms
 
 
+def graph_replay(w, steps, warmup):
+    """The launch-bound case: one whole outer iteration (tau-1 local steps and
+    the fused last step, all on one gradient set) captured into a HIP graph and
+    replayed.  With unchanged gradient pointers the library only launches
+    kernels, and for the SGD base with the reset policy every outer iteration
+    is the same sequence of launches with the same arguments, so a replay is one
+    more outer iteration.  Returns ms per replayed iteration (median, min) --
+    a launch-overhead figure, not a bandwidth claim."""
+    import torch
+    assert w.base == "sgd_nesterov" and w.policy == "reset" and fusable(w)
+    prob, opt = build_problem(w, 1)
+    arr = opt.grad_pointer_array(prob.grads[0])
+
+    def one_round():
+        for _ in range(w.tau - 1):
+            opt.local_step(arr, w.lr)
+        opt.local_outer_step(arr, w.lr)
+
+    one_round()                                 # eager: uploads the pointer table
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=cap):
+        one_round()
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    marks = []
+    for _ in range(steps + 1):
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        marks.append(e)
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
+    opt.close()
+    del prob, opt, graph
+    torch.cuda.empty_cache()
+    return {"median": _median(ms), "min": min(ms), "n": len(ms),
+            "what": "ms per outer iteration replayed from a HIP graph (tau kernel launches)"}
+
+
 def _median(v):
     v = sorted(v)
     n = len(v)
@@ -477,6 +521,8 @@ def main():
         for w2, steps2, warm2, krounds in others:
             r2 = measure(w2, steps2, warm2, default_ring(w2), kernel_rounds=krounds)
             r2["variant"] = variant_name(w2)
+            if w2.name == "tiny":       # launch-bound: also as a captured graph
+                r2["hip_graph_replay_ms"] = graph_replay(w2, 50, 5)
             if w2.name == "transformer_big" and w2.mix == "none" and not args.no_cpu_baseline:
                 r2["cpu_baseline"] = cpu_baseline(w2, budget_s=10.0)
             out["other_workloads"].append(r2)

@@ -242,11 +242,21 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
  * step.  They are read from memory unless a flag says that the kernel still
  * holds them: OWN_HELD / SOURCE_HELD -- the operand is the source operand of
  * the closest earlier entry that has one; SOURCE_IS_FIRST -- the operand is
- * the own operand of the closest earlier entry flagged OPENS_CYCLE.  The order
+ * the own operand of the closest earlier entry flagged OPENS_CYCLE.  The
+ * kernel has SLOWMO_MIX_SAVED_REGISTERS more registers for operands ("saved"),
+ * numbered from 1; three 3-bit fields of `flags` (0 = no) refer to them:
+ * SLOWMO_MIX_SAVE(flags) = k -- before this entry's source operand replaces the
+ * held one (the source operand of the closest earlier entry that has one), the
+ * held operand is copied into saved register k, because a later entry needs it
+ * again; SLOWMO_MIX_OWN_SAVED(flags) = k / SLOWMO_MIX_SOURCE_SAVED(flags) = k --
+ * the operand is the one in saved register k (as a source it also becomes the
+ * held operand again).  A sender with several receivers is thus read once even
+ * when other senders come in between (as long as a register is free;
+ * otherwise it is read again).  The order
  * is valid if no entry reads from memory a worker that an earlier entry has
  * written.  Idle workers (no sender, no receiver) have no entry.  Entries of
  * one connected group of workers are consecutive and the first of them carries
- * GROUP_START; no HELD / IS_FIRST flag refers across a group start, and the
+ * GROUP_START; no HELD / IS_FIRST / SAVED flag refers across a group start, and the
  * library runs the groups as separate kernel launches.
  * Writes at most m entries to `out` (host) and returns their number, or -1
  * for bad arguments.  Host-only.
@@ -259,6 +269,10 @@ enum {
   SLOWMO_MIX_NO_SOURCE = 16,
   SLOWMO_MIX_GROUP_START = 32
 };
+#define SLOWMO_MIX_SAVED_REGISTERS 4
+#define SLOWMO_MIX_SAVE(flags) (((flags) >> 6) & 7)
+#define SLOWMO_MIX_OWN_SAVED(flags) (((flags) >> 9) & 7)
+#define SLOWMO_MIX_SOURCE_SAVED(flags) (((flags) >> 12) & 7)
 typedef struct slowmo_mix_entry {
   int32_t worker;
   int32_t source;

@@ -39,6 +39,19 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
 
 (SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
  SLOWMO_MIX_NO_SOURCE, SLOWMO_MIX_GROUP_START) = 1, 2, 4, 8, 16, 32
+SLOWMO_MIX_SAVED_REGISTERS = 4
+
+
+def SLOWMO_MIX_SAVE(flags: int) -> int:
+    return (flags >> 6) & 7
+
+
+def SLOWMO_MIX_OWN_SAVED(flags: int) -> int:
+    return (flags >> 9) & 7
+
+
+def SLOWMO_MIX_SOURCE_SAVED(flags: int) -> int:
+    return (flags >> 12) & 7
 
 
 class slowmo_mix_entry(C.Structure):

@@ -940,6 +940,13 @@ slowmo_status slowmo_local_mix_step(slowmo_ctx *ctx, const void *const *grads, f
 
 int32_t slowmo_plan_mix(int32_t m, const int32_t *in_peer, slowmo_mix_entry *out) {
   static_assert(sizeof(slowmo_mix_entry) == sizeof(MixEntry), "public and internal entry differ");
+  static_assert(SLOWMO_MIX_SAVE(5 << 6) == mix_save(5 << 6) && mix_save(5 << 6) == 5 &&
+                    SLOWMO_MIX_OWN_SAVED(5 << 9) == mix_own_saved(5 << 9) &&
+                    mix_own_saved(5 << 9) == 5 &&
+                    SLOWMO_MIX_SOURCE_SAVED(5 << 12) == mix_src_saved(5 << 12) &&
+                    mix_src_saved(5 << 12) == 5 && SLOWMO_MIX_SAVED_REGISTERS == kMixSaved &&
+                    SLOWMO_MIX_GROUP_START == kMixGroupStart,
+                "public and internal flags differ");
   if (m < 1 || m > SLOWMO_MAX_WORKERS || !in_peer || !out) return -1;
   for (int32_t i = 0; i < m; ++i)
     if (in_peer[i] < 0 || in_peer[i] >= m) return -1;

@@ -615,6 +615,46 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
 #endif
 constexpr int kMixBatch = SLOWMO_MIX_BATCH;
 
+// The saved registers of the mixing kernels: kMixSaved values of type T, read
+// and written with a register number 1..kMixSaved that is uniform over the
+// workgroup (named members, so that they live in registers).
+template <typename T>
+struct SavedRegs {
+  T r1, r2, r3, r4;
+  __device__ __forceinline__ void clear(const T &z) { r1 = r2 = r3 = r4 = z; }
+  __device__ __forceinline__ void put(int k, const T &v) {
+    if (k == 1) {
+      r1 = v;
+    } else if (k == 2) {
+      r2 = v;
+    } else if (k == 3) {
+      r3 = v;
+    } else if (k == 4) {
+      r4 = v;
+    }
+  }
+  __device__ __forceinline__ T get(int k, T v) const {   // v: the result for k == 0
+    if (k == 1) {
+      v = r1;
+    } else if (k == 2) {
+      v = r2;
+    } else if (k == 3) {
+      v = r3;
+    } else if (k == 4) {
+      v = r4;
+    }
+    return v;
+  }
+};
+static_assert(kMixSaved == 4, "SavedRegs has four members");
+// an entry's operand that is in a register already (not read from memory)
+__device__ __forceinline__ bool mix_own_in_register(int32_t flags) {
+  return (flags & kMixOwnFromS) || mix_own_saved(flags);
+}
+__device__ __forceinline__ bool mix_src_in_register(int32_t flags) {
+  return (flags & (kMixSrcFromS | kMixSrcFromFirst)) || mix_src_saved(flags);
+}
+
 template <bool NT>
 __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
     const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
@@ -632,6 +672,8 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
   if (e0 >= n) return;
   if (ti.unaligned == 0 && e0 + 4 <= n) {
     V4 S = {0.f, 0.f, 0.f, 0.f}, first = S;
+    SavedRegs<V4> H;
+    H.clear(S);
     for (int base = 0; base < len; base += kMixBatch) {
       V4 own[kMixBatch], sv[kMixBatch];
       float *ptr[kMixBatch];
@@ -640,8 +682,8 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
         if (base + q < len) {
           const MixEntry en = seq[base + q];
           ptr[q] = xp[en.node] + eo + e0;
-          if (!(en.flags & kMixOwnFromS)) own[q] = ld4<NT && SLOWMO_MIX_OWN_NT>(ptr[q]);
-          if (!(en.flags & (kMixSrcFromS | kMixSrcFromFirst | kMixNoSrc)))
+          if (!mix_own_in_register(en.flags)) own[q] = ld4<NT && SLOWMO_MIX_OWN_NT>(ptr[q]);
+          if (!(en.flags & kMixNoSrc) && !mix_src_in_register(en.flags))
             sv[q] = ld4<NT && SLOWMO_MIX_SRC_NT>(xp[en.src] + eo + e0);
         }
       }
@@ -649,15 +691,16 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
       for (int q = 0; q < kMixBatch; ++q) {
         if (base + q < len) {
           const MixEntry en = seq[base + q];
-          const V4 o = (en.flags & kMixOwnFromS) ? S : own[q];
+          const V4 o = (en.flags & kMixOwnFromS) ? S : H.get(mix_own_saved(en.flags), own[q]);
           if (en.flags & kMixSaveFirst) first = o;
           if (en.flags & kMixNoSrc) {
             st4<NT>(ptr[q], en.a * o);
           } else {
+            H.put(mix_save(en.flags), S);
             if (en.flags & kMixSrcFromFirst) {
               S = first;
             } else if (!(en.flags & kMixSrcFromS)) {
-              S = sv[q];
+              S = H.get(mix_src_saved(en.flags), sv[q]);
             }
             st4<NT>(ptr[q], en.a * o + en.b * S);
           }
@@ -668,16 +711,23 @@ __global__ __launch_bounds__(kOuterBlock) void k_mix_step(
     const int e1 = e0 + 4 < n ? e0 + 4 : n;
     for (int j = e0; j < e1; ++j) {
       float S = 0.f, first = 0.f;
+      SavedRegs<float> H;
+      H.clear(0.f);
       for (int i = 0; i < len; ++i) {
         const MixEntry en = seq[i];
         float *ptr = xp[en.node] + eo + j;
-        const float o = (en.flags & kMixOwnFromS) ? S : ld1(ptr);
+        const float o = (en.flags & kMixOwnFromS)       ? S
+                        : mix_own_saved(en.flags) != 0 ? H.get(mix_own_saved(en.flags), 0.f)
+                                                       : ld1(ptr);
         if (en.flags & kMixSaveFirst) first = o;
         if (en.flags & kMixNoSrc) {
           st1(ptr, en.a * o);
         } else {
+          H.put(mix_save(en.flags), S);
           if (en.flags & kMixSrcFromFirst) {
             S = first;
+          } else if (mix_src_saved(en.flags)) {
+            S = H.get(mix_src_saved(en.flags), 0.f);
           } else if (!(en.flags & kMixSrcFromS)) {
             S = ld1(xp[en.src] + eo + j);
           }
@@ -764,6 +814,10 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
   if (e0 >= n) return;
   if (e0 + 4 <= n) {
     V4 Sx = {0.f, 0.f, 0.f, 0.f}, Sh = Sx, Sv = Sx, first = Sx;
+    SavedRegs<V4> Hx, Hh, Hv;       // saved stepped workers: new x, h and v
+    Hx.clear(Sx);
+    Hh.clear(Sx);
+    Hv.clear(Sx);
 #pragma unroll 1
     for (int i = 0; i < len; ++i) {
       const MixEntry en = seq[i];
@@ -771,10 +825,10 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
       float *hi = h0 + en.node * d_pad + e0;
       float *vi = BASE == 1 ? v0 + en.node * d_pad + e0 : nullptr;
       V4 xo, ho, vo;
-      if (en.flags & kMixOwnFromS) {
-        xo = Sx;
-        ho = Sh;
-        vo = Sv;
+      if (mix_own_in_register(en.flags)) {       // in a saved register, else held in S
+        xo = Hx.get(mix_own_saved(en.flags), Sx);
+        ho = Hh.get(mix_own_saved(en.flags), Sh);
+        vo = Hv.get(mix_own_saved(en.flags), Sv);
       } else {
         const void *gi =
             static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
@@ -786,8 +840,15 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
       if (en.flags & kMixNoSrc) {
         st4<NT>(xi, en.a * xo);
       } else {
+        Hx.put(mix_save(en.flags), Sx);
+        Hh.put(mix_save(en.flags), Sh);
+        Hv.put(mix_save(en.flags), Sv);
         if (en.flags & kMixSrcFromFirst) {
           Sx = first;
+        } else if (mix_src_saved(en.flags)) {
+          Sx = Hx.get(mix_src_saved(en.flags), Sx);
+          Sh = Hh.get(mix_src_saved(en.flags), Sh);
+          Sv = Hv.get(mix_src_saved(en.flags), Sv);
         } else if (!(en.flags & kMixSrcFromS)) {
           const void *gs =
               static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;
@@ -801,16 +862,20 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
   } else {
     for (int j = e0; j < n; ++j) {        // ragged tail of the tensor
       float Sx = 0.f, Sh = 0.f, Sv = 0.f, first = 0.f;
+      SavedRegs<float> Hx, Hh, Hv;
+      Hx.clear(0.f);
+      Hh.clear(0.f);
+      Hv.clear(0.f);
       for (int i = 0; i < len; ++i) {
         const MixEntry en = seq[i];
         float *xi = xp[en.node] + eo + j;
         float *hi = h0 + en.node * d_pad + j;
         float *vi = BASE == 1 ? v0 + en.node * d_pad + j : nullptr;
         float xo, ho, vo;
-        if (en.flags & kMixOwnFromS) {
-          xo = Sx;
-          ho = Sh;
-          vo = Sv;
+        if (mix_own_in_register(en.flags)) {
+          xo = Hx.get(mix_own_saved(en.flags), Sx);
+          ho = Hh.get(mix_own_saved(en.flags), Sh);
+          vo = Hv.get(mix_own_saved(en.flags), Sv);
         } else {
           const void *gi =
               static_cast<const char *>(gp[static_cast<int64_t>(en.node) * n_tensors]) + eo * gsize;
@@ -822,8 +887,15 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_mix_step(
         if (en.flags & kMixNoSrc) {
           st1(xi, en.a * xo);
         } else {
+          Hx.put(mix_save(en.flags), Sx);
+          Hh.put(mix_save(en.flags), Sh);
+          Hv.put(mix_save(en.flags), Sv);
           if (en.flags & kMixSrcFromFirst) {
             Sx = first;
+          } else if (mix_src_saved(en.flags)) {
+            Sx = Hx.get(mix_src_saved(en.flags), Sx);
+            Sh = Hh.get(mix_src_saved(en.flags), Sh);
+            Sv = Hv.get(mix_src_saved(en.flags), Sv);
           } else if (!(en.flags & kMixSrcFromS)) {
             const void *gs =
                 static_cast<const char *>(gp[static_cast<int64_t>(en.src) * n_tensors]) + eo * gsize;

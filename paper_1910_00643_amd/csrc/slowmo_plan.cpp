@@ -156,13 +156,55 @@ void plan_mix(int32_t m, const int32_t *in_peer, std::vector<MixEntry> &seq,
     seq.back().flags |= kMixSrcFromFirst;
   }
   for (size_t at : group_start) seq[at].flags |= kMixGroupStart;
-  // operands that the kernel still holds from the previous entry of the group
-  int32_t held = -1;  // worker whose old value is in the kernel's source register
-  for (MixEntry &e : seq) {
-    if (e.flags & kMixGroupStart) held = -1;
-    if (e.node == held) e.flags |= kMixOwnFromS;
+  // Operands the kernel still holds when an entry needs them.  `held`: the
+  // worker whose old value is in the source register (the previous entry's
+  // source).  saved[k]: the worker whose old value was copied into saved
+  // register k when another source took its place in the source register,
+  // because it is needed again (by a later receiver, or at its own turn, which
+  // is always its last use); the register is free again after that turn.
+  std::vector<int32_t> last_use(m, -1);
+  for (size_t idx = 0; idx < seq.size(); ++idx) {
+    if (!(seq[idx].flags & kMixNoSrc)) last_use[seq[idx].src] = static_cast<int32_t>(idx);
+    last_use[seq[idx].node] = static_cast<int32_t>(idx);
+  }
+  int32_t held = -1, saved[kMixSaved];
+  for (int32_t &w : saved) w = -1;
+  auto saved_in = [&](int32_t w) {
+    for (int k = 0; k < kMixSaved; ++k)
+      if (w >= 0 && saved[k] == w) return k;
+    return -1;
+  };
+  for (size_t idx = 0; idx < seq.size(); ++idx) {
+    MixEntry &e = seq[idx];
+    if (e.flags & kMixGroupStart) {
+      held = -1;
+      for (int32_t &w : saved) w = -1;
+    }
+    const int own_saved = saved_in(e.node);
+    if (e.node == held) {
+      e.flags |= kMixOwnFromS;
+    } else if (own_saved >= 0) {
+      e.flags |= (own_saved + 1) << kMixOwnSavedShift;
+    }
+    if (own_saved >= 0) saved[own_saved] = -1;  // the worker's own turn is its last use
     if (e.flags & kMixNoSrc) continue;
-    if (e.src == held && !(e.flags & kMixSrcFromFirst)) e.flags |= kMixSrcFromS;
+    const bool from_first = (e.flags & kMixSrcFromFirst) != 0;
+    if (!from_first && e.src == held) {
+      e.flags |= kMixSrcFromS;
+      continue;
+    }
+    // the source register gets a new value: keep the old one if it is needed again
+    if (held >= 0 && last_use[held] > static_cast<int32_t>(idx) && saved_in(held) < 0) {
+      for (int k = 0; k < kMixSaved; ++k) {
+        if (saved[k] < 0) {
+          saved[k] = held;
+          e.flags |= (k + 1) << kMixSaveShift;
+          break;
+        }
+      }
+    }
+    const int src_saved = from_first ? -1 : saved_in(e.src);
+    if (src_saved >= 0) e.flags |= (src_saved + 1) << kMixSrcSavedShift;
     held = e.src;
   }
 }

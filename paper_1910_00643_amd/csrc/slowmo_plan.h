@@ -77,6 +77,10 @@ struct PlanRun {  // host description of a tile (mirrors slowmo_plan_run)
 // needed; the members of a cycle follow each other, each before its source,
 // and the last one takes the first one's old value from a register.  Where an
 // operand is the previous entry's source it is taken from a register too.
+// Two more registers ("saved" operands) keep a sender whose later receivers or
+// own turn come only after other senders have passed through the source
+// register, so that it is not read (in the fused kernel: stepped) again.
+constexpr int32_t kMixSaved = 4;
 enum MixFlag : int32_t {
   kMixOwnFromS = 1,      // the worker's old value is the previous entry's source value
   kMixSrcFromS = 2,      // same source as the previous entry
@@ -85,6 +89,19 @@ enum MixFlag : int32_t {
   kMixNoSrc = 16,        // receives from nobody: x <- a * x
   kMixGroupStart = 32,   // first entry of a connected group of workers (for the launcher only)
 };
+// Three 3-bit fields above the flag bits, each 0 (no) or 1 + the number of a
+// saved register:
+//   save : before this entry's source replaces the held source value, the held
+//          one is copied into that saved register;
+//   own  : the worker's old value is in that saved register;
+//   src  : the source value is in that saved register (and becomes the held
+//          source value again).
+constexpr int32_t kMixSaveShift = 6, kMixOwnSavedShift = 9, kMixSrcSavedShift = 12;
+constexpr int32_t kMixFieldMask = 7;
+constexpr int32_t mix_save(int32_t flags) { return (flags >> kMixSaveShift) & kMixFieldMask; }
+constexpr int32_t mix_own_saved(int32_t flags) { return (flags >> kMixOwnSavedShift) & kMixFieldMask; }
+constexpr int32_t mix_src_saved(int32_t flags) { return (flags >> kMixSrcSavedShift) & kMixFieldMask; }
+static_assert(kMixSaved <= kMixFieldMask, "register numbers must fit the fields");
 struct MixEntry {
   int32_t node;    // worker updated by this entry
   int32_t src;     // worker it receives from (the worker itself with kMixNoSrc)

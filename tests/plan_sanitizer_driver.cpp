@@ -51,7 +51,7 @@ static void check_tiling(std::mt19937_64 &rng) {
   }
 }
 
-// Replays the entries on one array the way the kernel does (two registers) and
+// Replays the entries on one array the way the kernel does (its registers) and
 // compares with the update computed from a saved copy.
 static void check_mix(int32_t m, const std::vector<int32_t> &peer) {
   std::vector<MixEntry> seq;
@@ -67,17 +67,28 @@ static void check_mix(int32_t m, const std::vector<int32_t> &peer) {
   }
   REQUIRE(seq.empty() || (seq[0].flags & kMixGroupStart));
   std::vector<char> written(m, 0);
-  float S = 0.f, first = 0.f;
-  bool s_valid = false, first_valid = false;
+  float S = 0.f, first = 0.f, H[kMixSaved + 1] = {};           // saved registers, numbered from 1
+  bool s_valid = false, first_valid = false, h_valid[kMixSaved + 1] = {};
+  int64_t reads = 0;
   for (const MixEntry &e : seq) {
     REQUIRE(e.node >= 0 && e.node < m && e.src >= 0 && e.src < m && !written[e.node]);
-    if (e.flags & kMixGroupStart) s_valid = first_valid = false;  // a launch of its own
+    if (e.flags & kMixGroupStart) {     // a launch of its own: registers start empty
+      s_valid = first_valid = false;
+      for (bool &v : h_valid) v = false;
+    }
+    REQUIRE(mix_save(e.flags) <= kMixSaved && mix_own_saved(e.flags) <= kMixSaved &&
+            mix_src_saved(e.flags) <= kMixSaved);
     float own;
     if (e.flags & kMixOwnFromS) {
       REQUIRE(s_valid);
       own = S;
+    } else if (mix_own_saved(e.flags)) {
+      const int k = mix_own_saved(e.flags);
+      REQUIRE(h_valid[k]);
+      own = H[k];
     } else {
       own = x[e.node];
+      ++reads;
     }
     if (e.flags & kMixSaveFirst) {
       first = own;
@@ -88,20 +99,31 @@ static void check_mix(int32_t m, const std::vector<int32_t> &peer) {
       x[e.node] = e.a * own;
     } else {
       REQUIRE(e.src == peer[e.node] && e.src != e.node);
+      if (mix_save(e.flags)) {
+        REQUIRE(s_valid);
+        H[mix_save(e.flags)] = S;
+        h_valid[mix_save(e.flags)] = true;
+      }
       if (e.flags & kMixSrcFromFirst) {
         REQUIRE(first_valid);
         S = first;
+      } else if (mix_src_saved(e.flags)) {
+        const int k = mix_src_saved(e.flags);
+        REQUIRE(h_valid[k]);
+        S = H[k];
       } else if (e.flags & kMixSrcFromS) {
         REQUIRE(s_valid);
       } else {
         REQUIRE(!written[e.src]);
         S = x[e.src];
+        ++reads;
       }
       s_valid = true;
       x[e.node] = e.a * own + e.b * S;
     }
     written[e.node] = 1;
   }
+  REQUIRE(reads <= 2 * static_cast<int64_t>(seq.size()));
   for (int32_t i = 0; i < m; ++i) {
     REQUIRE(std::memcmp(&x[i], &want[i], sizeof(float)) == 0);
     if (!written[i]) {  // idle: no sender, no receiver

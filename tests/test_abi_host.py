@@ -218,6 +218,7 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
             got = x.copy()
             seen = set()
             held = first = None          # what the kernel keeps in registers
+            saved = [None] * (B.SLOWMO_MIX_SAVED_REGISTERS + 1)      # numbered from 1
             loads = 0
             group_of = {}
             for worker, source, keep, take, flags in plan:
@@ -225,12 +226,20 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
                 assert worker not in seen
                 if flags & B.SLOWMO_MIX_GROUP_START:    # another launch: registers start empty
                     held = first = None
+                    saved = [None] * (B.SLOWMO_MIX_SAVED_REGISTERS + 1)
                     group = len(set(group_of.values()))
                     assert not flags & (B.SLOWMO_MIX_OWN_HELD | B.SLOWMO_MIX_SOURCE_HELD
                                         | B.SLOWMO_MIX_SOURCE_IS_FIRST)
+                    assert not (B.SLOWMO_MIX_OWN_SAVED(flags) or B.SLOWMO_MIX_SOURCE_SAVED(flags)
+                                or B.SLOWMO_MIX_SAVE(flags))
                 group_of[worker] = group
+                assert max(B.SLOWMO_MIX_SAVE(flags), B.SLOWMO_MIX_OWN_SAVED(flags),
+                           B.SLOWMO_MIX_SOURCE_SAVED(flags)) <= B.SLOWMO_MIX_SAVED_REGISTERS
                 if flags & B.SLOWMO_MIX_OWN_HELD:
                     own = held
+                elif B.SLOWMO_MIX_OWN_SAVED(flags):
+                    own = saved[B.SLOWMO_MIX_OWN_SAVED(flags)]
+                    assert own is not None
                 else:
                     own = got[worker].copy()
                     loads += 1
@@ -241,8 +250,14 @@ def test_mix_plan_applied_in_place_equals_the_simultaneous_update(kind):
                     got[worker] = keep * own
                 else:
                     assert source == peers[worker] != worker
+                    if B.SLOWMO_MIX_SAVE(flags):
+                        assert held is not None
+                        saved[B.SLOWMO_MIX_SAVE(flags)] = held
                     if flags & B.SLOWMO_MIX_SOURCE_IS_FIRST:
                         held = first
+                    elif B.SLOWMO_MIX_SOURCE_SAVED(flags):
+                        held = saved[B.SLOWMO_MIX_SOURCE_SAVED(flags)]
+                        assert held is not None
                     elif not flags & B.SLOWMO_MIX_SOURCE_HELD:
                         assert source not in seen       # memory still holds the old value
                         held = got[source].copy()
