@@ -87,6 +87,20 @@ def fused_bytes_per_element(w) -> int:
     return reads + writes
 
 
+BIG_TILE = 65536                # elements of a big tile (kBigTile of the library)
+
+
+def big_elements(w, fused: bool) -> int:
+    """Elements that the big-tile kernels take in the outer step (fused with
+    the last local step or not): the whole 65 536-element pieces of every
+    tensor, from 8 workers on for the fused kernel and from 16 for the plain
+    outer step, unless the buffers are averaged (the library's rule; every
+    tensor of the benchmark is 16-byte aligned)."""
+    if not w.exact_average or w.policy == "average" or w.m < (8 if fused else 16):
+        return 0
+    return sum(n // BIG_TILE * BIG_TILE for n in w.numel)
+
+
 def fusable(w) -> bool:
     return w.exact_average and w.mix == "none"
 
@@ -329,8 +343,12 @@ def measure(w, steps, warmup, ring, unfused=False, kernel_rounds=None, debias=Fa
              "local_mix": "k_local_mix_step (steady state; all launches of one step)",
              "local_mix_first": "k_local_mix_step (buffers read as zero)",
              "mix": "k_mix_step (all launches of one step)",
-             "outer": "k_outer_noavg" if not w.exact_average else "k_outer_step",
-             "fused_last_outer": "k_local_outer_step", "debias": "k_debias"}
+             "outer": "k_outer_noavg" if not w.exact_average else
+                      "k_outer_big + k_outer_step (whole 65 536-element pieces + rest)"
+                      if big_elements(w, False) else "k_outer_step",
+             "fused_last_outer": "k_local_outer_big + k_local_outer_step (whole 65 536-element "
+                                 "pieces + rest)" if big_elements(w, True) else "k_local_outer_step",
+             "debias": "k_debias"}
     kernels = {}
     for kind, ms in kern_ms.items():
         if ms:

@@ -51,7 +51,10 @@
  *    kernels or copies (slowmo_mix_step and slowmo_local_mix_step launch one
  *    kernel per connected group of workers; slowmo_local_outer_step and
  *    slowmo_local_mix_step launch two kernels when a pointer is not 16-byte
- *    aligned; slowmo_import_state copies up to four arrays).  If the HIP
+ *    aligned; slowmo_outer_step and slowmo_local_outer_step launch one kernel
+ *    for the whole 65 536-element pieces of the tensors and one for the rest
+ *    when there are 8 workers or more; slowmo_import_state copies up to four
+ *    arrays).  If the HIP
  *    runtime refuses one of them after an earlier one was issued, device
  *    memory is partly updated and cannot be rolled back: the call returns
  *    SLOWMO_ERR_HIP with a message that says so, counters and weights keep

@@ -37,11 +37,11 @@ size_t ztab_bytes(int32_t m, int32_t n_tensors) {
 
 // Byte offsets of the sections of the caller's workspace.
 struct Sections {
-  size_t x0, u, h, v, xtab_t, gtab[kGradSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, total;
+  size_t x0, u, h, v, xtab_t, gtab[kGradSlots], mixtab[kSlots], ztab[kSlots], slots, tensors, ltiles, otiles, btiles, rtiles, total;
 };
 
 Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &L, size_t n_ltiles,
-                       size_t n_otiles) {
+                       size_t n_otiles, size_t n_btiles) {
   Sections s{};
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -64,6 +64,9 @@ Sections make_sections(const slowmo_config &c, int32_t n_tensors, const Layout &
   s.tensors = take(static_cast<size_t>(n_tensors) * sizeof(TensorInfo));
   s.ltiles = take(n_ltiles * sizeof(TileRef));
   s.otiles = take(n_otiles * sizeof(TileRef));
+  // big tiles and the ordinary tiles they leave over (at most all of them)
+  s.btiles = take(n_btiles * sizeof(TileRef));
+  s.rtiles = take(n_btiles ? n_otiles * sizeof(TileRef) : 0);
   s.total = off;
   return s;
 }
@@ -231,6 +234,13 @@ struct slowmo_ctx {
   TileRef *d_ltiles = nullptr;
   TileRef *d_otiles = nullptr;
   int32_t n_ltiles = 0, n_otiles = 0;
+  // With big tiles in use, the outer step and the fused last step run twice:
+  // over the big tiles (whole kBigTile pieces of the tensors all of whose
+  // replicas are 16-byte aligned) and over the ordinary tiles these leave
+  // over.  Otherwise n_btiles = 0 and the rest list is the whole ordinary list.
+  TileRef *d_btiles = nullptr, *d_rtiles = nullptr;
+  int32_t n_btiles = 0, n_rtiles = 0;
+  bool big_outer = false;  // the plain outer step uses them too (it gains only with many workers)
 
   TableRing<kGradSlots> gtab;  // gradient-pointer tables of recent calls (m * n_tensors each)
   TableRing<kSlots> mixtab;  // update order of the current mixing step (at most m entries)
@@ -292,6 +302,27 @@ slowmo_status fail_midway(slowmo_ctx *ctx, hipError_t e, const char *what) {
                   "partly updated and the context refuses further steps");
 }
 
+// A kernel that walks all workers per workgroup runs over the big tiles (if
+// any) with `big`, then over the ordinary tiles they leave over with `rest`;
+// both take (tiles, count) and return a hipError_t.  *launched counts the
+// kernels of the current call issued so far: a failure after the first one is
+// a failure halfway.
+template <typename FB, typename FR>
+slowmo_status run_tiled(slowmo_ctx *ctx, bool use_big, int *launched, const char *what, FB &&big,
+                        FR &&rest) {
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool b = pass == 0;
+    if (b && !use_big) continue;
+    const TileRef *tiles = b ? ctx->d_btiles : (use_big ? ctx->d_rtiles : ctx->d_otiles);
+    const int32_t n = b ? ctx->n_btiles : (use_big ? ctx->n_rtiles : ctx->n_otiles);
+    if (n <= 0) continue;
+    const hipError_t e = guarded(ctx, [&] { return b ? big(tiles, n) : rest(tiles, n); });
+    if (e != hipSuccess) return *launched ? fail_midway(ctx, e, what) : fail_hip(ctx, e, what);
+    ++*launched;
+  }
+  return SLOWMO_OK;
+}
+
 const char *kBrokenMsg =
     "an earlier multi-kernel call failed halfway; the context's state is undefined: destroy it";
 
@@ -321,7 +352,8 @@ size_t slowmo_state_bytes(const slowmo_config *cfg, int32_t n_tensors, const int
   Layout L = make_layout(n_tensors, numel);
   return make_sections(*cfg, n_tensors, L,
                        static_cast<size_t>(count_local_tiles(cfg->m, n_tensors, numel)),
-                       static_cast<size_t>(count_outer_tiles(n_tensors, numel)))
+                       static_cast<size_t>(count_outer_tiles(n_tensors, numel)),
+                       static_cast<size_t>(count_big_tiles(n_tensors, numel)))
       .total;
 }
 
@@ -426,12 +458,18 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.fuse_last = env_flag("SLOWMO_FUSE_LAST", 1) ? 1 : 0;
   ctx->tune.fuse_mix = env_flag("SLOWMO_FUSE_MIX", 1) ? 1 : 0;
   ctx->tune.outer_lds = std::min(std::max(env_flag("SLOWMO_OUTER_LDS", 0), 0), 64 * 1024);
+  // big tiles: -1 = by the worker count (see kBigFusedFromWorkers), 0 = never, 1 = always
+  const int32_t big = env_flag("SLOWMO_BIG_TILES", -1);
+  ctx->tune.big_tiles =
+      ((big < 0 ? m >= kBigFusedFromWorkers : big != 0) && ctx->tune.nontemporal) ? 1 : 0;
+  ctx->big_outer = ctx->tune.big_tiles && (big > 0 || m >= kBigOuterFromWorkers);
   ctx->fail_launch_at = env_flag("SLOWMO_TEST_FAIL_LAUNCH", 0);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
   const int64_t n_otiles = count_outer_tiles(n_tensors, numel);
   const Sections sec = make_sections(*cfg, n_tensors, ctx->layout, static_cast<size_t>(n_ltiles),
-                                     static_cast<size_t>(n_otiles));
+                                     static_cast<size_t>(n_otiles),
+                                     static_cast<size_t>(count_big_tiles(n_tensors, numel)));
   if (state_bytes < sec.total) {
     delete ctx;
     return fail(nullptr, SLOWMO_ERR_NOMEM, "state workspace is smaller than slowmo_state_bytes()");
@@ -477,6 +515,8 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->d_otiles = reinterpret_cast<TileRef *>(base + sec.otiles);
   ctx->n_ltiles = static_cast<int32_t>(n_ltiles);
   ctx->n_otiles = static_cast<int32_t>(n_otiles);
+  ctx->d_btiles = reinterpret_cast<TileRef *>(base + sec.btiles);
+  ctx->d_rtiles = reinterpret_cast<TileRef *>(base + sec.rtiles);
 
 #define CREATE_HIP(call, what)              \
   do {                                      \
@@ -533,6 +573,30 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
     CREATE_HIP(hipMemcpyAsync(ctx->d_otiles, ot.data(), ot.size() * sizeof(TileRef),
                               hipMemcpyHostToDevice, stream),
                "upload of the outer-step tiles");
+  std::vector<TileRef> bt, rt;
+  if (ctx->tune.big_tiles) {
+    constexpr int64_t per_big = kBigTile / kOuterTile;
+    for (int32_t j = 0; j < n_tensors; ++j) {
+      const int64_t n_big = tinfo[j].unaligned ? 0 : numel[j] / kBigTile;
+      for (int64_t k = 0; k < n_big; ++k) bt.push_back({j, static_cast<int32_t>(k)});
+      for (int64_t k = n_big * per_big; k * kOuterTile < numel[j]; ++k)
+        rt.push_back({j, static_cast<int32_t>(k)});
+    }
+  }
+  if (bt.empty()) {
+    ctx->d_rtiles = ctx->d_otiles;
+    ctx->n_rtiles = ctx->n_otiles;
+  } else {
+    CREATE_HIP(hipMemcpyAsync(ctx->d_btiles, bt.data(), bt.size() * sizeof(TileRef),
+                              hipMemcpyHostToDevice, stream),
+               "upload of the big tiles");
+    if (!rt.empty())
+      CREATE_HIP(hipMemcpyAsync(ctx->d_rtiles, rt.data(), rt.size() * sizeof(TileRef),
+                                hipMemcpyHostToDevice, stream),
+                 "upload of the tiles the big ones leave over");
+    ctx->n_btiles = static_cast<int32_t>(bt.size());
+    ctx->n_rtiles = static_cast<int32_t>(rt.size());
+  }
   CREATE_HIP(hipMemcpyAsync(ctx->d_tensors, tinfo.data(), tinfo.size() * sizeof(TensorInfo),
                             hipMemcpyHostToDevice, stream),
              "upload of the tensor table");
@@ -700,9 +764,10 @@ OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
   return a;
 }
 
-hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
+// Lines 6-8 and the copy into the replicas.  *launched: kernels of the same
+// call already issued (a failure is then a failure halfway).
+slowmo_status run_outer(slowmo_ctx *ctx, float lr, int *launched, hipStream_t stream) {
   const slowmo_config &c = ctx->cfg;
-  if (ctx->fail_launch_at > 0 && ++ctx->launches == ctx->fail_launch_at) return hipErrorLaunchFailure;
   if (c.no_average) {  // Section 6: lines 7-8 per worker, no line 6
     OuterNoAvgArgs na{};
     na.tiles = ctx->d_ltiles;
@@ -713,9 +778,26 @@ hipError_t launch_outer_any(slowmo_ctx *ctx, float lr, hipStream_t stream) {
     na.lr = lr;
     na.alpha = c.alpha;
     na.beta = c.beta;
-    return launch_outer_noavg_step(na, ctx->tune, stream);
+    const hipError_t e =
+        guarded(ctx, [&] { return launch_outer_noavg_step(na, ctx->tune, stream); });
+    if (e != hipSuccess)
+      return *launched ? fail_midway(ctx, e, "outer-step kernel launch")
+                       : fail_hip(ctx, e, "outer-step kernel launch");
+    ++*launched;
+    return SLOWMO_OK;
   }
-  return launch_outer_step(outer_args(ctx, lr), ctx->tune, stream);
+  OuterArgs a = outer_args(ctx, lr);
+  auto with = [&](const TileRef *tiles, int32_t n) {
+    a.tiles = tiles;
+    a.ntiles = n;
+    return a;
+  };
+  // the big-tile kernel has no buffer average
+  const bool use_big = ctx->n_btiles > 0 && ctx->big_outer && !a.avg_h;
+  return run_tiled(
+      ctx, use_big, launched, "outer-step kernel launch",
+      [&](const TileRef *t, int32_t n) { return launch_outer_big(with(t, n), ctx->tune, stream); },
+      [&](const TileRef *t, int32_t n) { return launch_outer_step(with(t, n), ctx->tune, stream); });
 }
 
 }  // namespace
@@ -726,8 +808,9 @@ slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (!finite_pos(lr)) return fail(ctx, SLOWMO_ERR_ARG, "lr must be finite and > 0");
   if (ctx->k != ctx->cfg.tau)
     return fail(ctx, SLOWMO_ERR_STATE, "the outer step needs exactly tau local steps before it");
-  hipError_t e = launch_outer_any(ctx, lr, static_cast<hipStream_t>(stream_));
-  if (e != hipSuccess) return fail_hip(ctx, e, "outer-step kernel launch");
+  int launched = 0;
+  const slowmo_status st = run_outer(ctx, lr, &launched, static_cast<hipStream_t>(stream_));
+  if (st != SLOWMO_OK) return st;
   finish_outer(ctx);
   return SLOWMO_OK;
 }
@@ -755,14 +838,30 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
                                ctx->tune, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, e, "local-step kernel launch");
-    e = launch_outer_any(ctx, outer_lr, stream);
-    if (e != hipSuccess) return fail_midway(ctx, e, "outer-step kernel launch");
+    int launched = 1;
+    st = run_outer(ctx, outer_lr, &launched, stream);
+    if (st != SLOWMO_OK) return st;
   } else {
-    hipError_t e = guarded(ctx, [&] {
-      return launch_local_outer_step(a, outer_args(ctx, outer_lr), ctx->n_tensors, c.base, bf16,
-                                     ctx->buffers_zero, c.policy, ctx->tune, stream);
-    });
-    if (e != hipSuccess) return fail_hip(ctx, e, "fused local+outer kernel launch");
+    OuterArgs o = outer_args(ctx, outer_lr);
+    auto with = [&](const TileRef *tiles, int32_t n) {
+      o.tiles = tiles;
+      o.ntiles = n;
+      return o;
+    };
+    int launched = 0;
+    // the big-tile kernel stores the buffers or drops them; it does not average them
+    const bool use_big = ctx->n_btiles > 0 && c.policy != SLOWMO_BUF_AVERAGE;
+    st = run_tiled(
+        ctx, use_big, &launched, "fused local+outer kernel launch",
+        [&](const TileRef *t, int32_t n) {
+          return launch_local_outer_big(a, with(t, n), ctx->n_tensors, c.base, bf16,
+                                        ctx->buffers_zero, c.policy, ctx->tune, stream);
+        },
+        [&](const TileRef *t, int32_t n) {
+          return launch_local_outer_step(a, with(t, n), ctx->n_tensors, c.base, bf16,
+                                         ctx->buffers_zero, c.policy, ctx->tune, stream);
+        });
+    if (st != SLOWMO_OK) return st;
   }
   finish_local(ctx);
   finish_outer(ctx);

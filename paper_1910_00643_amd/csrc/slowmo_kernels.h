@@ -80,6 +80,7 @@ struct LaunchTuning {
   int32_t nontemporal;  // 1: streaming (non-temporal) loads and stores
   int32_t fuse_last;    // 1: slowmo_local_outer_step runs one fused kernel when it can
   int32_t fuse_mix;     // 1: slowmo_local_mix_step runs one fused kernel when it can
+  int32_t big_tiles;    // 1: whole kBigTile pieces of aligned tensors go to the big-tile kernels
   int32_t outer_lds;    // bytes of (unused) dynamic LDS per outer-step workgroup: caps the
                         // number of resident wavefronts per CU (160 KiB / outer_lds); 0 = no cap
 };
@@ -98,6 +99,14 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &tune, hipSt
 hipError_t launch_local_outer_step(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
                                    int base, bool bf16, bool first, int policy,
                                    const LaunchTuning &tune, hipStream_t stream);
+// The same two operations on BIG tiles (a.tiles / o.tiles list whole kBigTile
+// pieces, every one full and 16-byte aligned in every stream).  Results are
+// bit-identical to the ordinary tiles'.  launch_outer_big handles no buffer
+// average (a.avg_h must be NULL); launch_local_outer_big handles policies 0 and 1.
+hipError_t launch_outer_big(const OuterArgs &a, const LaunchTuning &tune, hipStream_t stream);
+hipError_t launch_local_outer_big(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                  int base, bool bf16, bool first, int policy,
+                                  const LaunchTuning &tune, hipStream_t stream);
 // Copies worker 0's replica into x0 (x0_copies copies, d_pad apart) and into the
 // replicas of workers 1..m-1; uses a.tiles, a.tensors, a.xtab_t, a.x0, a.d_pad, a.m.
 hipError_t launch_init_broadcast(const OuterArgs &a, int32_t x0_copies, const LaunchTuning &tune,

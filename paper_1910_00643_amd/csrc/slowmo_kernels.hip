@@ -3,6 +3,7 @@
 // k_local_step         Algorithm 1 lines 3-5 for all workers (Table C.1 rows SGD, Adam)
 // k_outer_step         lines 6-8 + copy into every replica (+ "average" buffer strategy)
 // k_local_outer_step   the last local step of an outer iteration fused with the outer step
+// k_outer_big, k_local_outer_big   the same two on 65 536-element pieces (many workers)
 // k_init_broadcast     Algorithm 1 "Input": x_{0,0} into x0 and every replica
 // k_outer_noavg        lines 7-8 per worker, without line 6 (Section 6)
 // k_mix_step        mixing step of stochastic gradient push (Algorithm C.1)
@@ -593,6 +594,160 @@ __global__ __launch_bounds__(kOuterBlock) void k_local_outer_step(
   }
 }
 
+// ---- big tiles: the two kernels above on whole 65 536-element pieces ---------------
+// One 1024-thread workgroup = kBigTile elements of one tensor, all workers;
+// lane t owns the vectors [v * 4096 + 4t, + 4), v = 0..15, of every stream.  All
+// 16 waves of the workgroup read 256 KiB of replica 0, then of replica 1, ...:
+// measured, a memory region that is visited in pieces of this size serves the
+// many-stream walk about 10 % faster than 1 KiB pieces from unrelated waves
+// (m = 32).  The pieces are full and 16-byte aligned in every stream, so there
+// is no element-wise path.  Same arithmetic, same order of the sum, same
+// results as the ordinary tiles.  Streams are addressed as a uniform base (the
+// piece of vector v) plus the lane's offset, which keeps the addresses in
+// scalar registers: the 128 vector registers a 1024-thread workgroup can have
+// per lane hold the 16 accumulators and the operands of a few vectors.
+constexpr int kBigStride = 4 * kBigBlock;  // floats between a lane's consecutive vectors
+
+__global__ __launch_bounds__(kBigBlock) void k_outer_big(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, float *__restrict__ x0base, float *__restrict__ ubase,
+    int ntiles, int chunk, int remap, int m, OuterP p0) {
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
+  const int64_t eo = static_cast<int64_t>(t.k) * kBigTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
+  const int lane = 4 * static_cast<int>(threadIdx.x);
+  constexpr int HALF = kBigVpt / 2;
+  V4 acc[kBigVpt];
+  for (int i = 0; i < m; ++i) {       // line 6: ordered sum, i = 0, 1, ..., m-1
+    const float *x = xp[i] + eo;
+#pragma unroll
+    for (int v0 = 0; v0 < kBigVpt; v0 += HALF) {
+      V4 xv[HALF];
+#pragma unroll
+      for (int v = 0; v < HALF; ++v) xv[v] = ld4<true>(x + (v0 + v) * kBigStride + lane);
+#pragma unroll
+      for (int v = 0; v < HALF; ++v) acc[v0 + v] = (i == 0) ? xv[v] : acc[v0 + v] + xv[v];
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < kBigVpt; ++v) {
+    const V4 x0v = ld4<true>(x0 + v * kBigStride + lane);
+    V4 uv = ld4<true>(u + v * kBigStride + lane), xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<true>(u + v * kBigStride + lane, uv);
+    st4<true>(x0 + v * kBigStride + lane, xn);
+    acc[v] = xn;
+  }
+  for (int i = 0; i < m; ++i) {
+    float *x = xp[i] + eo;
+#pragma unroll
+    for (int v = 0; v < kBigVpt; ++v) st4<true>(x + v * kBigStride + lane, acc[v]);
+  }
+}
+
+// POLICY 0 (reset: the buffers of this step are not stored) or 1 (maintain).
+// A worker's step runs over SUB vectors at a time: their operands are loaded,
+// stepped, added to the sum and dropped before the next SUB are loaded.
+template <int BASE, bool BF16, bool FIRST, int POLICY>
+__global__ __launch_bounds__(kBigBlock) void k_local_outer_big(
+    const TileRef *__restrict__ tiles, const TensorInfo *__restrict__ tensors,
+    float *const *__restrict__ xtab_t, const void *const *__restrict__ gtab,
+    float *__restrict__ x0base, float *__restrict__ ubase, float *__restrict__ hbase,
+    float *__restrict__ vbase, int64_t d_pad, int n_tensors, int ntiles, int chunk, int remap,
+    int m, SgdP sp, AdamP ap, OuterP p0) {
+  static_assert(POLICY == 0 || POLICY == 1, "no buffer average on big tiles");
+  const int tile = tile_of(blockIdx.x, chunk, remap);
+  if (tile >= ntiles) return;
+  const TileRef t = tiles[tile];
+  const TensorInfo ti = tensors[t.owner];
+  const OuterP p = for_tensor(p0, ti.lr_scale);
+  sp.lr = sp.lr * ti.lr_scale;
+  sp.wd = ti.wd;
+  ap.lr = ap.lr * ti.lr_scale;
+  ap.wd = ti.wd;
+  const int64_t eo = static_cast<int64_t>(t.k) * kBigTile;
+  float *const *__restrict__ xp = xtab_t + static_cast<int64_t>(t.owner) * m;
+  const void *const *__restrict__ gp = gtab + t.owner;       // worker i: gp[i * n_tensors]
+  float *x0 = x0base + ti.fo + eo;
+  float *u = ubase + ti.fo + eo;
+  float *h0 = hbase + ti.fo + eo;                              // worker i: h0 + i * d_pad
+  float *v0 = BASE == 1 ? vbase + ti.fo + eo : nullptr;
+  constexpr int gsize = BF16 ? 2 : 4;
+  constexpr int SUB = 2;
+  const int lane = 4 * static_cast<int>(threadIdx.x);
+  V4 acc[kBigVpt];
+  for (int i = 0; i < m; ++i) {
+    const float *xi = xp[i] + eo;
+    float *hi = h0 + i * d_pad;
+    float *vi = BASE == 1 ? v0 + i * d_pad : nullptr;
+    const char *gi = static_cast<const char *>(gp[static_cast<int64_t>(i) * n_tensors]) + eo * gsize;
+#pragma unroll
+    for (int s0 = 0; s0 < kBigVpt; s0 += SUB) {
+      V4 xv[SUB], hv[SUB], vv[SUB], gv[SUB];
+#pragma unroll
+      for (int v = 0; v < SUB; ++v) {
+        const int off = (s0 + v) * kBigStride;
+        xv[v] = ld4<true>(xi + off + lane);
+        if constexpr (!FIRST) hv[v] = ld4<true>(hi + off + lane);
+        if constexpr (!FIRST && BASE == 1) vv[v] = ld4<true>(vi + off + lane);
+        gv[v] = ldg4<BF16, true>(gi + static_cast<int64_t>(off) * gsize, threadIdx.x);
+      }
+#pragma unroll
+      for (int v = 0; v < SUB; ++v) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float xe = xv[v][c], he = FIRST ? 0.f : hv[v][c];
+          if constexpr (BASE == 0) {
+            sgd_elem<FIRST>(xe, he, gv[v][c], sp);
+          } else {
+            float ve = FIRST ? 0.f : vv[v][c];
+            adam_elem<FIRST>(xe, he, ve, gv[v][c], ap);
+            vv[v][c] = ve;
+          }
+          xv[v][c] = xe;
+          hv[v][c] = he;
+        }
+        if constexpr (POLICY == 1) {
+          const int off = (s0 + v) * kBigStride;
+          st4<true>(hi + off + lane, hv[v]);
+          if constexpr (BASE == 1) st4<true>(vi + off + lane, vv[v]);
+        }
+        acc[s0 + v] = (i == 0) ? xv[v] : acc[s0 + v] + xv[v];
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < kBigVpt; ++v) {
+    const V4 x0v = ld4<true>(x0 + v * kBigStride + lane);
+    V4 uv = ld4<true>(u + v * kBigStride + lane), xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float ue = uv[c];
+      xn[c] = outer_elem(acc[v][c], x0v[c], ue, p);
+      uv[c] = ue;
+    }
+    st4<true>(u + v * kBigStride + lane, uv);
+    st4<true>(x0 + v * kBigStride + lane, xn);
+    acc[v] = xn;
+  }
+  for (int i = 0; i < m; ++i) {
+    float *x = xp[i] + eo;
+#pragma unroll
+    for (int v = 0; v < kBigVpt; ++v) st4<true>(x + v * kBigStride + lane, acc[v]);
+  }
+}
+
 // ---- mixing step of stochastic gradient push (Algorithm C.1) ---------------------
 // x^{(i)} <- p(i,i) x^{(i)} + p(i,j) x^{(j)}, j = in_peer(i), in place; one
 // workgroup = 256 elements of one tensor, all workers.  See MixEntry.  Every entry overwrites one worker
@@ -1021,6 +1176,59 @@ hipError_t launch_outer_step(const OuterArgs &a, const LaunchTuning &t, hipStrea
   }
   return avg == 0 ? launch_outer_t<false, 0>(a, t, s)
                   : avg == 1 ? launch_outer_t<false, 1>(a, t, s) : launch_outer_t<false, 2>(a, t, s);
+}
+
+hipError_t launch_outer_big(const OuterArgs &a, const LaunchTuning &t, hipStream_t s) {
+  if (a.ntiles <= 0) return hipSuccess;
+  if (a.avg_h || a.avg_v || !t.nontemporal) return hipErrorInvalidValue;
+  const Grid g = make_grid(a.ntiles, t);
+  const OuterP p{a.lr, 0.f, a.beta, a.m_f, a.alpha};
+  hipLaunchKernelGGL(k_outer_big, dim3(g.blocks), dim3(kBigBlock), 0, s, a.tiles, a.tensors,
+                     a.xtab_t, a.x0, a.u, a.ntiles, g.chunk, g.run, a.m, p);
+  return hipGetLastError();
+}
+
+namespace {
+
+template <int BASE, bool BF16, bool FIRST>
+hipError_t launch_fused_big_t(const LocalArgs &l, const OuterArgs &o, int n_tensors, int policy,
+                              const LaunchTuning &t, hipStream_t s) {
+  const Grid g = make_grid(o.ntiles, t);
+  const SgdP sp{l.lr, l.mu, l.wd};
+  const AdamP ap{l.lr, l.wd, l.b1, l.b2, l.omb1, l.omb2, l.rc1, l.rc2, l.eps};
+  const OuterP p{o.lr, 0.f, o.beta, o.m_f, o.alpha};
+  if (policy == 0) {
+    hipLaunchKernelGGL((k_local_outer_big<BASE, BF16, FIRST, 0>), dim3(g.blocks), dim3(kBigBlock),
+                       0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h, l.v, o.d_pad,
+                       n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
+  } else {
+    hipLaunchKernelGGL((k_local_outer_big<BASE, BF16, FIRST, 1>), dim3(g.blocks), dim3(kBigBlock),
+                       0, s, o.tiles, o.tensors, o.xtab_t, l.gtab, o.x0, o.u, l.h, l.v, o.d_pad,
+                       n_tensors, o.ntiles, g.chunk, g.run, o.m, sp, ap, p);
+  }
+  return hipGetLastError();
+}
+
+template <int BASE, bool BF16>
+hipError_t launch_fused_big_f(const LocalArgs &l, const OuterArgs &o, int n_tensors, bool first,
+                              int policy, const LaunchTuning &t, hipStream_t s) {
+  return first ? launch_fused_big_t<BASE, BF16, true>(l, o, n_tensors, policy, t, s)
+               : launch_fused_big_t<BASE, BF16, false>(l, o, n_tensors, policy, t, s);
+}
+
+}  // namespace
+
+hipError_t launch_local_outer_big(const LocalArgs &l, const OuterArgs &o, int32_t n_tensors,
+                                  int base, bool bf16, bool first, int policy,
+                                  const LaunchTuning &t, hipStream_t s) {
+  if (o.ntiles <= 0) return hipSuccess;
+  if ((policy != 0 && policy != 1) || !t.nontemporal) return hipErrorInvalidValue;
+  if (base == 0) {
+    return bf16 ? launch_fused_big_f<0, true>(l, o, n_tensors, first, policy, t, s)
+                : launch_fused_big_f<0, false>(l, o, n_tensors, first, policy, t, s);
+  }
+  return bf16 ? launch_fused_big_f<1, true>(l, o, n_tensors, first, policy, t, s)
+              : launch_fused_big_f<1, false>(l, o, n_tensors, first, policy, t, s);
 }
 
 namespace {

@@ -31,6 +31,12 @@ int64_t count_outer_tiles(int32_t n_tensors, const int64_t *numel) {
   return t;
 }
 
+int64_t count_big_tiles(int32_t n_tensors, const int64_t *numel) {
+  int64_t t = 0;
+  for (int32_t j = 0; j < n_tensors; ++j) t += numel[j] / kBigTile;
+  return t;
+}
+
 static void cut(int32_t worker, int32_t n_tensors, const int64_t *numel, int64_t tile,
                 std::vector<PlanRun> &runs) {
   for (int32_t j = 0; j < n_tensors; ++j) {

@@ -31,6 +31,22 @@ constexpr int32_t kLocalTile = 4 * kLocalBlock;
 constexpr int32_t kOuterBlock = SLOWMO_OUTER_BLOCK;
 constexpr int32_t kOuterTile = 4 * kOuterBlock;
 
+// Big tiles of the outer step and of the fused last step: one 1024-thread
+// workgroup takes kBigVpt vectors per lane, i.e. 256 KiB of every stream it
+// walks (its 16 waves start together and move from replica to replica
+// together).  Measured in one process on the same replicas against the
+// single-wave tiles: the fused last step is 10-14 % faster at m = 32, 6-7 % at
+// m = 16, 3-5 % at m = 8 and no faster at m = 4; the plain outer step 8 % faster
+// at m = 32 and within +-4 % at m = 8.  Smaller shapes (128 or 64 KiB per stream
+// and workgroup) gain half of that or nothing.  Used for the whole kBigTile
+// pieces of aligned tensors from these worker counts on:
+constexpr int32_t kBigBlock = 1024;
+constexpr int32_t kBigVpt = 16;
+constexpr int32_t kBigTile = 4 * kBigBlock * kBigVpt;
+constexpr int32_t kBigFusedFromWorkers = 8;
+constexpr int32_t kBigOuterFromWorkers = 16;
+static_assert(kBigTile % kOuterTile == 0, "a big tile is a whole number of ordinary tiles");
+
 // One tile of either kernel: the k-th piece of a tensor.  For the local step
 // `owner` is the slot (worker * n_tensors + tensor); for the outer step it is
 // the tensor.  8 bytes, read with one scalar load.
@@ -122,6 +138,8 @@ Layout make_layout(int32_t n_tensors, const int64_t *numel);
 // Number of tiles of each kind (no allocation).
 int64_t count_local_tiles(int32_t m, int32_t n_tensors, const int64_t *numel);
 int64_t count_outer_tiles(int32_t n_tensors, const int64_t *numel);
+// Whole kBigTile pieces over all tensors (an upper bound on the big tiles in use).
+int64_t count_big_tiles(int32_t n_tensors, const int64_t *numel);
 
 // Tiles in launch order: worker-major, tensors in list order, offsets ascending.
 void plan_local(int32_t m, int32_t n_tensors, const int64_t *numel, std::vector<PlanRun> &runs);

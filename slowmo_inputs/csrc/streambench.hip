@@ -56,8 +56,16 @@ __global__ __launch_bounds__(B) void k_streams(float *base, Shape sh) {
   for (int it = 0; it < sh.iters; ++it) {
     const int64_t L = b * sh.iters + it;
     if (L >= sh.total) return;
-    const int64_t u = sh.order ? L % sh.units : L / sh.tiles_per_unit;
-    const int64_t k = sh.order ? L / sh.units : L % sh.tiles_per_unit;
+    // one 64-bit division, not four: it is expanded inline and a wave that
+    // moves a few KiB feels the length of what runs before its first load
+    int64_t u, k;
+    if (sh.order) {
+      k = L / sh.units;
+      u = L - k * sh.units;
+    } else {
+      u = L / sh.tiles_per_unit;
+      k = L - u * sh.tiles_per_unit;
+    }
     float *p = base + u * sh.S * sh.stride + (k * (B * VPT) + threadIdx.x) * 4;
     V4 acc[VPT];
 #pragma unroll

@@ -13,12 +13,11 @@ HBM_PEAK_GBPS = 8000.0
 
 def cases(m: int, n: int):
     """(label, kwargs of device.streambench, HBM bytes per launch)."""
-    f = 4 * n
     out = []
 
     def add(label, units, S, R, W, in_place=True, **kw):
         out.append((label, dict(units=units, S=S, R=R, W=W, in_place=in_place, **kw),
-                    units * (R + W) * f))
+                    units * (R + W) * 4 * kw.get("n", n)))
 
     # ceilings.  A workgroup that moves 1 KiB is bound by the rate at which
     # workgroups are dispatched, so the plain streams also run with 16 KiB each.
@@ -29,6 +28,16 @@ def cases(m: int, n: int):
     add("write, 256 threads x 4 vec4/lane, plain stores", m, 1, 0, 1, B=256, VPT=4, nt=0)
     add("copy (1 read, 1 write), 1 KiB per stream and workgroup", m, 2, 1, 1, in_place=False)
     add("copy, 256 threads x 4 vec4/lane", m, 2, 1, 1, in_place=False, B=256, VPT=4)
+    # read : write mixes, one 1 KiB vector load or store per stream and wave
+    add("2r/1w  in place", m, 2, 2, 1)
+    add("3r/1w  in place", m, 3, 3, 1)
+    add("1r/2w  out of place", m, 3, 1, 2, in_place=False)
+    add("2r/2w  in place (first local step under \"reset\": x, g read; x, h written)", m, 2, 2, 2)
+    add("3r/3w  in place", m, 3, 3, 3)
+    add("4r/2w  in place", m, 4, 4, 2)
+    add("4r/3w  in place (Adam: x, h, v, g read; x, h, v written)", m, 4, 4, 3)
+    add("2 streams written per wave (nothing read)", m, 2, 0, 2)
+    add("3 streams read per wave (nothing written)", m, 3, 3, 0)
     # the SGD local step's mix: x, h, g read; x, h written
     add("3r/2w  64 threads, 1 vec4/lane, retire, NT, XCD-contiguous  [library shape]", m, 3, 3, 2)
     add("3r/2w  same, plain loads and stores", m, 3, 3, 2, nt=0)
@@ -54,6 +63,12 @@ def cases(m: int, n: int):
     add(f"{m + 2} streams in place, 64 threads, 1 vec4/lane, no XCD remap", 1, m + 2, m + 2, m + 2,
         remap=False)
     add(f"{m + 2} streams in place, 64 threads, NT loads, plain stores", 1, m + 2, m + 2, m + 2, nt=1)
+    # the same bytes with the m+2 streams cut into pieces that lie side by side
+    # (what a caller could give only by interleaving the replicas)
+    for piece in (65536, 16384, 4096, 256):
+        if n % piece == 0:
+            add(f"{m + 2} streams in place, streams cut into pieces of {piece * 4 // 1024} KiB laid "
+                f"side by side", n // piece, m + 2, m + 2, m + 2, n=piece, stride=piece)
     add(f"{m} streams read per workgroup (nothing written)", 1, m, m, 0)
     add(f"{m} streams read, 1024 threads x 16 vec4/lane", 1, m, m, 0, B=1024, VPT=16)
     add(f"{m} streams written per workgroup (nothing read)", 1, m, 0, m)
@@ -79,16 +94,19 @@ def run(m: int = 32, n: int = 25_559_040, reps: int = 5, device: str = "cuda:0")
     assert n % 65536 == 0
     stride = n + 65536                         # streams start 256 KiB after the previous one ends
     all_cases = cases(m, n)
-    most = max(kw["units"] * kw["S"] for _, kw, _ in all_cases)
-    buf = torch.zeros(most * stride, dtype=torch.float32, device=device)
+    most = max(kw["units"] * kw["S"] * kw.get("stride", stride) for _, kw, _ in all_cases)
+    buf = torch.zeros(most, dtype=torch.float32, device=device)
     rows = []
     for label, kw, nbytes in all_cases:
-        D.streambench(buf, stride, n=n, **kw)
+        kw = dict(kw)
+        args = (buf, kw.pop("stride", stride))
+        kw.setdefault("n", n)
+        D.streambench(*args, **kw)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(reps):
-            D.streambench(buf, stride, n=n, **kw)
+            D.streambench(*args, **kw)
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / reps

@@ -74,12 +74,13 @@ def family(kernel):
     name = kernel.partition("<")[0]
     a = _targs(kernel)
     fam = {"k_local_step": "local", "k_local_outer_step": "local_outer", "k_outer_step": "outer",
+           "k_local_outer_big": "local_outer", "k_outer_big": "outer",
            "k_mix_step": "mix", "k_local_mix_step": "local_mix", "k_outer_noavg": "outer_noavg",
            "k_debias": "debias", "k_calib_copy": "copy"}.get(name)
     steady = True
     if name == "k_local_step":
         steady = a[2] == "false" and a[3] == "false"
-    elif name in ("k_local_mix_step", "k_local_outer_step"):
+    elif name in ("k_local_mix_step", "k_local_outer_step", "k_local_outer_big"):
         steady = a[2] == "false"
     return fam, steady
 
@@ -113,14 +114,20 @@ def algorithmic_bytes(kernel, w, rounds, dispatches):
     if name == "k_mix_step":
         calls = rounds * w.tau
         return 4 * md * calls, 4 * md * calls, calls
-    if name == "k_local_outer_step":
+    # the outer step and the fused last step run as two kernels when big tiles
+    # are in use: the whole 65 536-element pieces, and the rest
+    if name in ("k_local_outer_step", "k_local_outer_big"):
         first = a[2] == "true"
         r = w.m * (4 + (0 if first else 4 * nbuf) + g) + 8
         wr = 4 * w.m + 8 + (0 if reset else 4 * nbuf * w.m)
-        return r * d * calls, wr * d * calls, calls
-    if name == "k_outer_step":
+        big = bench.big_elements(w, True)
+        n = big if name == "k_local_outer_big" else d - big
+        return r * n * calls, wr * n * calls, calls
+    if name in ("k_outer_step", "k_outer_big"):
         b = bench.outer_bytes_per_element(w)
-        return b // 2 * d * calls, b // 2 * d * calls, calls
+        big = bench.big_elements(w, False)
+        n = big if name == "k_outer_big" else d - big
+        return b // 2 * n * calls, b // 2 * n * calls, calls
     if name == "k_outer_noavg":
         return 12 * md * calls, 12 * md * calls, calls
     if name == "k_debias":

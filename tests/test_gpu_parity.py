@@ -393,6 +393,53 @@ def test_fused_last_local_and_outer_step(base, grad_dtype, policy, tau, layouts)
             assert np.array_equal(res[0]["v"], res[1]["v"])
 
 
+def _with_env(name, value, make):
+    """make() with the environment variable set (the library reads its knobs at
+    slowmo_create)."""
+    import os
+    old = os.environ.get(name)
+    os.environ[name] = value
+    try:
+        return make()
+    finally:
+        if old is None:
+            os.environ.pop(name, None)
+        else:
+            os.environ[name] = old
+
+
+@pytest.mark.parametrize("base,grad_dtype,policy,m,layouts", [
+    ("sgd_nesterov", "f32", "reset", 3, ("separate", "padded")),
+    ("sgd_nesterov", "bf16", "maintain", 3, ("separate", "separate")),
+    ("sgd_nesterov", "f32", "average", 3, ("separate", "padded")),     # buffers averaged: ordinary tiles
+    ("adam", "bf16", "maintain", 3, ("separate", "padded")),
+    ("adam", "f32", "reset", 3, ("separate", "separate")),
+    ("sgd_nesterov", "f32", "reset", 3, ("flat", "padded")),           # unaligned replicas: no big tile
+    ("sgd_nesterov", "f32", "reset", 17, ("separate", "separate")),    # big tiles on by themselves
+])
+@pytest.mark.parametrize("fused", [False, True])
+def test_big_tiles_equal_the_ordinary_tiles_bitwise(base, grad_dtype, policy, m, layouts, fused):
+    """The outer step and the fused last step on 65 536-element pieces (one
+    1024-thread workgroup each; the tensors of 70 001 and 131 077 elements have
+    one and two of them, plus a rest) against the same run on ordinary tiles,
+    bit for bit, and against the oracle."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy=policy, m=m),
+                            tau=3, rounds=3,
+                            tensor_wd=tuple(1e-4 * (j % 3) for j in range(26)),
+                            tensor_lr_scale=tuple((1.0, 0.5, 2.0)[j % 3] for j in range(26)))
+    idx = np.arange(w.d, dtype=np.int64)
+    res = []
+    for big in ("0", "1") if m < 16 else ("0", "-1"):
+        prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
+        opt = _with_env("SLOWMO_BIG_TILES", big, lambda: PU.make_gpu(w, prob))
+        PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
+                       fused_last=fused)
+        res.append(PU.gpu_state(w, prob, opt, idx))
+        opt.close()
+    for key in ("x", "x0", "u", "h") + (("v",) if base == "adam" else ()):
+        assert np.array_equal(res[0][key], res[1][key]), key
+
+
 @pytest.mark.parametrize("m", [1, 2, 7, 33, 300])
 def test_worker_counts(m):
     """m = 1 (Lookahead-like), odd m (true division by m), m above the
