@@ -635,6 +635,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   return SLOWMO_OK;
 }
 
+extern "C++" {
 namespace {
 
 // Checks the arguments of a local step, uploads the gradient-pointer table if
@@ -718,6 +719,7 @@ void finish_outer(slowmo_ctx *ctx) {
 }
 
 }  // namespace
+}  // extern "C++"
 
 slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float lr,
                                 void *stream_) {
@@ -740,6 +742,7 @@ slowmo_status slowmo_local_step(slowmo_ctx *ctx, const void *const *grads, float
   return SLOWMO_OK;
 }
 
+extern "C++" {
 namespace {
 
 OuterArgs outer_args(const slowmo_ctx *ctx, float lr) {
@@ -801,6 +804,7 @@ slowmo_status run_outer(slowmo_ctx *ctx, float lr, int *launched, hipStream_t st
 }
 
 }  // namespace
+}  // extern "C++"
 
 slowmo_status slowmo_outer_step(slowmo_ctx *ctx, float lr, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
@@ -881,6 +885,7 @@ slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer
   return SLOWMO_OK;
 }
 
+extern "C++" {
 namespace {
 
 // Ranges [first, last) of the mixing entries to run as separate launches: one
@@ -971,6 +976,7 @@ void mix_weights(slowmo_ctx *ctx, const int32_t *in_peer) {
 }
 
 }  // namespace
+}  // extern "C++"
 
 slowmo_status slowmo_mix_step(slowmo_ctx *ctx, const int32_t *in_peer, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
@@ -1064,6 +1070,7 @@ slowmo_status slowmo_get_pushsum_weights(const slowmo_ctx *ctx, float *w) {
   return SLOWMO_OK;
 }
 
+extern "C++" {
 namespace {
 
 // z = x / w for every worker.  The table the kernel reads (m * n_tensors
@@ -1111,6 +1118,7 @@ slowmo_status debias_into(slowmo_ctx *ctx, float *const *z, void *table_dev, hip
 }
 
 }  // namespace
+}  // extern "C++"
 
 slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream_) {
   if (!ctx) return fail(nullptr, SLOWMO_ERR_ARG, "ctx is NULL");
@@ -1169,6 +1177,7 @@ slowmo_status slowmo_set_tensor_hparams(slowmo_ctx *ctx, const float *weight_dec
   return SLOWMO_OK;
 }
 
+extern "C++" {
 namespace {
 
 // Header of an exported state blob (256 bytes), followed by the m push-sum
@@ -1199,6 +1208,7 @@ BlobParts blob_parts(const slowmo_ctx *ctx) {
 }
 
 }  // namespace
+}  // extern "C++"
 
 size_t slowmo_export_bytes(const slowmo_ctx *ctx) { return ctx ? blob_parts(ctx).total : 0; }
 
