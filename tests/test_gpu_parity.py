@@ -452,6 +452,23 @@ def test_worker_counts(m):
     opt.close()
 
 
+@pytest.mark.parametrize("m,fused", [(8, True), (9, True), (16, False), (33, True), (33, False),
+                                     (150, True)])
+def test_worker_counts_on_big_tiles(m, fused):
+    """Tensors of exactly one big tile (no rest), one big tile and five
+    elements, two big tiles, and one too small for any, at worker counts on both
+    sides of the thresholds from which the big-tile kernels are used."""
+    w = dataclasses.replace(W.ragged_mini(m=m),
+                            shapes=tuple([("a", (65536,)), ("b", (65541,)), ("c", (3,)),
+                                          ("d", (131072,)), ("e", (65535,))]),
+                            rounds=2, tau=2)
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    PU.compare_run(w, prob, opt, np.arange(w.d, dtype=np.int64), w.rounds, bitwise_f32=True,
+                   fused_last=fused)
+    opt.close()
+
+
 @pytest.mark.parametrize("mix,exact", [("random", True), ("expgraph", True), ("random", False)])
 def test_largest_worker_count_with_gossip(mix, exact):
     """m = SLOWMO_MAX_WORKERS = 1024 replicas: pointer tables, mixing order
