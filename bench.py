@@ -94,11 +94,13 @@ def big_elements(w, fused: bool) -> int:
     """Elements that the big-tile kernels take in the outer step (fused with
     the last local step or not): the whole 65 536-element pieces of every
     tensor, from 8 workers on for the fused kernel and from 16 for the plain
-    outer step, unless the buffers are averaged (the library's rule; every
-    tensor of the benchmark is 16-byte aligned)."""
+    outer step, if there are at least 160 such pieces and the buffers are not
+    averaged (the library's rule; every tensor of the benchmark is 16-byte
+    aligned)."""
     if not w.exact_average or w.policy == "average" or w.m < (8 if fused else 16):
         return 0
-    return sum(n // BIG_TILE * BIG_TILE for n in w.numel)
+    tiles = sum(n // BIG_TILE for n in w.numel)
+    return tiles * BIG_TILE if tiles >= 160 else 0
 
 
 def fusable(w) -> bool:

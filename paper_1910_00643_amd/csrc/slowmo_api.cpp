@@ -583,7 +583,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
         rt.push_back({j, static_cast<int32_t>(k)});
     }
   }
-  if (bt.empty()) {
+  if (bt.empty() || (big < 0 && static_cast<int64_t>(bt.size()) < kBigMinTiles)) {
     ctx->d_rtiles = ctx->d_otiles;
     ctx->n_rtiles = ctx->n_otiles;
   } else {

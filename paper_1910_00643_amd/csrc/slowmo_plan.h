@@ -45,6 +45,11 @@ constexpr int32_t kBigVpt = 16;
 constexpr int32_t kBigTile = 4 * kBigBlock * kBigVpt;
 constexpr int32_t kBigFusedFromWorkers = 8;
 constexpr int32_t kBigOuterFromWorkers = 16;
+// ... and only when there are enough of them to occupy the chip: one big tile
+// keeps one of the 256 CUs busy.  Measured on one tensor of k big tiles (m = 8
+// and 32): twice as slow as single-wave tiles at k = 64, 6-17 % slower at
+// k = 128, 4-15 % faster from k = 173 on.
+constexpr int32_t kBigMinTiles = 160;
 static_assert(kBigTile % kOuterTile == 0, "a big tile is a whole number of ordinary tiles");
 
 // One tile of either kernel: the k-th piece of a tensor.  For the local step

@@ -6,6 +6,7 @@ kernels that walk all workers differ by up to 15 % between placements, so a
 comparison across processes says little.
 
     python -m slowmo_inputs.ab_big_tiles            # the table of profiles/outer_step_two_pass_and_wide_tiles.md
+    python -m slowmo_inputs.ab_big_tiles --sweep    # one tensor of k big tiles, k = 4 .. 1024: where they start to pay
 
 Measurement only."""
 from __future__ import annotations
@@ -39,11 +40,14 @@ def _context(w, prob, big: int):
 def compare(name: str, fused: bool, reps: int = 6, **changes):
     """Median and minimum ms of the call with single-wave tiles and with big
     tiles.  fused: slowmo_local_outer_step (tau = 2: a first step, then the
-    fused last step), else slowmo_outer_step (tau = 1)."""
+    fused last step), else slowmo_outer_step (tau = 1).  name: a workload of
+    slowmo_inputs.workloads, or "mini" (the small SGD configuration of the
+    parity tests, for use with shapes=...)."""
     import torch
     from . import workloads as W
     from .gpu_problem import GpuProblem
-    w = dataclasses.replace(W.BY_NAME[name](), tau=2 if fused else 1, **changes)
+    base = W.ragged_mini(m=changes.pop("m", 3)) if name == "mini" else W.BY_NAME[name]()
+    w = dataclasses.replace(base, tau=2 if fused else 1, **changes)
     prob = GpuProblem(w, "cuda:0", ring=1, grad_layout="padded", param_layout="separate")
     prob.fill_grads(0, 0)
     opts = {b: _context(w, prob, b) for b in (0, 1)}
@@ -89,5 +93,18 @@ def main(repetitions: int = 2):
                   f"(min {ms[1][1]:.4f}), ratio {ms[1][0] / ms[0][0]:.3f}", flush=True)
 
 
+def sweep():
+    """One tensor of k whole big tiles: a big tile keeps one CU busy, so few of
+    them leave the chip idle."""
+    for m in (8, 32):
+        for k in (4, 16, 32, 64, 96, 128, 192, 256, 384, 512, 1024):
+            shapes = (("a", (k * 65536,)),)
+            _, f = compare("mini", True, reps=8, m=m, shapes=shapes)
+            _, o = compare("mini", False, reps=8, m=m, shapes=shapes)
+            print(f"m={m} big tiles={k:5d}: last local step + outer step {f[0][0]:.4f} -> {f[1][0]:.4f} ms "
+                  f"(ratio {f[1][0] / f[0][0]:.3f}); outer step {o[0][0]:.4f} -> {o[1][0]:.4f} ms "
+                  f"(ratio {o[1][0] / o[0][0]:.3f})", flush=True)
+
+
 if __name__ == "__main__":
-    main()
+    sweep() if "--sweep" in sys.argv[1:] else main()

@@ -415,7 +415,7 @@ def _with_env(name, value, make):
     ("adam", "bf16", "maintain", 3, ("separate", "padded")),
     ("adam", "f32", "reset", 3, ("separate", "separate")),
     ("sgd_nesterov", "f32", "reset", 3, ("flat", "padded")),           # unaligned replicas: no big tile
-    ("sgd_nesterov", "f32", "reset", 17, ("separate", "separate")),    # big tiles on by themselves
+    ("sgd_nesterov", "f32", "reset", 17, ("separate", "separate")),
 ])
 @pytest.mark.parametrize("fused", [False, True])
 def test_big_tiles_equal_the_ordinary_tiles_bitwise(base, grad_dtype, policy, m, layouts, fused):
@@ -429,7 +429,7 @@ def test_big_tiles_equal_the_ordinary_tiles_bitwise(base, grad_dtype, policy, m,
                             tensor_lr_scale=tuple((1.0, 0.5, 2.0)[j % 3] for j in range(26)))
     idx = np.arange(w.d, dtype=np.int64)
     res = []
-    for big in ("0", "1") if m < 16 else ("0", "-1"):
+    for big in ("0", "1"):        # by itself the library takes big tiles only for large lists
         prob = _problem(w, ring=2, param_layout=layouts[0], grad_layout=layouts[1])
         opt = _with_env("SLOWMO_BIG_TILES", big, lambda: PU.make_gpu(w, prob))
         PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
@@ -456,14 +456,15 @@ def test_worker_counts(m):
                                      (150, True)])
 def test_worker_counts_on_big_tiles(m, fused):
     """Tensors of exactly one big tile (no rest), one big tile and five
-    elements, two big tiles, and one too small for any, at worker counts on both
-    sides of the thresholds from which the big-tile kernels are used."""
+    elements, two big tiles, and one too small for any, at several worker
+    counts (big tiles forced: by itself the library takes them only when there
+    are enough to occupy the chip)."""
     w = dataclasses.replace(W.ragged_mini(m=m),
                             shapes=tuple([("a", (65536,)), ("b", (65541,)), ("c", (3,)),
                                           ("d", (131072,)), ("e", (65535,))]),
                             rounds=2, tau=2)
     prob = _problem(w, grad_layout="separate")
-    opt = PU.make_gpu(w, prob)
+    opt = _with_env("SLOWMO_BIG_TILES", "1", lambda: PU.make_gpu(w, prob))
     PU.compare_run(w, prob, opt, np.arange(w.d, dtype=np.int64), w.rounds, bitwise_f32=True,
                    fused_last=fused)
     opt.close()
