@@ -328,6 +328,33 @@ slowmo_status slowmo_debias(slowmo_ctx *ctx, float *const *z, void *stream);
 slowmo_status slowmo_debias_static(slowmo_ctx *ctx, float *const *z, void *stream);
 
 /*
+ * The two learning-rate schedules of the paper's experiments, as functions of
+ * the base-optimizer step number `step` >= 0 (the caller passes the result as
+ * `lr`; nothing in a context depends on them).  Host-only, computed in double
+ * precision and rounded once to float.
+ *
+ * slowmo_lr_step_decay (Section 4, CIFAR-10 and ImageNet): linear warm-up from
+ * start_lr at step 0 to base_lr at step warmup_steps, then
+ * base_lr * factor^(number of milestones <= step); the paper uses factor 0.1
+ * at epochs 100/150/175 and 30/60/80 after 5 epochs of warm-up (the caller
+ * converts epochs to steps).  milestones: n_milestones ascending step numbers
+ * (may be NULL if n_milestones = 0).
+ *
+ * slowmo_lr_inverse_sqrt (Appendix A.3, WMT'16 En-De): linear warm-up from
+ * init_lr to peak_lr over warmup_steps steps (4000 steps to 1e-3 in the
+ * paper), then peak_lr * sqrt(warmup_steps / step).
+ *
+ * Errors: ARG for a NULL lr_out, step < 0, warmup_steps < 0, rates that are
+ * not finite or base_lr / peak_lr <= 0, start_lr / init_lr < 0, factor not in
+ * (0, 1], milestones that do not ascend.
+ */
+slowmo_status slowmo_lr_step_decay(float base_lr, float start_lr, int64_t warmup_steps,
+                                   const int64_t *milestones, int32_t n_milestones, float factor,
+                                   int64_t step, float *lr_out);
+slowmo_status slowmo_lr_inverse_sqrt(float peak_lr, float init_lr, int64_t warmup_steps,
+                                     int64_t step, float *lr_out);
+
+/*
  * The communication pattern of Appendix C.1 (one-peer, time-varying directed
  * exponential graph): at iteration `step` every worker receives from the
  * worker 2^(step mod L) ranks below it (mod m), L = floor(log2(m-1)) + 1.

@@ -13,7 +13,8 @@ Readings of the paper where it is silent or inconsistent: coupled L2 weight
 decay; Adam's bias-correction exponent
 counts the current update (starts at 1); eps is added after the square root of
 the bias-corrected second moment; the learning rate is a per-call scalar (the
-one given to the outer step is gamma_t of Eq. (2)-(3)); the mean is a
+one given to the outer step is gamma_t of Eq. (2)-(3); the two schedules of
+Section 4 / Appendix A.3 are plain functions of the step number); the mean is a
 left-to-right sum over workers 0..m-1 followed by a division by m; "reset"
 zeroes the buffers (and Adam's step counter) at the start of every outer
 iteration, "maintain" leaves them alone, "average" replaces every worker's
@@ -91,6 +92,28 @@ def exponential_graph_in_peers(m: int, step: int) -> np.ndarray:
     n_hops = int(np.floor(np.log2(m - 1))) + 1 if m > 2 else 1
     hop = 1 << (step % n_hops)
     return ((np.arange(m) - hop) % m).astype(np.int32)
+
+
+def lr_warmup_step_decay(base_lr: float, start_lr: float, warmup_steps: int, milestones,
+                         factor: float, step: int) -> float:
+    """Section 4 (CIFAR-10, ImageNet): the learning rate rises linearly during
+    the warm-up and afterwards drops by a constant factor at every milestone.
+    Steps are base-optimizer steps counted from 0; the rate reaches base_lr at
+    step warmup_steps.  Where the paper is silent: the warm-up starts at
+    start_lr, and a milestone counts from the step that bears its number."""
+    if step < warmup_steps:
+        return start_lr + (base_lr - start_lr) * step / warmup_steps
+    passed = sum(1 for ms in milestones if step >= ms)
+    return base_lr * factor ** passed
+
+
+def lr_warmup_inverse_sqrt(peak_lr: float, init_lr: float, warmup_steps: int, step: int) -> float:
+    """Appendix A.3 (WMT'16 En-De): the learning rate rises linearly to peak_lr
+    over warmup_steps steps and then decays in proportion to the inverse square
+    root of the step number (continuous at step warmup_steps)."""
+    if step < warmup_steps:
+        return init_lr + (peak_lr - init_lr) * step / warmup_steps
+    return peak_lr * (warmup_steps / step) ** 0.5 if step > 0 else peak_lr
 
 
 def _ptr(a: np.ndarray) -> C.c_void_p:
@@ -208,6 +231,8 @@ class SlowMoOracle:
                 for (a, b), s, wd in zip(self.bounds, self.t_lr, self.t_wd) if b > a]
 
     exponential_graph_in_peers = staticmethod(exponential_graph_in_peers)
+    lr_warmup_step_decay = staticmethod(lr_warmup_step_decay)
+    lr_warmup_inverse_sqrt = staticmethod(lr_warmup_inverse_sqrt)
 
     # Algorithm C.1, communication half of a stochastic-gradient-push step
     def mix_step(self, in_peer) -> None:

@@ -9,7 +9,7 @@ from .binding import (SlowMoError, slowmo_config, slowmo_create, slowmo_destroy,
                       slowmo_expgraph_in_peers, slowmo_export_bytes, slowmo_export_state,
                       slowmo_import_state, slowmo_local_outer_step, slowmo_local_step,
                       slowmo_mix_step, slowmo_local_mix_step, slowmo_plan_mix, slowmo_check_device_range, slowmo_get_pushsum_weights, slowmo_debias,
-                      slowmo_debias_static,
+                      slowmo_debias_static, slowmo_lr_step_decay, slowmo_lr_inverse_sqrt,
                       slowmo_set_tensor_hparams,
                       slowmo_outer_step, slowmo_plan_local,
                       slowmo_plan_outer, slowmo_state_bytes, slowmo_version)

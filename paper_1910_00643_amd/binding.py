@@ -34,7 +34,8 @@ EXPORTS = ["slowmo_state_bytes", "slowmo_create", "slowmo_local_step", "slowmo_o
            "slowmo_expgraph_in_peers", "slowmo_set_tensor_hparams", "slowmo_export_bytes",
            "slowmo_export_state", "slowmo_import_state", "slowmo_local_outer_step",
            "slowmo_get_pushsum_weights", "slowmo_debias", "slowmo_plan_mix",
-           "slowmo_local_mix_step", "slowmo_check_device_range", "slowmo_debias_static"]
+           "slowmo_local_mix_step", "slowmo_check_device_range", "slowmo_debias_static",
+           "slowmo_lr_step_decay", "slowmo_lr_inverse_sqrt"]
 
 
 (SLOWMO_MIX_OWN_HELD, SLOWMO_MIX_SOURCE_HELD, SLOWMO_MIX_SOURCE_IS_FIRST, SLOWMO_MIX_OPENS_CYCLE,
@@ -130,6 +131,11 @@ def lib() -> C.CDLL:
     L.slowmo_debias.restype = C.c_int
     L.slowmo_debias_static.argtypes = [vp, C.POINTER(vp), vp]
     L.slowmo_debias_static.restype = C.c_int
+    L.slowmo_lr_step_decay.argtypes = [C.c_float, C.c_float, i64, C.POINTER(i64), i32, C.c_float, i64,
+                                       C.POINTER(C.c_float)]
+    L.slowmo_lr_step_decay.restype = C.c_int
+    L.slowmo_lr_inverse_sqrt.argtypes = [C.c_float, C.c_float, i64, i64, C.POINTER(C.c_float)]
+    L.slowmo_lr_inverse_sqrt.restype = C.c_int
     L.slowmo_expgraph_in_peers.argtypes = [i32, i64, C.POINTER(i32)]
     L.slowmo_expgraph_in_peers.restype = C.c_int
     L.slowmo_set_tensor_hparams.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
@@ -257,6 +263,24 @@ def slowmo_debias_static(ctx, z, stream: int = 0) -> None:
     (no allocation; m * n_tensors <= SLOWMO_STATIC_MAX_POINTERS)."""
     arr = z if (z is None or isinstance(z, C.Array)) else _ptr_array(z)
     _check(lib().slowmo_debias_static(ctx, arr, C.c_void_p(stream) if stream else None), ctx)
+
+
+def slowmo_lr_step_decay(base_lr: float, start_lr: float, warmup_steps: int, milestones,
+                         factor: float, step: int) -> float:
+    """Linear warm-up, then one factor per milestone passed (Section 4)."""
+    ms = list(milestones or [])
+    arr = (C.c_int64 * max(len(ms), 1))(*ms)
+    out = C.c_float()
+    _check(lib().slowmo_lr_step_decay(base_lr, start_lr, warmup_steps, arr if ms else None, len(ms),
+                                      factor, step, C.byref(out)), None)
+    return out.value
+
+
+def slowmo_lr_inverse_sqrt(peak_lr: float, init_lr: float, warmup_steps: int, step: int) -> float:
+    """Linear warm-up, then proportional to 1 / sqrt(step) (Appendix A.3)."""
+    out = C.c_float()
+    _check(lib().slowmo_lr_inverse_sqrt(peak_lr, init_lr, warmup_steps, step, C.byref(out)), None)
+    return out.value
 
 
 def slowmo_expgraph_in_peers(m: int, step: int):

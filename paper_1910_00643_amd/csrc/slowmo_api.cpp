@@ -872,6 +872,49 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
   return SLOWMO_OK;
 }
 
+slowmo_status slowmo_lr_step_decay(float base_lr, float start_lr, int64_t warmup_steps,
+                                   const int64_t *milestones, int32_t n_milestones, float factor,
+                                   int64_t step, float *lr_out) {
+  if (!lr_out || step < 0 || warmup_steps < 0 || n_milestones < 0 ||
+      (n_milestones > 0 && !milestones))
+    return fail(nullptr, SLOWMO_ERR_ARG, "bad arguments");
+  if (!finite_pos(base_lr) || !std::isfinite(start_lr) || start_lr < 0.f ||
+      !std::isfinite(factor) || factor <= 0.f || factor > 1.f)
+    return fail(nullptr, SLOWMO_ERR_ARG,
+                "base_lr must be finite and > 0, start_lr finite and >= 0, factor in (0, 1]");
+  for (int32_t i = 0; i < n_milestones; ++i)
+    if (milestones[i] < 0 || (i > 0 && milestones[i] <= milestones[i - 1]))
+      return fail(nullptr, SLOWMO_ERR_ARG, "milestones must be >= 0 and ascend");
+  double lr;
+  if (step < warmup_steps) {  // Section 4: linear warm-up
+    lr = static_cast<double>(start_lr) + (static_cast<double>(base_lr) - start_lr) *
+                                             static_cast<double>(step) / static_cast<double>(warmup_steps);
+  } else {                    // ... then one factor per milestone passed
+    lr = base_lr;
+    for (int32_t i = 0; i < n_milestones && milestones[i] <= step; ++i) lr *= static_cast<double>(factor);
+  }
+  *lr_out = static_cast<float>(lr);
+  return SLOWMO_OK;
+}
+
+slowmo_status slowmo_lr_inverse_sqrt(float peak_lr, float init_lr, int64_t warmup_steps,
+                                     int64_t step, float *lr_out) {
+  if (!lr_out || step < 0 || warmup_steps < 0) return fail(nullptr, SLOWMO_ERR_ARG, "bad arguments");
+  if (!finite_pos(peak_lr) || !std::isfinite(init_lr) || init_lr < 0.f)
+    return fail(nullptr, SLOWMO_ERR_ARG, "peak_lr must be finite and > 0, init_lr finite and >= 0");
+  double lr;
+  if (step < warmup_steps) {  // Appendix A.3: linear warm-up
+    lr = static_cast<double>(init_lr) + (static_cast<double>(peak_lr) - init_lr) *
+                                            static_cast<double>(step) / static_cast<double>(warmup_steps);
+  } else if (step == 0) {
+    lr = peak_lr;
+  } else {                    // ... then proportional to 1 / sqrt(step)
+    lr = peak_lr * std::sqrt(static_cast<double>(warmup_steps) / static_cast<double>(step));
+  }
+  *lr_out = static_cast<float>(lr);
+  return SLOWMO_OK;
+}
+
 slowmo_status slowmo_expgraph_in_peers(int32_t m, int64_t step, int32_t *in_peer) {
   if (m < 1 || step < 0 || !in_peer) return fail(nullptr, SLOWMO_ERR_ARG, "bad arguments");
   if (m == 1) {

@@ -726,6 +726,50 @@ def pin_weight_decay_under_push_sum_acts_on_the_numerator(make):
 
 # ------------------------------------------- per-tensor hyper-parameters
 
+def pin_step_decay_schedule_of_the_image_experiments(make):
+    """Section 4: linear warm-up over the first 5 epochs, then a factor 10 down
+    at epochs 30, 60, 80 (ImageNet, 90 epochs) or 100, 150, 175 (CIFAR-10, 200
+    epochs).  Values written out by hand for 100 steps per epoch."""
+    O = type(make(np.zeros(1), m=1, tau=1, alpha=1.0, beta=0.0))
+    f = O.lr_warmup_step_decay
+    S, base, start = 100, 3.2, 0.1                      # 0.1 x 32 workers (Appendix A.2)
+    imagenet = [30 * S, 60 * S, 80 * S]
+    expect = {0: 0.1, 1: 0.1 + 3.1 / 500, 250: 1.65, 499: 3.2 - 3.1 / 500, 500: 3.2, 501: 3.2,
+              2999: 3.2, 3000: 0.32, 3001: 0.32, 5999: 0.32, 6000: 0.032, 7999: 0.032,
+              8000: 0.0032, 8999: 0.0032}
+    for step, lr in expect.items():
+        assert abs(f(base, start, 5 * S, imagenet, 0.1, step) - lr) <= 1e-12 * max(1.0, lr), step
+    cifar = [100 * S, 150 * S, 175 * S]
+    for step, lr in {9999: 3.2, 10000: 0.32, 15000: 0.032, 17499: 0.032, 17500: 0.0032,
+                     19999: 0.0032}.items():
+        assert abs(f(base, start, 5 * S, cifar, 0.1, step) - lr) <= 1e-12, step
+    # no warm-up, no milestone: constant
+    assert f(0.05, 0.0, 0, [], 0.1, 0) == 0.05 and f(0.05, 0.0, 0, [], 0.1, 10 ** 6) == 0.05
+    # the warm-up is a straight line: equal increments
+    inc = [f(base, start, 500, imagenet, 0.1, s + 1) - f(base, start, 500, imagenet, 0.1, s)
+           for s in range(499)]
+    assert max(inc) - min(inc) < 1e-12 and abs(inc[0] - 3.1 / 500) < 1e-12
+
+
+def pin_inverse_square_root_schedule_of_the_translation_experiment(make):
+    """Appendix A.3: the rate rises linearly for 4000 steps to 1e-3 and then
+    decays in proportion to 1 / sqrt(step): four times the steps, half the rate."""
+    O = type(make(np.zeros(1), m=1, tau=1, alpha=1.0, beta=0.0))
+    f = O.lr_warmup_inverse_sqrt
+    assert f(1e-3, 0.0, 4000, 0) == 0.0
+    assert abs(f(1e-3, 0.0, 4000, 1000) - 0.25e-3) < 1e-18
+    assert abs(f(1e-3, 0.0, 4000, 3999) - 1e-3 * 3999 / 4000) < 1e-18
+    assert f(1e-3, 0.0, 4000, 4000) == 1e-3
+    assert abs(f(1e-3, 0.0, 4000, 16000) - 0.5e-3) < 1e-18
+    assert abs(f(1e-3, 0.0, 4000, 64000) - 0.25e-3) < 1e-18
+    assert abs(f(1e-3, 0.0, 4000, 4001) - 1e-3 * (4000 / 4001) ** 0.5) < 1e-18
+    # a warm-up that starts above zero
+    assert f(1e-3, 1e-7, 4000, 0) == 1e-7 and abs(f(1e-3, 1e-7, 4000, 2000) - (1e-7 + (1e-3 - 1e-7) / 2)) < 1e-18
+    # after the warm-up, rate x sqrt(step) is constant
+    c = [f(7e-4, 0.0, 100, s) * s ** 0.5 for s in (100, 101, 1000, 12345)]
+    assert max(c) - min(c) < 1e-15
+
+
 def pin_parameter_groups_vs_library(make):
     """Per-tensor weight decay and learning-rate scale are the library
     optimizers' parameter groups: m = 1, alpha = 1, beta = 0 leaves the bare

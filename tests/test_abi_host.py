@@ -282,3 +282,40 @@ def test_mix_plan_rejects_bad_maps():
     assert P.slowmo_plan_mix([0, 3]) is None
     assert P.slowmo_plan_mix([-1, 0]) is None
     assert P.slowmo_plan_mix([]) is None
+
+
+def test_learning_rate_schedules_match_the_oracle_and_reject_bad_arguments():
+    """The two schedules of the paper's experiments (Section 4, Appendix A.3):
+    the library's value is the oracle's, rounded to float."""
+    from oracle import slowmo_oracle as O
+    S = 100
+    for ms in ([30 * S, 60 * S, 80 * S], [100 * S, 150 * S, 175 * S], []):
+        for step in list(range(0, 520, 7)) + [2999, 3000, 3001, 6000, 8000, 8999, 10000, 15000,
+                                               17500, 10 ** 7]:
+            want = np.float32(O.lr_warmup_step_decay(3.2, 0.1, 5 * S, ms, 0.1, step))
+            got = P.slowmo_lr_step_decay(3.2, 0.1, 5 * S, ms, 0.1, step)
+            # base_lr and factor reach the library as floats
+            assert abs(got - want) <= 2e-7 * want, (ms, step, got, want)
+    for step in (0, 1, 1000, 3999, 4000, 4001, 16000, 64000, 10 ** 7):
+        want = np.float32(O.lr_warmup_inverse_sqrt(1e-3, 0.0, 4000, step))
+        got = P.slowmo_lr_inverse_sqrt(1e-3, 0.0, 4000, step)
+        assert abs(got - want) <= 2e-7 * want, (step, got, want)
+    assert P.slowmo_lr_inverse_sqrt(1e-3, 0.0, 4000, 16000) == pytest.approx(0.5e-3, rel=1e-6)
+    assert P.slowmo_lr_step_decay(3.2, 0.1, 500, [3000, 6000, 8000], 0.1, 6000) == \
+        pytest.approx(0.032, rel=1e-6)
+    bad = [lambda: P.slowmo_lr_step_decay(0.0, 0.0, 5, [], 0.1, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, -0.1, 5, [], 0.1, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, 0.0, -1, [], 0.1, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, 0.0, 5, [30, 20], 0.1, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, 0.0, 5, [10], 0.0, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, 0.0, 5, [10], 1.5, 0),
+           lambda: P.slowmo_lr_step_decay(1.0, 0.0, 5, [10], 0.1, -1),
+           lambda: P.slowmo_lr_step_decay(float("inf"), 0.0, 5, [10], 0.1, 0),
+           lambda: P.slowmo_lr_inverse_sqrt(0.0, 0.0, 10, 0),
+           lambda: P.slowmo_lr_inverse_sqrt(1e-3, -1.0, 10, 0),
+           lambda: P.slowmo_lr_inverse_sqrt(1e-3, 0.0, -1, 0),
+           lambda: P.slowmo_lr_inverse_sqrt(1e-3, 0.0, 10, -5)]
+    for call in bad:
+        with pytest.raises(P.SlowMoError) as e:
+            call()
+        assert e.value.status == B.SLOWMO_ERR_ARG

@@ -553,6 +553,48 @@ def test_learning_rate_schedule_and_side_stream():
     opt.close()
 
 
+@pytest.mark.parametrize("base", ["sgd_nesterov", "adam"])
+def test_run_under_the_papers_schedules(base):
+    """A short run whose learning rate follows the schedules of the paper's
+    experiments: warm-up and step decay for SGD (Section 4), warm-up and
+    inverse square root for Adam (Appendix A.3).  The GPU side takes the rate
+    from the library's helper, the oracle from its own function; the constants
+    are exact in fp32, so both get the same float."""
+    import paper_1910_00643_amd as P
+    from oracle import slowmo_oracle as O
+    w = dataclasses.replace(W.ragged_mini(base=base), tau=4, rounds=5)
+    idx = np.arange(w.d, dtype=np.int64)
+    if base == "sgd_nesterov":
+        gpu_lr = lambda s: P.slowmo_lr_step_decay(0.125, 0.0078125, 6, [10, 14, 17], 0.5, s)    # noqa: E731
+        ref_lr = lambda s: O.lr_warmup_step_decay(0.125, 0.0078125, 6, [10, 14, 17], 0.5, s)    # noqa: E731
+    else:
+        gpu_lr = lambda s: P.slowmo_lr_inverse_sqrt(0.0009765625, 0.0, 8, s)                    # noqa: E731
+        ref_lr = lambda s: O.lr_warmup_inverse_sqrt(0.0009765625, 0.0, 8, s)                    # noqa: E731
+    o = PU.make_oracle(w, idx)
+    o32 = PU.make_oracle(w, idx, "f32")
+    prob = _problem(w, grad_layout="separate")
+    opt = PU.make_gpu(w, prob)
+    step = 0
+    for t in range(w.rounds):
+        for k in range(w.tau):
+            lr = gpu_lr(step + 1)                   # step 0 of a warm-up from zero has rate 0
+            assert lr == float(np.float32(ref_lr(step + 1))), (step, lr)
+            prob.fill_grads(0, step)
+            opt.local_step(prob.grads[0], lr)
+            g = PU.oracle_grads(w, idx, step)
+            o.local_step(g, lr)
+            o32.local_step(g, lr)
+            step += 1
+        opt.outer_step(lr)                          # gamma_t of Eq. (2)-(3): the current rate
+        o.outer_step(lr)
+        o32.outer_step(lr)
+    final = PU.gpu_state(w, prob, opt, idx)
+    PU.assert_params_close(final["x0"], o.x0, "x0 under the paper's schedule")
+    if base == "sgd_nesterov":
+        assert np.array_equal(final["x0"], o32.x0) and np.array_equal(final["u"], o32.u)
+    opt.close()
+
+
 def test_two_contexts_side_by_side():
     """Contexts share nothing: two optimizers over different tensor lists,
     stepped alternately, give the results each gives alone."""

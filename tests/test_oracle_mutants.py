@@ -86,6 +86,20 @@ PY_MUTANTS = [
     ("groups_ignore_tensor_wd", "lr_j, self.momentum, wd_j)", "lr_j, self.momentum, self.weight_decay)", 0),
     ("groups_outer_uses_global_lr", "_ptr(self.u[a:b]), lr_j, self.alpha, self.beta)", "_ptr(self.u[a:b]), lr, self.alpha, self.beta)", 0),
     ("groups_outer_not_copied_back", "                self.x[:, a:b] = xs\n", "", 0),
+    ("schedule_milestone_one_step_late", "passed = sum(1 for ms in milestones if step >= ms)",
+     "passed = sum(1 for ms in milestones if step > ms)", 0),
+    ("schedule_factor_applied_once", "return base_lr * factor ** passed",
+     "return base_lr * factor ** min(passed, 1)", 0),
+    ("schedule_warmup_starts_at_zero", "return start_lr + (base_lr - start_lr) * step / warmup_steps",
+     "return base_lr * step / warmup_steps", 0),
+    ("schedule_warmup_ends_one_step_early", "return start_lr + (base_lr - start_lr) * step / warmup_steps",
+     "return start_lr + (base_lr - start_lr) * (step + 1) / warmup_steps", 0),
+    ("schedule_inverse_not_root", "return peak_lr * (warmup_steps / step) ** 0.5 if step > 0 else peak_lr",
+     "return peak_lr * (warmup_steps / step) if step > 0 else peak_lr", 0),
+    ("schedule_inverse_sqrt_of_step_only", "return peak_lr * (warmup_steps / step) ** 0.5 if step > 0 else peak_lr",
+     "return peak_lr * (1.0 / step) ** 0.5 if step > 0 else peak_lr", 0),
+    ("schedule_inverse_warmup_ignores_init", "return init_lr + (peak_lr - init_lr) * step / warmup_steps",
+     "return peak_lr * step / warmup_steps", 0),
     ("pushsum_weights_not_reset_at_exact_average",
      "            self.w[...] = 1     # all mass is shared equally again after the exact average\n",
      "            pass\n", 0),
