@@ -94,10 +94,13 @@ def big_elements(w, fused: bool) -> int:
     """Elements that the big-tile kernels take in the outer step (fused with
     the last local step or not): the whole 65 536-element pieces of every
     tensor, from 8 workers on for the fused kernel and from 16 for the plain
-    outer step, if there are at least 160 such pieces and the buffers are not
+    outer step, if there are at least 160 such pieces; the fused kernel only
+    under the "reset" buffer strategy, the plain one unless the buffers are
     averaged (the library's rule; every tensor of the benchmark is 16-byte
     aligned)."""
     if not w.exact_average or w.policy == "average" or w.m < (8 if fused else 16):
+        return 0
+    if fused and w.policy != "reset":
         return 0
     tiles = sum(n // BIG_TILE for n in w.numel)
     return tiles * BIG_TILE if tiles >= 160 else 0

@@ -53,8 +53,9 @@
  *    slowmo_local_mix_step launch two kernels when a pointer is not 16-byte
  *    aligned; slowmo_outer_step and slowmo_local_outer_step launch one kernel
  *    for the whole 65 536-element pieces of the tensors and one for the rest
- *    when there are 8 workers or more and at least 160 such pieces; slowmo_import_state copies up to four
- *    arrays).  If the HIP
+ *    when the tensor list has at least 160 such pieces -- the former from 16
+ *    workers on, the latter from 8 on under SLOWMO_BUF_RESET;
+ *    slowmo_import_state copies up to four arrays).  If the HIP
  *    runtime refuses one of them after an earlier one was issued, device
  *    memory is partly updated and cannot be rolled back: the call returns
  *    SLOWMO_ERR_HIP with a message that says so, counters and weights keep

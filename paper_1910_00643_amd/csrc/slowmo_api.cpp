@@ -241,6 +241,7 @@ struct slowmo_ctx {
   TileRef *d_btiles = nullptr, *d_rtiles = nullptr;
   int32_t n_btiles = 0, n_rtiles = 0;
   bool big_outer = false;  // the plain outer step uses them too (it gains only with many workers)
+  bool big_forced = false; // SLOWMO_BIG_TILES=1: wherever the kernels allow
 
   TableRing<kGradSlots> gtab;  // gradient-pointer tables of recent calls (m * n_tensors each)
   TableRing<kSlots> mixtab;  // update order of the current mixing step (at most m entries)
@@ -463,6 +464,7 @@ slowmo_status slowmo_create(slowmo_ctx **out, const slowmo_config *cfg, int32_t 
   ctx->tune.big_tiles =
       ((big < 0 ? m >= kBigFusedFromWorkers : big != 0) && ctx->tune.nontemporal) ? 1 : 0;
   ctx->big_outer = ctx->tune.big_tiles && (big > 0 || m >= kBigOuterFromWorkers);
+  ctx->big_forced = big > 0;
   ctx->fail_launch_at = env_flag("SLOWMO_TEST_FAIL_LAUNCH", 0);
 
   const int64_t n_ltiles = count_local_tiles(m, n_tensors, numel);
@@ -853,8 +855,13 @@ slowmo_status slowmo_local_outer_step(slowmo_ctx *ctx, const void *const *grads,
       return o;
     };
     int launched = 0;
-    // the big-tile kernel stores the buffers or drops them; it does not average them
-    const bool use_big = ctx->n_btiles > 0 && c.policy != SLOWMO_BUF_AVERAGE;
+    // big tiles pay when the buffers of this step are dropped ("reset"); stores of
+    // every worker's buffers inside the walk cost them their gain (measured: 2-10 %
+    // slower than single-wave tiles under "maintain"), and the buffer average does
+    // not fit their registers
+    const bool use_big =
+        ctx->n_btiles > 0 && (c.policy == SLOWMO_BUF_RESET ||
+                              (ctx->big_forced && c.policy == SLOWMO_BUF_MAINTAIN));
     st = run_tiled(
         ctx, use_big, &launched, "fused local+outer kernel launch",
         [&](const TileRef *t, int32_t n) {

@@ -38,8 +38,11 @@ constexpr int32_t kOuterTile = 4 * kOuterBlock;
 // single-wave tiles: the fused last step is 10-14 % faster at m = 32, 6-7 % at
 // m = 16, 3-5 % at m = 8 and no faster at m = 4; the plain outer step 8 % faster
 // at m = 32 and within +-4 % at m = 8.  Smaller shapes (128 or 64 KiB per stream
-// and workgroup) gain half of that or nothing.  Used for the whole kBigTile
-// pieces of aligned tensors from these worker counts on:
+// and workgroup) gain half of that or nothing.  Under "maintain" the fused
+// kernel stores every worker's buffers inside the walk and is 2-10 % slower in
+// this shape than in single waves, so it takes big tiles only under "reset".
+// Used for the whole kBigTile pieces of aligned tensors from these worker
+// counts on:
 constexpr int32_t kBigBlock = 1024;
 constexpr int32_t kBigVpt = 16;
 constexpr int32_t kBigTile = 4 * kBigBlock * kBigVpt;
