@@ -476,6 +476,10 @@ def main():
     ap.add_argument("--ladder", action="store_true",
                     help="instead of the benchmark: the microbenchmark ladder of access shapes "
                          "(slowmo_inputs/ladder.py), m and floats per stream from --ladder-m/-n")
+    ap.add_argument("--placement", action="store_true",
+                    help="instead of the benchmark: three launches of the stream microbenchmark on "
+                         "40 buffers allocated one after the other (how much the place of the "
+                         "operands in memory matters)")
     ap.add_argument("--ladder-m", type=int, default=32)
     ap.add_argument("--ladder-n", type=int, default=25_559_040)
     args = ap.parse_args()
@@ -488,6 +492,10 @@ def main():
     from slowmo_inputs import workloads as W
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.placement:
+        from slowmo_inputs import ladder
+        ladder.placement(args.ladder_m, args.ladder_n)
+        return
     if args.ladder:
         from slowmo_inputs import ladder
         ladder.main(args.ladder_m, args.ladder_n)

@@ -115,6 +115,40 @@ def run(m: int = 32, n: int = 25_559_040, reps: int = 5, device: str = "cuda:0")
     return {"m": m, "floats_per_stream": n, "reps": reps, "rows": rows}
 
 
+def placement(m: int = 32, n: int = 25_559_040, count: int = 40, device: str = "cuda:0"):
+    """The same three launches on `count` buffers allocated one after the other
+    and kept (so that each lies in other physical memory): m+2 streams in place
+    with single waves and with 1024-thread workgroups, and the local step's
+    mix.  Shows how much of a kernel's figure is the place its operands
+    happen to lie in (`python bench.py --placement`)."""
+    import torch
+    from . import device as D
+    stride = n + 65536
+    S = m + 2
+
+    def frac(buf, **kw):
+        D.streambench(buf, stride, n=n, **kw)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            D.streambench(buf, stride, n=n, **kw)
+        b.record()
+        torch.cuda.synchronize()
+        return kw["units"] * (kw["R"] + kw["W"]) * 4 * n / (a.elapsed_time(b) / 5) / 1e6 / HBM_PEAK_GBPS
+
+    keep = []
+    for i in range(count):
+        buf = torch.zeros(S * stride, dtype=torch.float32, device=device)
+        keep.append(buf)
+        f1 = frac(buf, units=1, S=S, R=S, W=S, in_place=True)
+        f2 = frac(buf, units=1, S=S, R=S, W=S, in_place=True, B=1024, VPT=16)
+        f3 = frac(buf, units=S // 3, S=3, R=3, W=2, in_place=True)
+        print(f"buffer {i:2d} ({S * stride * 4 / 2**30:.2f} GiB, after {i * S * stride * 4 / 2**30:6.1f} GiB of "
+              f"others): {S} streams in place, single waves {f1:.3f}; 1024 threads x 16 vec4/lane "
+              f"{f2:.3f}; 3r/2w {f3:.3f}", flush=True)
+
+
 def main(m: int = 32, n: int = 25_559_040):
     res = run(m, n)
     for r in res["rows"]:
