@@ -172,17 +172,18 @@ def summarize(directory, bench_args, out_md, title, extra_note=""):
     fetch, write = fetch or {}, write or {}
     cmd = "python3 $R/bench.py " + " ".join(bench_args)
     name = os.path.basename(os.path.normpath(directory))
+    where = "$R/" + os.path.relpath(os.path.abspath(directory), ROOT)   # as given on the command line
     out = [f"# rocprofv3 summary: {title}\n",
            f"Workload: {bench.describe(w)}. One MI355X; {a.warmup} warm-up + {a.steps} timed + "
            f"{a.steps} per-kernel-timed outer iterations per run; three runs of the same command "
            "under different rocprofv3 options.\n",
            "Commands (run from /tmp with TMPDIR=/tmp; `$R` is the repository root):\n",
            "```",
-           f"rocprofv3 --kernel-trace --stats -f csv -d $R/gpurun_out/{name}/kt -- {cmd}",
-           *([f"rocprofv3 --pmc FETCH_SIZE -f csv -d $R/gpurun_out/{name}/fetch -- {cmd}",
-              f"rocprofv3 --pmc WRITE_SIZE -f csv -d $R/gpurun_out/{name}/write -- {cmd}"]
+           f"rocprofv3 --kernel-trace --stats -f csv -d {where}/kt -- {cmd}",
+           *([f"rocprofv3 --pmc FETCH_SIZE -f csv -d {where}/fetch -- {cmd}",
+              f"rocprofv3 --pmc WRITE_SIZE -f csv -d {where}/write -- {cmd}"]
              if counters else []),
-           f"python3 -m slowmo_inputs.profile_summary $R/gpurun_out/{name} {' '.join(bench_args)}",
+           f"python3 -m slowmo_inputs.profile_summary {where} {' '.join(bench_args)}",
            "```\n",
            ("Counter scaling: `k_calib_copy` moves exactly 1 048 576 KiB each way per launch; "
             f"FETCH_SIZE reads {sum(fetch[cal]) / len(fetch[cal]):.2f} for it (factor {fs:.5f}), "
