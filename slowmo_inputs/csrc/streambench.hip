@@ -89,19 +89,31 @@ __global__ __launch_bounds__(B) void k_streams(float *base, Shape sh) {
   }
 }
 
+// lds: bytes of (unused) dynamic LDS per workgroup -- caps how many workgroups
+// share a CU (160 KiB per CU).
+template <int B, int VPT, bool NTL, bool NTS>
+hipError_t launch_nt(float *base, const Shape &sh, int lds, dim3 g, hipStream_t s) {
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_streams<B, VPT, NTL, NTS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_streams<B, VPT, NTL, NTS>), g, dim3(B), lds, s, base, sh);
+  return hipGetLastError();
+}
+
 template <int B, int VPT>
-hipError_t launch(float *base, const Shape &sh, int nt, hipStream_t s) {
+hipError_t launch(float *base, const Shape &sh, int nt, int lds, hipStream_t s) {
   const int64_t blocks = (sh.total + sh.iters - 1) / sh.iters;
   const int64_t grid = sh.remap ? (blocks + 7) / 8 * 8 : blocks;
   if (grid > INT32_MAX) return hipErrorInvalidValue;
-  const dim3 g(static_cast<unsigned>(grid)), blk(B);
+  const dim3 g(static_cast<unsigned>(grid));
   switch (nt & 3) {  // bit 0: non-temporal loads, bit 1: non-temporal stores
-    case 0: hipLaunchKernelGGL((k_streams<B, VPT, false, false>), g, blk, 0, s, base, sh); break;
-    case 1: hipLaunchKernelGGL((k_streams<B, VPT, true, false>), g, blk, 0, s, base, sh); break;
-    case 2: hipLaunchKernelGGL((k_streams<B, VPT, false, true>), g, blk, 0, s, base, sh); break;
-    default: hipLaunchKernelGGL((k_streams<B, VPT, true, true>), g, blk, 0, s, base, sh); break;
+    case 0: return launch_nt<B, VPT, false, false>(base, sh, lds, g, s);
+    case 1: return launch_nt<B, VPT, true, false>(base, sh, lds, g, s);
+    case 2: return launch_nt<B, VPT, false, true>(base, sh, lds, g, s);
+    default: return launch_nt<B, VPT, true, true>(base, sh, lds, g, s);
   }
-  return hipGetLastError();
 }
 
 }  // namespace
@@ -110,16 +122,17 @@ hipError_t launch(float *base, const Shape &sh, int nt, hipStream_t s) {
 // units * S * stride floats; n (floats per stream, <= stride) must be a multiple
 // of 4 * B * VPT and stride a multiple of 4.  Supported (B, VPT): see the switch
 // below.  nt: bit 0 =
-// non-temporal loads, bit 1 = non-temporal stores.  Returns 0 or a
+// non-temporal loads, bit 1 = non-temporal stores.  lds: bytes of unused
+// dynamic LDS per workgroup (0 .. 160 KiB), to cap the workgroups per CU.  Returns 0 or a
 // hipError_t value (hipErrorInvalidValue for an unsupported shape).
 extern "C" int slowmo_inputs_streambench(void *base, int64_t stride, int32_t units, int32_t S,
                                          int32_t R, int32_t W, int32_t in_place, int64_t n,
                                          int32_t B, int32_t VPT, int32_t nt, int32_t order,
-                                         int32_t remap, int32_t iters, void *stream) {
+                                         int32_t remap, int32_t iters, int32_t lds, void *stream) {
   const int64_t tile = static_cast<int64_t>(4) * B * VPT;
   if (!base || units < 1 || S < 1 || R < 0 || W < 0 || R > S || W > S || R + W == 0 ||
       (!in_place && R + W > S) || n <= 0 || n > stride || stride % 4 || tile <= 0 || n % tile ||
-      iters < 1)
+      iters < 1 || lds < 0 || lds > 160 * 1024)
     return static_cast<int>(hipErrorInvalidValue);
   Shape sh{};
   sh.stride = stride;
@@ -138,29 +151,29 @@ extern "C" int slowmo_inputs_streambench(void *base, int64_t stride, int32_t uni
   hipError_t e = hipErrorInvalidValue;
   const int key = B * 100 + VPT;
   switch (key) {
-    case 6401: e = launch<64, 1>(p, sh, nt, s); break;
-    case 6402: e = launch<64, 2>(p, sh, nt, s); break;
-    case 6404: e = launch<64, 4>(p, sh, nt, s); break;
-    case 6408: e = launch<64, 8>(p, sh, nt, s); break;
-    case 12801: e = launch<128, 1>(p, sh, nt, s); break;
-    case 12804: e = launch<128, 4>(p, sh, nt, s); break;
-    case 25601: e = launch<256, 1>(p, sh, nt, s); break;
-    case 25602: e = launch<256, 2>(p, sh, nt, s); break;
-    case 25604: e = launch<256, 4>(p, sh, nt, s); break;
-    case 25608: e = launch<256, 8>(p, sh, nt, s); break;
-    case 25616: e = launch<256, 16>(p, sh, nt, s); break;
-    case 25632: e = launch<256, 32>(p, sh, nt, s); break;
-    case 51201: e = launch<512, 1>(p, sh, nt, s); break;
-    case 51204: e = launch<512, 4>(p, sh, nt, s); break;
-    case 51208: e = launch<512, 8>(p, sh, nt, s); break;
-    case 51216: e = launch<512, 16>(p, sh, nt, s); break;
-    case 51232: e = launch<512, 32>(p, sh, nt, s); break;
-    case 102401: e = launch<1024, 1>(p, sh, nt, s); break;
-    case 102402: e = launch<1024, 2>(p, sh, nt, s); break;
-    case 102404: e = launch<1024, 4>(p, sh, nt, s); break;
-    case 102408: e = launch<1024, 8>(p, sh, nt, s); break;
-    case 102416: e = launch<1024, 16>(p, sh, nt, s); break;
-    case 102432: e = launch<1024, 32>(p, sh, nt, s); break;
+    case 6401: e = launch<64, 1>(p, sh, nt, lds, s); break;
+    case 6402: e = launch<64, 2>(p, sh, nt, lds, s); break;
+    case 6404: e = launch<64, 4>(p, sh, nt, lds, s); break;
+    case 6408: e = launch<64, 8>(p, sh, nt, lds, s); break;
+    case 12801: e = launch<128, 1>(p, sh, nt, lds, s); break;
+    case 12804: e = launch<128, 4>(p, sh, nt, lds, s); break;
+    case 25601: e = launch<256, 1>(p, sh, nt, lds, s); break;
+    case 25602: e = launch<256, 2>(p, sh, nt, lds, s); break;
+    case 25604: e = launch<256, 4>(p, sh, nt, lds, s); break;
+    case 25608: e = launch<256, 8>(p, sh, nt, lds, s); break;
+    case 25616: e = launch<256, 16>(p, sh, nt, lds, s); break;
+    case 25632: e = launch<256, 32>(p, sh, nt, lds, s); break;
+    case 51201: e = launch<512, 1>(p, sh, nt, lds, s); break;
+    case 51204: e = launch<512, 4>(p, sh, nt, lds, s); break;
+    case 51208: e = launch<512, 8>(p, sh, nt, lds, s); break;
+    case 51216: e = launch<512, 16>(p, sh, nt, lds, s); break;
+    case 51232: e = launch<512, 32>(p, sh, nt, lds, s); break;
+    case 102401: e = launch<1024, 1>(p, sh, nt, lds, s); break;
+    case 102402: e = launch<1024, 2>(p, sh, nt, lds, s); break;
+    case 102404: e = launch<1024, 4>(p, sh, nt, lds, s); break;
+    case 102408: e = launch<1024, 8>(p, sh, nt, lds, s); break;
+    case 102416: e = launch<1024, 16>(p, sh, nt, lds, s); break;
+    case 102432: e = launch<1024, 32>(p, sh, nt, lds, s); break;
     default: break;
   }
   return static_cast<int>(e);

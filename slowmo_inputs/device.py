@@ -41,7 +41,7 @@ def lib() -> C.CDLL:
         _lib.slowmo_inputs_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         _lib.slowmo_inputs_calib_copy.restype = C.c_int
         _lib.slowmo_inputs_streambench.argtypes = [C.c_void_p, C.c_int64] + [C.c_int32] * 5 + \
-            [C.c_int64] + [C.c_int32] * 6 + [C.c_void_p]
+            [C.c_int64] + [C.c_int32] * 7 + [C.c_void_p]
         _lib.slowmo_inputs_streambench.restype = C.c_int
     return _lib
 
@@ -99,7 +99,7 @@ def calib_copy(src, dst) -> None:
 
 def streambench(buf, stride: int, units: int, S: int, R: int, W: int, in_place: bool, n: int,
                 B: int = 64, VPT: int = 1, nt: int = 3, order: int = 0, remap: bool = True,
-                iters: int = 1) -> None:
+                iters: int = 1, lds: int = 0) -> None:
     """One launch of the stream microbenchmark kernel (csrc/streambench.hip) on
     the fp32 CUDA tensor `buf` seen as units x S streams of n floats, `stride`
     floats apart.  nt: 1 = non-temporal loads, 2 = non-temporal stores, 3 = both."""
@@ -107,7 +107,7 @@ def streambench(buf, stride: int, units: int, S: int, R: int, W: int, in_place: 
     assert buf.is_cuda and buf.is_contiguous() and buf.dtype == torch.float32
     assert buf.numel() >= units * S * stride
     rc = lib().slowmo_inputs_streambench(buf.data_ptr(), stride, units, S, R, W, int(in_place), n,
-                                         B, VPT, int(nt), order, int(remap), iters,
+                                         B, VPT, int(nt), order, int(remap), iters, lds,
                                          torch.cuda.current_stream(buf.device).cuda_stream)
     if rc != 0:
         raise RuntimeError(f"slowmo_inputs_streambench failed with hipError {rc}")
