@@ -1,5 +1,6 @@
 """HIP path vs CPU oracle on the same seeded inputs, through the C ABI."""
 import dataclasses
+import os
 import gc
 
 import numpy as np
@@ -889,6 +890,22 @@ def test_resnet18_shaped_every_element():
 
 def test_resnet50_shaped_every_element():
     _every_element(W.resnet50(), 2)         # 32 replicas of 25.6M elements, 24 local steps
+
+
+@pytest.mark.skipif(os.environ.get("SLOWMO_FULL_PARITY") != "1",
+                    reason="several minutes and about 100 GB of host memory: set SLOWMO_FULL_PARITY=1")
+def test_transformer_big_shaped_every_element_one_round():
+    """Every element of the 8 x 209 911 808 replicas, of h, v, x0 and u after one
+    outer iteration (48 Adam steps on bf16 gradients + outer step) against the
+    fp64 oracle.  Not part of the default run (its size); the default run
+    checks this configuration on samples and a dense slab."""
+    w = W.transformer_big()
+    prob = _problem(w, ring=2, grad_layout="padded")
+    opt = PU.make_gpu(w, prob)
+    worst = PU.compare_run(w, prob, opt, None, 1, bitwise_f32=False, device_inputs=True)
+    print(w.name, "every element of", w.d, "x", w.m, "workers, 1 round: worst errors", worst,
+          flush=True)
+    opt.close()
 
 
 # ---- full sizes, sampled elements ------------------------------------------------
