@@ -454,7 +454,7 @@ def test_worker_counts(m):
 
 
 @pytest.mark.parametrize("m,fused", [(8, True), (9, True), (16, False), (33, True), (33, False),
-                                     (150, True)])
+                                     (150, True), (1024, True)])
 def test_worker_counts_on_big_tiles(m, fused):
     """Tensors of exactly one big tile (no rest), one big tile and five
     elements, two big tiles, and one too small for any, at several worker
