@@ -149,6 +149,52 @@ def test_gossip_launch_refused_for_the_second_group_of_workers():
     opt.close()
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_outer_step_on_big_tiles_is_two_launches(fused):
+    """With big tiles the outer step (alone or fused with the last local step)
+    launches one kernel for the whole 65 536-element pieces and one for the
+    rest.  The first refused: nothing has changed and the call can be repeated;
+    the second refused: the call says that memory is partly updated, and the
+    context refuses further steps."""
+    import paper_1910_00643_amd as P
+    B = P.binding
+    w = dataclasses.replace(W.ragged_mini(m=4, policy="reset"), tau=3, rounds=1)
+    idx = np.arange(w.d, dtype=np.int64)
+    first = 3 if fused else 4           # launches before the call: tau - 1 or tau local steps
+    results = []
+    for fail_at in (0, first, first + 1):
+        prob = _problem(w, grad_layout="separate")
+        os.environ["SLOWMO_BIG_TILES"] = "1"
+        try:
+            opt = _make(w, prob, fail_at)
+        finally:
+            os.environ.pop("SLOWMO_BIG_TILES", None)
+        for k in range(w.tau - (1 if fused else 0)):
+            prob.fill_grads(0, k)
+            opt.local_step(prob.grads[0], w.lr)
+        prob.fill_grads(0, w.tau - 1)
+        call = (lambda: opt.local_outer_step(prob.grads[0], w.lr)) if fused else \
+            (lambda: opt.outer_step(w.lr))
+        if fail_at == first:
+            before = _everything(w, prob, opt, idx)
+            with pytest.raises(P.SlowMoError) as e:
+                call()
+            assert e.value.status == B.SLOWMO_ERR_HIP and "partly" not in e.value.message
+            _assert_same(before, _everything(w, prob, opt, idx))
+        if fail_at == first + 1:
+            with pytest.raises(P.SlowMoError) as e:
+                call()
+            assert e.value.status == B.SLOWMO_ERR_HIP and "partly" in e.value.message
+            with pytest.raises(P.SlowMoError) as e:
+                call()
+            assert e.value.status == B.SLOWMO_ERR_STATE and "destroy" in e.value.message
+        else:
+            call()
+            results.append(_everything(w, prob, opt, idx))
+        opt.close()
+    _assert_same(results[0], results[1])
+
+
 def test_import_checks_the_whole_blob_before_it_touches_the_context():
     """A blob with a good header whose later parts are bad (a non-positive
     push-sum weight; counters that do not fit) is refused with the context's
