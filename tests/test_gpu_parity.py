@@ -453,6 +453,26 @@ def test_worker_counts(m):
     opt.close()
 
 
+@pytest.mark.parametrize("base,grad_dtype", [("sgd_nesterov", "f32"), ("sgd_nesterov", "bf16"),
+                                             ("adam", "bf16")])
+def test_big_tiles_when_the_first_step_is_also_the_last(base, grad_dtype):
+    """tau = 1 under "reset": every call is the fused step with the buffers read
+    as zero and not stored."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy="reset", m=5),
+                            tau=1, rounds=4)
+    idx = np.arange(w.d, dtype=np.int64)
+    res = []
+    for big in ("0", "1"):
+        prob = _problem(w, ring=2, grad_layout="padded")
+        opt = _with_env("SLOWMO_BIG_TILES", big, lambda: PU.make_gpu(w, prob))
+        PU.compare_run(w, prob, opt, idx, w.rounds, bitwise_f32=(base == "sgd_nesterov"),
+                       fused_last=True)
+        res.append(PU.gpu_state(w, prob, opt, idx))
+        opt.close()
+    for key in ("x", "x0", "u"):
+        assert np.array_equal(res[0][key], res[1][key]), key
+
+
 @pytest.mark.parametrize("m,fused", [(8, True), (9, True), (16, False), (33, True), (33, False),
                                      (150, True), (1024, True)])
 def test_worker_counts_on_big_tiles(m, fused):
