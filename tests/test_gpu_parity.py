@@ -453,12 +453,14 @@ def test_worker_counts(m):
     opt.close()
 
 
-@pytest.mark.parametrize("base,grad_dtype", [("sgd_nesterov", "f32"), ("sgd_nesterov", "bf16"),
-                                             ("adam", "bf16")])
-def test_big_tiles_when_the_first_step_is_also_the_last(base, grad_dtype):
-    """tau = 1 under "reset": every call is the fused step with the buffers read
-    as zero and not stored."""
-    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy="reset", m=5),
+@pytest.mark.parametrize("base,grad_dtype,policy", [
+    ("sgd_nesterov", "f32", "reset"), ("sgd_nesterov", "bf16", "reset"), ("adam", "bf16", "reset"),
+    ("adam", "f32", "maintain"), ("sgd_nesterov", "f32", "maintain")])
+def test_big_tiles_when_the_first_step_is_also_the_last(base, grad_dtype, policy):
+    """tau = 1: every call is the fused step; under "reset" always with the
+    buffers read as zero and not stored, under "maintain" the very first one
+    reads them as zero."""
+    w = dataclasses.replace(W.ragged_mini(base=base, grad_dtype=grad_dtype, policy=policy, m=5),
                             tau=1, rounds=4)
     idx = np.arange(w.d, dtype=np.int64)
     res = []
@@ -469,7 +471,7 @@ def test_big_tiles_when_the_first_step_is_also_the_last(base, grad_dtype):
                        fused_last=True)
         res.append(PU.gpu_state(w, prob, opt, idx))
         opt.close()
-    for key in ("x", "x0", "u"):
+    for key in ("x", "x0", "u") + (("h",) if policy == "maintain" else ()):
         assert np.array_equal(res[0][key], res[1][key]), key
 
 
